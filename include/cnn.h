@@ -1,0 +1,142 @@
+/*
+ * libcnn -- one GPU's share of a synchronous-SGD training step for CNNs/DNNs,
+ * native to AMD MI355X (gfx950): direct convolution forward, backward-data and
+ * backward-weights (with the weight-gradient sum over the per-GPU minibatch),
+ * the fully-connected GEMMs and the SGD weight update, all in fp32.
+ * The operations are those of arxiv 1602.06709, Section 2.1.
+ *
+ * General rules for every entry point
+ *   - Returns an int status: CNN_OK (0) or a negative CNN_E* code.  Never throws,
+ *     aborts or prints.  cnn_strerror() maps a code to a static string and
+ *     cnn_last_error() returns the last HIP error text recorded in the context.
+ *   - Every tensor pointer is DEVICE memory owned by the caller, at least 16-byte
+ *     aligned, dense row-major fp32.  The library allocates and frees no device
+ *     memory, keeps no pointer after a call returns, and never synchronises:
+ *     work is enqueued on the context's stream (borrowed from the caller).
+ *   - Scratch memory is a caller-owned device buffer attached with
+ *     cnn_set_workspace(); cnn_workspace_bytes() says how much a call needs.
+ *     Calls sharing one context must not overlap in time (they share the scratch).
+ *   - Outputs are overwritten (the paper's "+=" starts from zero).  Inputs and
+ *     outputs must not alias, except w and v in cnn_sgd_update (in place).
+ *   - Arguments are validated before anything is launched: a failed call leaves
+ *     device memory untouched.
+ *
+ * Layouts (canonical on this boundary)
+ *   activations and their gradients:   [N][C][H][W]   (minibatch, feature map, row, col)
+ *   weights and their gradients:       [K][C][R][S]   (output feature, input feature, kernel row, col);
+ *       the paper writes wts[ifm][ofm][kh][kw] -- the same tensor with its first two axes swapped.
+ *   fully connected:                   x[N][I], w[O][I], y[N][O]
+ *   P = floor((H + 2*pad - R)/stride) + 1 output rows, Q likewise columns.
+ *   The paper's channel-blocked layouts (Section 2.3) are available through
+ *   cnn_pack_* / cnn_unpack_* for callers that hold data in that form.
+ */
+#ifndef CNN_H
+#define CNN_H
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+enum {
+    CNN_OK = 0,
+    CNN_EINVAL = -1,       /* null pointer, non-positive dimension, stride < 1, pad < 0, empty output, misaligned pointer */
+    CNN_EUNSUPPORTED = -2, /* shape outside what any kernel covers (e.g. a tensor of 2^31 or more elements)               */
+    CNN_EWORKSPACE = -3,   /* attached workspace smaller than cnn_workspace_bytes() for this call                        */
+    CNN_EHIP = -4          /* a HIP call failed; text via cnn_last_error()                                              */
+};
+
+/* op codes for cnn_workspace_bytes() */
+enum {
+    CNN_OP_CONV_FWD = 0,
+    CNN_OP_CONV_BWD_DATA = 1,
+    CNN_OP_CONV_BWD_WEIGHT = 2,
+    CNN_OP_FC_FWD = 3,     /* N, I = C, O = K; H = W = R = S = 1 */
+    CNN_OP_FC_BWD = 4
+};
+
+/* options for cnn_set_option() */
+enum {
+    CNN_OPT_FORCE_DIRECT = 0 /* value != 0: route conv / fc calls to the plain one-thread-per-output kernels
+                                (kept as the any-shape fallback); default 0 */
+};
+
+typedef struct cnn_ctx cnn_ctx; /* opaque; owns nothing on the device */
+
+/* Context.  hip_stream is a hipStream_t passed as void* (NULL = the default stream); it is borrowed. */
+int cnn_create(cnn_ctx** out, void* hip_stream);
+int cnn_destroy(cnn_ctx* ctx);
+int cnn_set_stream(cnn_ctx* ctx, void* hip_stream);
+int cnn_set_workspace(cnn_ctx* ctx, void* dev_ptr, size_t bytes); /* caller-owned; may be NULL/0 to detach */
+int cnn_set_option(cnn_ctx* ctx, int option, int value);
+/* Scratch bytes the given call needs (0 if none).  For FC ops pass C = I, K = O, H = W = R = S = 1, stride 1, pad 0. */
+size_t cnn_workspace_bytes(int op, int N, int C, int H, int W, int K, int R, int S, int stride, int pad);
+const char* cnn_strerror(int status);
+const char* cnn_last_error(const cnn_ctx* ctx);
+
+/* ---- Section 2.1, Algorithm 1 "Forward Propagation":
+ *   y[n][k][p][q] = sum_{c,r,s} x[n][c][p*stride + r - pad][q*stride + s - pad] * w[k][c][r][s]
+ *   (cross-correlation; positions outside the input contribute 0).
+ *   x: N*C*H*W in, w: K*C*R*S in, y: N*K*P*Q out. */
+int cnn_conv_fwd(cnn_ctx* ctx, int N, int C, int H, int W, int K, int R, int S, int stride, int pad,
+                 const float* x, const float* w, float* y);
+
+/* ---- Section 2.1 "Backpropagation":
+ *   dx[n][c][p*stride + r - pad][q*stride + s - pad] += dy[n][k][p][q] * w[k][c][r][s]   (from dx = 0)
+ *   dy: N*K*P*Q in, w in, dx: N*C*H*W out (input positions no tap reaches get 0). */
+int cnn_conv_bwd_data(cnn_ctx* ctx, int N, int C, int H, int W, int K, int R, int S, int stride, int pad,
+                      const float* dy, const float* w, float* dx);
+
+/* ---- Section 2.1 "Weight-gradient Update", summed over the per-GPU minibatch (no 1/N):
+ *   dw[k][c][r][s] = sum_{n,p,q} x[n][c][p*stride + r - pad][q*stride + s - pad] * dy[n][k][p][q]
+ *   x, dy in; dw: K*C*R*S out.  Needs workspace (partial sums of the split contraction,
+ *   reduced in a fixed order: results are bitwise repeatable). */
+int cnn_conv_bwd_weight(cnn_ctx* ctx, int N, int C, int H, int W, int K, int R, int S, int stride, int pad,
+                        const float* x, const float* dy, float* dw);
+
+/* ---- Section 2.1: the fully-connected layer is the same loop nest with k_h = k_w = out_h = out_w = 1.
+ *   y[n][o] = sum_i x[n][i] * w[o][i] */
+int cnn_fc_fwd(cnn_ctx* ctx, int N, int I, int O, const float* x, const float* w, float* y);
+/*   dx[n][i] = sum_o dy[n][o] * w[o][i]      (skipped when dx == NULL; then w may be NULL)
+ *   dw[o][i] = sum_n dy[n][o] * x[n][i]      (skipped when dw == NULL; then x may be NULL) */
+int cnn_fc_bwd(cnn_ctx* ctx, int N, int I, int O, const float* x, const float* w, const float* dy,
+               float* dx, float* dw);
+
+/* ---- SGD step (the paper's "vanilla SGD", Sections 1 and 3.4; no weight decay, no Nesterov):
+ *   v <- momentum * v + dw ;  w <- w - lr * v         (v == NULL: w <- w - lr * dw, momentum ignored)
+ *   n elements; w and v updated in place.  One launch over the whole (flat) parameter arena. */
+int cnn_sgd_update(cnn_ctx* ctx, size_t n, float* w, const float* dw, float* v, float lr, float momentum);
+
+/* ---- Section 2.3 data layouts; pure permutations (bit-exact), lanes past C (or K) are written as 0.
+ *   activations:        [N][C][H][W]  <->  [N][ceil(C/SW)][H][W][SW]
+ *   weights (transpose == 0): [K][C][R][S] <-> [C][ceil(K/SW)][R][S][SW]   (paper: IFM x OFM/SW x KH x KW x SW)
+ *   weights (transpose != 0): [K][C][R][S] <-> [K][ceil(C/SW)][R][S][SW]   (paper: "transpose-weights") */
+size_t cnn_packed_act_elems(int N, int C, int H, int W, int SW);
+size_t cnn_packed_wt_elems(int K, int C, int R, int S, int SW, int transpose);
+int cnn_pack_act(cnn_ctx* ctx, int N, int C, int H, int W, int SW, const float* nchw, float* packed);
+int cnn_unpack_act(cnn_ctx* ctx, int N, int C, int H, int W, int SW, const float* packed, float* nchw);
+int cnn_pack_wt(cnn_ctx* ctx, int K, int C, int R, int S, int SW, int transpose, const float* kcrs, float* packed);
+int cnn_unpack_wt(cnn_ctx* ctx, int K, int C, int R, int S, int SW, int transpose, const float* packed, float* kcrs);
+
+/* ---- Glue between layers.  The paper does not describe these; the network workloads need them.
+ *   ReLU: a = max(z, 0); dz = da where z > 0 else 0 (uses the forward INPUT z).
+ *   2x2 stride-2 max-pool on [planes][H][W] (H, W even): arg (0..3, one byte) = first maximum in
+ *   row-major window order; backward routes dy to that position, zero elsewhere.
+ *   sigmoid: a = 1/(1+exp(-z)); dz = da * a * (1 - a) (uses the forward OUTPUT a).
+ *   softmax cross-entropy: loss_per_sample[n] = -log softmax(z[n])[label[n]];
+ *   dz[n][o] = (softmax(z[n])[o] - [o == label[n]]) / N.  dz may be NULL. */
+int cnn_relu_fwd(cnn_ctx* ctx, size_t n, const float* z, float* a);
+int cnn_relu_bwd(cnn_ctx* ctx, size_t n, const float* z, const float* da, float* dz);
+int cnn_maxpool2_fwd(cnn_ctx* ctx, size_t planes, int H, int W, const float* x, float* y, uint8_t* arg);
+int cnn_maxpool2_bwd(cnn_ctx* ctx, size_t planes, int H, int W, const float* dy, const uint8_t* arg, float* dx);
+int cnn_sigmoid_fwd(cnn_ctx* ctx, size_t n, const float* z, float* a);
+int cnn_sigmoid_bwd(cnn_ctx* ctx, size_t n, const float* a, const float* da, float* dz);
+int cnn_softmax_xent(cnn_ctx* ctx, int N, int O, const float* z, const int32_t* label,
+                     float* loss_per_sample, float* dz);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* CNN_H */

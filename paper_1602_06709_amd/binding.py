@@ -1,0 +1,281 @@
+"""Thin ctypes binding over libcnn.so (declared in include/cnn.h).
+
+Argument marshalling only: every function takes torch CUDA tensors (fp32, contiguous), passes their
+device pointers to the C ABI and returns the output tensor.  torch is used for device memory and the
+stream, nothing else; there is no CPU or torch fallback -- a missing library is an error.
+"""
+import ctypes as C
+import os
+
+import torch
+
+from . import build as _build
+
+_LIB = None
+
+OP_CONV_FWD, OP_CONV_BWD_DATA, OP_CONV_BWD_WEIGHT, OP_FC_FWD, OP_FC_BWD = range(5)
+OPT_FORCE_DIRECT = 0
+
+_vp, _i, _sz, _f = C.c_void_p, C.c_int, C.c_size_t, C.c_float
+_CONV = [_vp] + [_i] * 9 + [_vp] * 3
+
+SIGNATURES = {
+    "cnn_create": (_i, [C.POINTER(_vp), _vp]),
+    "cnn_destroy": (_i, [_vp]),
+    "cnn_set_stream": (_i, [_vp, _vp]),
+    "cnn_set_workspace": (_i, [_vp, _vp, _sz]),
+    "cnn_set_option": (_i, [_vp, _i, _i]),
+    "cnn_workspace_bytes": (_sz, [_i] * 10),
+    "cnn_strerror": (C.c_char_p, [_i]),
+    "cnn_last_error": (C.c_char_p, [_vp]),
+    "cnn_conv_fwd": (_i, _CONV),
+    "cnn_conv_bwd_data": (_i, _CONV),
+    "cnn_conv_bwd_weight": (_i, _CONV),
+    "cnn_fc_fwd": (_i, [_vp, _i, _i, _i, _vp, _vp, _vp]),
+    "cnn_fc_bwd": (_i, [_vp, _i, _i, _i, _vp, _vp, _vp, _vp, _vp]),
+    "cnn_sgd_update": (_i, [_vp, _sz, _vp, _vp, _vp, _f, _f]),
+    "cnn_packed_act_elems": (_sz, [_i] * 5),
+    "cnn_packed_wt_elems": (_sz, [_i] * 6),
+    "cnn_pack_act": (_i, [_vp] + [_i] * 5 + [_vp] * 2),
+    "cnn_unpack_act": (_i, [_vp] + [_i] * 5 + [_vp] * 2),
+    "cnn_pack_wt": (_i, [_vp] + [_i] * 6 + [_vp] * 2),
+    "cnn_unpack_wt": (_i, [_vp] + [_i] * 6 + [_vp] * 2),
+    "cnn_relu_fwd": (_i, [_vp, _sz, _vp, _vp]),
+    "cnn_relu_bwd": (_i, [_vp, _sz, _vp, _vp, _vp]),
+    "cnn_maxpool2_fwd": (_i, [_vp, _sz, _i, _i, _vp, _vp, _vp]),
+    "cnn_maxpool2_bwd": (_i, [_vp, _sz, _i, _i, _vp, _vp, _vp]),
+    "cnn_sigmoid_fwd": (_i, [_vp, _sz, _vp, _vp]),
+    "cnn_sigmoid_bwd": (_i, [_vp, _sz, _vp, _vp, _vp]),
+    "cnn_softmax_xent": (_i, [_vp, _i, _i, _vp, _vp, _vp, _vp]),
+}
+
+
+class CnnError(RuntimeError):
+    pass
+
+
+def library_path():
+    return _build.LIB
+
+
+def ensure_built():
+    """Build the library only if nothing is built (tests, smoke and bench load what is there)."""
+    if not os.path.exists(_build.LIB):
+        _build.build()
+    return _build.LIB
+
+
+def lib():
+    global _LIB
+    if _LIB is None:
+        path = library_path()
+        if not os.path.exists(path):
+            raise CnnError(f"{path} is missing: build it with `python -m paper_1602_06709_amd.build` "
+                           "(there is no CPU fallback)")
+        L = C.CDLL(path)
+        for name, (res, args) in SIGNATURES.items():
+            fn = getattr(L, name)
+            fn.restype, fn.argtypes = res, args
+        _LIB = L
+    return _LIB
+
+
+def _check(status, ctx=None):
+    if status != 0:
+        msg = lib().cnn_strerror(status).decode()
+        if ctx is not None and status == -4:
+            msg += ": " + lib().cnn_last_error(ctx).decode()
+        raise CnnError(f"libcnn status {status}: {msg}")
+
+
+def _t(t, dtype=torch.float32):
+    if not (isinstance(t, torch.Tensor) and t.is_cuda and t.dtype == dtype and t.is_contiguous()):
+        raise CnnError("expected a contiguous CUDA tensor of dtype %s" % dtype)
+    return t.data_ptr()
+
+
+def out_dim(n, k, stride, pad):
+    return (n + 2 * pad - k) // stride + 1
+
+
+class Context:
+    """A cnn_ctx bound to torch's current stream, with a torch-owned workspace that grows on demand."""
+
+    def __init__(self, stream=None):
+        self._h = _vp()
+        s = stream if stream is not None else torch.cuda.current_stream()
+        self.stream = s
+        _check(lib().cnn_create(C.byref(self._h), _vp(s.cuda_stream)))
+        self._ws = None
+
+    def close(self):
+        if self._h:
+            lib().cnn_destroy(self._h)
+            self._h = _vp()
+
+    def __del__(self):
+        try:
+            self.close()
+        except Exception:
+            pass
+
+    @property
+    def handle(self):
+        return self._h
+
+    def set_option(self, option, value):
+        _check(lib().cnn_set_option(self._h, option, int(value)))
+
+    def reserve(self, nbytes):
+        """Make the attached workspace at least nbytes (allocation happens here, never inside the library)."""
+        if nbytes and (self._ws is None or self._ws.numel() < nbytes):
+            self._ws = torch.empty(int(nbytes), dtype=torch.uint8, device="cuda")
+            _check(lib().cnn_set_workspace(self._h, _vp(self._ws.data_ptr()), nbytes))
+
+    def reserve_for(self, op, N, Cc, H, W, K, R, S, stride, pad):
+        self.reserve(lib().cnn_workspace_bytes(op, N, Cc, H, W, K, R, S, stride, pad))
+
+
+# ---------------------------------------------------------------- contractions
+def cnn_conv_fwd(ctx, x, w, stride=1, pad=0, out=None):
+    N, Cc, H, W = x.shape
+    K, C2, R, S = w.shape
+    assert Cc == C2
+    y = out if out is not None else torch.empty((N, K, out_dim(H, R, stride, pad), out_dim(W, S, stride, pad)),
+                                                dtype=torch.float32, device=x.device)
+    _check(lib().cnn_conv_fwd(ctx.handle, N, Cc, H, W, K, R, S, stride, pad, _t(x), _t(w), _t(y)), ctx.handle)
+    return y
+
+
+def cnn_conv_bwd_data(ctx, dy, w, H, W, stride=1, pad=0, out=None):
+    K, Cc, R, S = w.shape
+    N = dy.shape[0]
+    assert tuple(dy.shape) == (N, K, out_dim(H, R, stride, pad), out_dim(W, S, stride, pad))
+    ctx.reserve_for(OP_CONV_BWD_DATA, N, Cc, H, W, K, R, S, stride, pad)
+    dx = out if out is not None else torch.empty((N, Cc, H, W), dtype=torch.float32, device=dy.device)
+    _check(lib().cnn_conv_bwd_data(ctx.handle, N, Cc, H, W, K, R, S, stride, pad, _t(dy), _t(w), _t(dx)), ctx.handle)
+    return dx
+
+
+def cnn_conv_bwd_weight(ctx, x, dy, R, S, stride=1, pad=0, out=None):
+    N, Cc, H, W = x.shape
+    K = dy.shape[1]
+    assert tuple(dy.shape) == (N, K, out_dim(H, R, stride, pad), out_dim(W, S, stride, pad))
+    ctx.reserve_for(OP_CONV_BWD_WEIGHT, N, Cc, H, W, K, R, S, stride, pad)
+    dw = out if out is not None else torch.empty((K, Cc, R, S), dtype=torch.float32, device=x.device)
+    _check(lib().cnn_conv_bwd_weight(ctx.handle, N, Cc, H, W, K, R, S, stride, pad, _t(x), _t(dy), _t(dw)), ctx.handle)
+    return dw
+
+
+def cnn_fc_fwd(ctx, x, w, out=None):
+    N, I = x.shape
+    O, I2 = w.shape
+    assert I == I2
+    ctx.reserve_for(OP_FC_FWD, N, I, 1, 1, O, 1, 1, 1, 0)
+    y = out if out is not None else torch.empty((N, O), dtype=torch.float32, device=x.device)
+    _check(lib().cnn_fc_fwd(ctx.handle, N, I, O, _t(x), _t(w), _t(y)), ctx.handle)
+    return y
+
+
+def cnn_fc_bwd(ctx, x, w, dy, need_dx=True, need_dw=True, dx_out=None, dw_out=None):
+    N, O = dy.shape
+    I = w.shape[1] if w is not None else x.shape[1]
+    ctx.reserve_for(OP_FC_BWD, N, I, 1, 1, O, 1, 1, 1, 0)
+    dx = dw = None
+    if need_dx:
+        dx = dx_out if dx_out is not None else torch.empty((N, I), dtype=torch.float32, device=dy.device)
+    if need_dw:
+        dw = dw_out if dw_out is not None else torch.empty((O, I), dtype=torch.float32, device=dy.device)
+    _check(lib().cnn_fc_bwd(ctx.handle, N, I, O, _t(x) if x is not None else None, _t(w) if w is not None else None,
+                            _t(dy), _t(dx) if dx is not None else None, _t(dw) if dw is not None else None),
+           ctx.handle)
+    return dx, dw
+
+
+def cnn_sgd_update(ctx, w, dw, v=None, lr=0.01, momentum=0.0):
+    """In place on w (and v).  w, dw, v are flat views of equal length."""
+    n = w.numel()
+    assert dw.numel() == n and (v is None or v.numel() == n)
+    _check(lib().cnn_sgd_update(ctx.handle, n, _t(w), _t(dw), _t(v) if v is not None else None, lr, momentum),
+           ctx.handle)
+    return w
+
+
+# ---------------------------------------------------------------- layouts (Section 2.3)
+def cnn_pack_act(ctx, x, sw):
+    N, Cc, H, W = x.shape
+    out = torch.empty((N, (Cc + sw - 1) // sw, H, W, sw), dtype=torch.float32, device=x.device)
+    assert out.numel() == lib().cnn_packed_act_elems(N, Cc, H, W, sw)
+    _check(lib().cnn_pack_act(ctx.handle, N, Cc, H, W, sw, _t(x), _t(out)), ctx.handle)
+    return out
+
+
+def cnn_unpack_act(ctx, packed, Cc):
+    N, CB, H, W, sw = packed.shape
+    out = torch.empty((N, Cc, H, W), dtype=torch.float32, device=packed.device)
+    _check(lib().cnn_unpack_act(ctx.handle, N, Cc, H, W, sw, _t(packed), _t(out)), ctx.handle)
+    return out
+
+
+def cnn_pack_wt(ctx, w, sw, transpose=False):
+    K, Cc, R, S = w.shape
+    shape = (K, (Cc + sw - 1) // sw, R, S, sw) if transpose else (Cc, (K + sw - 1) // sw, R, S, sw)
+    out = torch.empty(shape, dtype=torch.float32, device=w.device)
+    assert out.numel() == lib().cnn_packed_wt_elems(K, Cc, R, S, sw, int(transpose))
+    _check(lib().cnn_pack_wt(ctx.handle, K, Cc, R, S, sw, int(transpose), _t(w), _t(out)), ctx.handle)
+    return out
+
+
+def cnn_unpack_wt(ctx, packed, K, Cc, transpose=False):
+    _, _, R, S, sw = packed.shape
+    out = torch.empty((K, Cc, R, S), dtype=torch.float32, device=packed.device)
+    _check(lib().cnn_unpack_wt(ctx.handle, K, Cc, R, S, sw, int(transpose), _t(packed), _t(out)), ctx.handle)
+    return out
+
+
+# ---------------------------------------------------------------- glue
+def cnn_relu_fwd(ctx, z, out=None):
+    a = out if out is not None else torch.empty_like(z)
+    _check(lib().cnn_relu_fwd(ctx.handle, z.numel(), _t(z), _t(a)), ctx.handle)
+    return a
+
+
+def cnn_relu_bwd(ctx, z, da, out=None):
+    dz = out if out is not None else torch.empty_like(z)
+    _check(lib().cnn_relu_bwd(ctx.handle, z.numel(), _t(z), _t(da), _t(dz)), ctx.handle)
+    return dz
+
+
+def cnn_maxpool2_fwd(ctx, x, out=None, arg_out=None):
+    N, Cc, H, W = x.shape
+    y = out if out is not None else torch.empty((N, Cc, H // 2, W // 2), dtype=torch.float32, device=x.device)
+    arg = arg_out if arg_out is not None else torch.empty((N, Cc, H // 2, W // 2), dtype=torch.uint8, device=x.device)
+    _check(lib().cnn_maxpool2_fwd(ctx.handle, N * Cc, H, W, _t(x), _t(y), _t(arg, torch.uint8)), ctx.handle)
+    return y, arg
+
+
+def cnn_maxpool2_bwd(ctx, dy, arg, H, W, out=None):
+    N, Cc = dy.shape[:2]
+    dx = out if out is not None else torch.empty((N, Cc, H, W), dtype=torch.float32, device=dy.device)
+    _check(lib().cnn_maxpool2_bwd(ctx.handle, N * Cc, H, W, _t(dy), _t(arg, torch.uint8), _t(dx)), ctx.handle)
+    return dx
+
+
+def cnn_sigmoid_fwd(ctx, z, out=None):
+    a = out if out is not None else torch.empty_like(z)
+    _check(lib().cnn_sigmoid_fwd(ctx.handle, z.numel(), _t(z), _t(a)), ctx.handle)
+    return a
+
+
+def cnn_sigmoid_bwd(ctx, a, da, out=None):
+    dz = out if out is not None else torch.empty_like(a)
+    _check(lib().cnn_sigmoid_bwd(ctx.handle, a.numel(), _t(a), _t(da), _t(dz)), ctx.handle)
+    return dz
+
+
+def cnn_softmax_xent(ctx, z, label, loss_out=None, dz_out=None):
+    N, O = z.shape
+    loss = loss_out if loss_out is not None else torch.empty((N,), dtype=torch.float32, device=z.device)
+    dz = dz_out if dz_out is not None else torch.empty_like(z)
+    _check(lib().cnn_softmax_xent(ctx.handle, N, O, _t(z), _t(label, torch.int32), _t(loss), _t(dz)), ctx.handle)
+    return loss, dz

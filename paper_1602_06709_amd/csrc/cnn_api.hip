@@ -1,0 +1,174 @@
+// C-ABI entry points: argument validation, kernel selection, error reporting.
+#include <new>
+#include <stdio.h>
+#include <string.h>
+
+#include "common.h"
+
+namespace cnn {
+
+int hip_check(cnn_ctx* ctx, hipError_t e, const char* what) {
+    if (e == hipSuccess) return CNN_OK;
+    if (ctx) snprintf(ctx->err, sizeof(ctx->err), "%s: %s", what, hipGetErrorString(e));
+    return CNN_EHIP;
+}
+int launch_check(cnn_ctx* ctx, const char* what) { return hip_check(ctx, hipGetLastError(), what); }
+
+}  // namespace cnn
+
+namespace {
+
+bool aligned16(const void* p) { return (reinterpret_cast<uintptr_t>(p) & 15u) == 0; }
+
+// Fills the shape and checks the paper's layer parameters (Section 2.1: minibatch, ifm, ofm, out_h, out_w,
+// k_h, k_w, stride).  Tensors are indexed with 32-bit element offsets inside the kernels.
+int make_shape(int N, int C, int H, int W, int K, int R, int S, int stride, int pad, ConvShape* s) {
+    if (N <= 0 || C <= 0 || H <= 0 || W <= 0 || K <= 0 || R <= 0 || S <= 0 || stride < 1 || pad < 0) return CNN_EINVAL;
+    const int P = cnn::out_dim(H, R, stride, pad), Q = cnn::out_dim(W, S, stride, pad);
+    if (P <= 0 || Q <= 0) return CNN_EINVAL;
+    const double lim = 2147483647.0;
+    if ((double)N * C * H * W > lim || (double)N * K * P * Q > lim || (double)K * C * R * S > lim) return CNN_EUNSUPPORTED;
+    *s = ConvShape{N, C, H, W, K, R, S, stride, pad, P, Q};
+    return CNN_OK;
+}
+
+}  // namespace
+
+extern "C" {
+
+int cnn_create(cnn_ctx** out, void* hip_stream) {
+    if (!out) return CNN_EINVAL;
+    cnn_ctx* c = new (std::nothrow) cnn_ctx;
+    if (!c) return CNN_EINVAL;
+    c->stream = reinterpret_cast<hipStream_t>(hip_stream);
+    c->ws = nullptr;
+    c->ws_bytes = 0;
+    c->force_direct = 0;
+    c->err[0] = 0;
+    *out = c;
+    return CNN_OK;
+}
+int cnn_destroy(cnn_ctx* ctx) {
+    if (!ctx) return CNN_EINVAL;
+    delete ctx;
+    return CNN_OK;
+}
+int cnn_set_stream(cnn_ctx* ctx, void* hip_stream) {
+    if (!ctx) return CNN_EINVAL;
+    ctx->stream = reinterpret_cast<hipStream_t>(hip_stream);
+    return CNN_OK;
+}
+int cnn_set_workspace(cnn_ctx* ctx, void* dev_ptr, size_t bytes) {
+    if (!ctx || (bytes && !dev_ptr) || !aligned16(dev_ptr)) return CNN_EINVAL;
+    ctx->ws = dev_ptr;
+    ctx->ws_bytes = dev_ptr ? bytes : 0;
+    return CNN_OK;
+}
+int cnn_set_option(cnn_ctx* ctx, int option, int value) {
+    if (!ctx) return CNN_EINVAL;
+    if (option == CNN_OPT_FORCE_DIRECT) { ctx->force_direct = value != 0; return CNN_OK; }
+    return CNN_EINVAL;
+}
+const char* cnn_strerror(int status) {
+    switch (status) {
+        case CNN_OK: return "ok";
+        case CNN_EINVAL: return "invalid argument";
+        case CNN_EUNSUPPORTED: return "unsupported shape";
+        case CNN_EWORKSPACE: return "workspace too small";
+        case CNN_EHIP: return "HIP error";
+        default: return "unknown status";
+    }
+}
+const char* cnn_last_error(const cnn_ctx* ctx) { return ctx ? ctx->err : ""; }
+
+size_t cnn_workspace_bytes(int op, int N, int C, int H, int W, int K, int R, int S, int stride, int pad) {
+    ConvShape s;
+    if (make_shape(N, C, H, W, K, R, S, stride, pad, &s) != CNN_OK) return 0;
+    switch (op) {
+        case CNN_OP_CONV_BWD_DATA: return cnn::mfma_conv_bwd_data_ws(s);
+        case CNN_OP_CONV_BWD_WEIGHT: return cnn::mfma_conv_bwd_weight_ws(s);
+        case CNN_OP_FC_FWD: return cnn::mfma_gemm_ws(N, K, C);
+        case CNN_OP_FC_BWD: {
+            const size_t a = cnn::mfma_gemm_ws(N, C, K), b = cnn::mfma_gemm_ws(K, C, N);
+            return a > b ? a : b;
+        }
+        default: return 0;
+    }
+}
+
+int cnn_conv_fwd(cnn_ctx* ctx, int N, int C, int H, int W, int K, int R, int S, int stride, int pad,
+                 const float* x, const float* w, float* y) {
+    if (!ctx || !x || !w || !y || !aligned16(x) || !aligned16(w) || !aligned16(y)) return CNN_EINVAL;
+    ConvShape s;
+    int st = make_shape(N, C, H, W, K, R, S, stride, pad, &s);
+    if (st != CNN_OK) return st;
+    if (!ctx->force_direct) {
+        st = cnn::mfma_conv_fwd(ctx, s, x, w, y);
+        if (st != CNN_EUNSUPPORTED) return st;
+    }
+    return cnn::direct_conv_fwd(ctx, s, x, w, y);
+}
+
+int cnn_conv_bwd_data(cnn_ctx* ctx, int N, int C, int H, int W, int K, int R, int S, int stride, int pad,
+                      const float* dy, const float* w, float* dx) {
+    if (!ctx || !dy || !w || !dx || !aligned16(dy) || !aligned16(w) || !aligned16(dx)) return CNN_EINVAL;
+    ConvShape s;
+    int st = make_shape(N, C, H, W, K, R, S, stride, pad, &s);
+    if (st != CNN_OK) return st;
+    if (!ctx->force_direct) {
+        st = cnn::mfma_conv_bwd_data(ctx, s, dy, w, dx);
+        if (st != CNN_EUNSUPPORTED) return st;
+    }
+    return cnn::direct_conv_bwd_data(ctx, s, dy, w, dx);
+}
+
+int cnn_conv_bwd_weight(cnn_ctx* ctx, int N, int C, int H, int W, int K, int R, int S, int stride, int pad,
+                        const float* x, const float* dy, float* dw) {
+    if (!ctx || !x || !dy || !dw || !aligned16(x) || !aligned16(dy) || !aligned16(dw)) return CNN_EINVAL;
+    ConvShape s;
+    int st = make_shape(N, C, H, W, K, R, S, stride, pad, &s);
+    if (st != CNN_OK) return st;
+    if (!ctx->force_direct) {
+        st = cnn::mfma_conv_bwd_weight(ctx, s, x, dy, dw);
+        if (st != CNN_EUNSUPPORTED) return st;
+    }
+    return cnn::direct_conv_bwd_weight(ctx, s, x, dy, dw);
+}
+
+// Fully-connected layers: the conv loop nest with k_h = k_w = out_h = out_w = 1 (Section 2.1), i.e. GEMMs.
+int cnn_fc_fwd(cnn_ctx* ctx, int N, int I, int O, const float* x, const float* w, float* y) {
+    if (!ctx || !x || !w || !y || !aligned16(x) || !aligned16(w) || !aligned16(y)) return CNN_EINVAL;
+    ConvShape s;
+    int st = make_shape(N, I, 1, 1, O, 1, 1, 1, 0, &s);
+    if (st != CNN_OK) return st;
+    if (!ctx->force_direct) {
+        st = cnn::mfma_gemm(ctx, N, O, I, x, 0, w, 0, y);   // y[n][o] = sum_i x[n][i] w[o][i]
+        if (st != CNN_EUNSUPPORTED) return st;
+    }
+    return cnn::direct_conv_fwd(ctx, s, x, w, y);
+}
+
+int cnn_fc_bwd(cnn_ctx* ctx, int N, int I, int O, const float* x, const float* w, const float* dy, float* dx,
+               float* dw) {
+    if (!ctx || !dy || !aligned16(dy)) return CNN_EINVAL;
+    if (dx && (!w || !aligned16(w) || !aligned16(dx))) return CNN_EINVAL;
+    if (dw && (!x || !aligned16(x) || !aligned16(dw))) return CNN_EINVAL;
+    ConvShape s;
+    int st = make_shape(N, I, 1, 1, O, 1, 1, 1, 0, &s);
+    if (st != CNN_OK) return st;
+    if (dw) {   // weight gradient first, as the paper orders it (Section 3.1)
+        st = CNN_EUNSUPPORTED;
+        if (!ctx->force_direct) st = cnn::mfma_gemm(ctx, O, I, N, dy, 1, x, 1, dw);   // dw[o][i] = sum_n dy[n][o] x[n][i]
+        if (st == CNN_EUNSUPPORTED) st = cnn::direct_conv_bwd_weight(ctx, s, x, dy, dw);
+        if (st != CNN_OK) return st;
+    }
+    if (dx) {
+        st = CNN_EUNSUPPORTED;
+        if (!ctx->force_direct) st = cnn::mfma_gemm(ctx, N, I, O, dy, 0, w, 1, dx);   // dx[n][i] = sum_o dy[n][o] w[o][i]
+        if (st == CNN_EUNSUPPORTED) st = cnn::direct_conv_bwd_data(ctx, s, dy, w, dx);
+        if (st != CNN_OK) return st;
+    }
+    return CNN_OK;
+}
+
+}  // extern "C"

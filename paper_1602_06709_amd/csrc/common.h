@@ -1,0 +1,49 @@
+// Internal declarations shared by the translation units of libcnn (not part of the C ABI).
+#pragma once
+#include <hip/hip_runtime.h>
+#include <stddef.h>
+#include <stdint.h>
+
+#include "../../include/cnn.h"
+
+struct cnn_ctx {
+    hipStream_t stream;
+    void* ws;
+    size_t ws_bytes;
+    int force_direct;
+    char err[256];
+};
+
+struct ConvShape {
+    int N, C, H, W, K, R, S, stride, pad, P, Q;
+};
+
+namespace cnn {
+
+inline int out_dim(int in, int k, int stride, int pad) {
+    const int span = in + 2 * pad - k;
+    return span < 0 ? 0 : span / stride + 1;
+}
+
+int hip_check(cnn_ctx* ctx, hipError_t e, const char* what);   // records text, returns CNN_OK / CNN_EHIP
+int launch_check(cnn_ctx* ctx, const char* what);              // hipGetLastError after a launch
+
+// ---- plain one-thread-per-output kernels: any shape, slow; the fallback of every contraction
+int direct_conv_fwd(cnn_ctx*, const ConvShape&, const float* x, const float* w, float* y);
+int direct_conv_bwd_data(cnn_ctx*, const ConvShape&, const float* dy, const float* w, float* dx);
+int direct_conv_bwd_weight(cnn_ctx*, const ConvShape&, const float* x, const float* dy, float* dw);
+
+// ---- MFMA paths; each returns CNN_EUNSUPPORTED (without launching) for shapes it does not cover
+int mfma_conv_fwd(cnn_ctx*, const ConvShape&, const float* x, const float* w, float* y);
+int mfma_conv_bwd_data(cnn_ctx*, const ConvShape&, const float* dy, const float* w, float* dx);
+int mfma_conv_bwd_weight(cnn_ctx*, const ConvShape&, const float* x, const float* dy, float* dw);
+size_t mfma_conv_bwd_weight_ws(const ConvShape&);
+size_t mfma_conv_bwd_data_ws(const ConvShape&);
+
+// C[M][Nn] = op(A) * op(B); row-major operands.
+//   a_kmajor == 0: A is [M][Kd] (contraction index contiguous);  != 0: A is [Kd][M]
+//   b_kmajor == 0: B is [Nn][Kd] (contraction index contiguous); != 0: B is [Kd][Nn]
+int mfma_gemm(cnn_ctx*, int M, int Nn, int Kd, const float* A, int a_kmajor, const float* B, int b_kmajor, float* C);
+size_t mfma_gemm_ws(int M, int Nn, int Kd);
+
+}  // namespace cnn

@@ -1,0 +1,164 @@
+"""Sequences libcnn calls into one training iteration of a layer list (paper Section 3.1 ordering:
+forward through all layers, then per layer weight gradient BEFORE backpropagation, the first layer
+skipping backpropagation, then one SGD update over the flat parameter arena).
+
+This module only orders calls and owns buffers; all arithmetic happens inside libcnn kernels.
+Every call's inputs and outputs stay alive in distinct buffers and are recorded in `self.trace`
+so that tests can re-evaluate each call on exactly the tensors it consumed.
+"""
+import numpy as np
+import torch
+
+from . import binding as B
+from . import synth
+
+
+class Net:
+    def __init__(self, ctx, wl: synth.Workload, weights=None, record=False):
+        self.ctx, self.wl, self.record = ctx, wl, record
+        self.layers = list(wl.layers)
+        dev = torch.device("cuda")
+        wshapes = synth.weight_shapes(wl)
+        sizes = [int(np.prod(s)) for s in wshapes]
+        # one contiguous arena per role so the SGD update is a single launch; each slice 16-byte aligned
+        offs, total = [], 0
+        for n in sizes:
+            offs.append(total)
+            total += (n + 3) // 4 * 4
+        self.n_params = sum(sizes)
+        self.arena_elems = total
+        self.w_arena = torch.zeros(total, dtype=torch.float32, device=dev)
+        self.dw_arena = torch.zeros(total, dtype=torch.float32, device=dev)
+        self.v_arena = torch.zeros(total, dtype=torch.float32, device=dev) if wl.momentum != 0.0 else None
+        self.w = [self.w_arena[o:o + n].view(s) for o, n, s in zip(offs, sizes, wshapes)]
+        self.dw = [self.dw_arena[o:o + n].view(s) for o, n, s in zip(offs, sizes, wshapes)]
+        if weights is not None:
+            for dst, src in zip(self.w, weights):
+                dst.copy_(torch.from_numpy(np.ascontiguousarray(src)))
+        # activations: act[i] = output of layer i; act_in[i] = its input
+        shp = synth.shapes(wl)
+        self.x = torch.empty(wl.input_shape, dtype=torch.float32, device=dev)
+        self.act, self.gact, self.arg = [], [], {}
+        for i, (L, s) in enumerate(zip(self.layers, shp)):
+            if L[0] == "flatten":
+                # a view in both directions: the gradient written by the next layer lands in the
+                # gradient buffer of the layer before
+                self.act.append(None)
+                self.gact.append(self.gact[i - 1].view(s))
+            else:
+                self.act.append(torch.empty(s, dtype=torch.float32, device=dev))
+                self.gact.append(torch.empty(s, dtype=torch.float32, device=dev))
+            if L[0] == "pool":
+                self.arg[i] = torch.empty(s, dtype=torch.uint8, device=dev)
+        self.gx = None  # gradient w.r.t. the network input is never needed (Section 3.1)
+        n = wl.input_shape[0]
+        self.labels = torch.zeros(n, dtype=torch.int32, device=dev)
+        self.loss_per_sample = torch.empty(n, dtype=torch.float32, device=dev)
+        self.trace = []
+        self._reserve()
+
+    # ------------------------------------------------------------ workspace
+    def _reserve(self):
+        need = 0
+        shp = [tuple(self.wl.input_shape)] + synth.shapes(self.wl)
+        L_ = B.lib()
+        for i, L in enumerate(self.layers):
+            sin = shp[i]
+            if L[0] == "conv":
+                _, c, k, r, s, st, pad = L
+                for op in (B.OP_CONV_FWD, B.OP_CONV_BWD_DATA, B.OP_CONV_BWD_WEIGHT):
+                    need = max(need, L_.cnn_workspace_bytes(op, sin[0], c, sin[2], sin[3], k, r, s, st, pad))
+            elif L[0] == "fc":
+                for op in (B.OP_FC_FWD, B.OP_FC_BWD):
+                    need = max(need, L_.cnn_workspace_bytes(op, sin[0], L[1], 1, 1, L[2], 1, 1, 1, 0))
+        self.ctx.reserve(need)
+
+    def _rec(self, *item):
+        if self.record:
+            self.trace.append(item)
+
+    def _input_of(self, i):
+        j = i - 1
+        return self.x if j < 0 else self.act[j]
+
+    # ------------------------------------------------------------ passes
+    def forward(self):
+        ctx, wi = self.ctx, 0
+        for i, L in enumerate(self.layers):
+            xin, kind = self._input_of(i), L[0]
+            if kind == "conv":
+                B.cnn_conv_fwd(ctx, xin, self.w[wi], L[5], L[6], out=self.act[i])
+                self._rec("conv_fwd", i, wi, xin, self.w[wi], self.act[i]); wi += 1
+            elif kind == "fc":
+                B.cnn_fc_fwd(ctx, xin, self.w[wi], out=self.act[i])
+                self._rec("fc_fwd", i, wi, xin, self.w[wi], self.act[i]); wi += 1
+            elif kind == "relu":
+                B.cnn_relu_fwd(ctx, xin, out=self.act[i]); self._rec("relu_fwd", i, xin, self.act[i])
+            elif kind == "sigmoid":
+                B.cnn_sigmoid_fwd(ctx, xin, out=self.act[i]); self._rec("sigmoid_fwd", i, xin, self.act[i])
+            elif kind == "pool":
+                B.cnn_maxpool2_fwd(ctx, xin, out=self.act[i], arg_out=self.arg[i])
+                self._rec("pool_fwd", i, xin, self.act[i], self.arg[i])
+            elif kind == "flatten":
+                self.act[i] = xin.view(xin.shape[0], -1)
+        return self.act[-1]
+
+    def loss(self):
+        """Softmax cross-entropy on the last activation; fills the gradient of the last activation."""
+        z = self.act[-1]
+        B.cnn_softmax_xent(self.ctx, z, self.labels, loss_out=self.loss_per_sample, dz_out=self.gact[-1])
+        self._rec("softmax_xent", len(self.layers) - 1, z, self.labels, self.loss_per_sample, self.gact[-1])
+        return self.loss_per_sample
+
+    def backward(self):
+        """Expects gact[-1] to hold the gradient of the last activation (from loss() or set_upstream())."""
+        ctx = self.ctx
+        wi = len(self.w)
+        for i in range(len(self.layers) - 1, -1, -1):
+            L, kind = self.layers[i], self.layers[i][0]
+            xin, dy = self._input_of(i), self.gact[i]
+            first = i == 0
+            dxb = None if first else self.gact[i - 1]
+            if kind == "conv":
+                wi -= 1
+                B.cnn_conv_bwd_weight(ctx, xin, dy, L[3], L[4], L[5], L[6], out=self.dw[wi])
+                self._rec("conv_bwd_weight", i, wi, xin, dy, self.dw[wi])
+                if not first:
+                    B.cnn_conv_bwd_data(ctx, dy, self.w[wi], xin.shape[2], xin.shape[3], L[5], L[6], out=dxb)
+                    self._rec("conv_bwd_data", i, wi, dy, self.w[wi], dxb)
+            elif kind == "fc":
+                wi -= 1
+                B.cnn_fc_bwd(ctx, xin, self.w[wi], dy, need_dx=not first, need_dw=True,
+                             dx_out=None if first else dxb.view(xin.shape), dw_out=self.dw[wi])
+                self._rec("fc_bwd", i, wi, xin, self.w[wi], dy, None if first else dxb.view(xin.shape), self.dw[wi])
+            elif kind == "relu":
+                B.cnn_relu_bwd(ctx, xin, dy, out=dxb); self._rec("relu_bwd", i, xin, dy, dxb)
+            elif kind == "sigmoid":
+                B.cnn_sigmoid_bwd(ctx, self.act[i], dy, out=dxb); self._rec("sigmoid_bwd", i, self.act[i], dy, dxb)
+            elif kind == "pool":
+                B.cnn_maxpool2_bwd(ctx, dy, self.arg[i], xin.shape[2], xin.shape[3], out=dxb)
+                self._rec("pool_bwd", i, dy, self.arg[i], dxb)
+            # flatten: nothing to do, gact[i] aliases gact[i-1]
+        return None
+
+    def sgd(self):
+        B.cnn_sgd_update(self.ctx, self.w_arena, self.dw_arena, self.v_arena, self.wl.lr, self.wl.momentum)
+
+    # ------------------------------------------------------------ helpers
+    def set_input(self, x_np, labels_np=None):
+        self.x.copy_(torch.from_numpy(x_np))
+        if labels_np is not None:
+            self.labels.copy_(torch.from_numpy(labels_np))
+
+    def set_upstream(self, g_np):
+        self.gact[-1].copy_(torch.from_numpy(g_np))
+
+    def step(self):
+        """One full iteration of the workload: forward, (loss), backward, (SGD)."""
+        self.trace.clear()
+        self.forward()
+        if self.wl.loss:
+            self.loss()
+        self.backward()
+        if self.wl.sgd:
+            self.sgd()

@@ -1,0 +1,151 @@
+"""Shared helpers for the GPU parity tests: tolerance checks and oracle evaluation of a recorded call."""
+import numpy as np
+
+import oracle
+from paper_1602_06709_amd import synth
+
+REL_L2 = 1e-5          # spec tolerance: relative L2 error of the whole tensor (or sample)
+PER_ELEM = 1e-4        # and |diff| <= 1e-4 * sum|a*b| over the element's contraction
+
+
+def check_contraction(name, got, ref, sabs):
+    got = np.asarray(got, dtype=np.float64).ravel()
+    ref = np.asarray(ref, dtype=np.float64).ravel()
+    sabs = np.asarray(sabs, dtype=np.float64).ravel()
+    assert got.shape == ref.shape, (name, got.shape, ref.shape)
+    assert np.all(np.isfinite(got)), f"{name}: non-finite output"
+    diff = np.abs(got - ref)
+    denom = np.linalg.norm(ref)
+    rel = np.linalg.norm(got - ref) / denom if denom > 0 else np.linalg.norm(got - ref)
+    worst = np.max(diff - PER_ELEM * sabs) if diff.size else 0.0
+    assert rel <= REL_L2, f"{name}: rel-L2 {rel:.3e} > {REL_L2}"
+    assert worst <= 0.0, f"{name}: per-element bound exceeded by {worst:.3e} (max diff {diff.max():.3e})"
+    return rel
+
+
+def check_elementwise(name, got, ref, atol_scale=None, rel_l2=REL_L2, ulps=4):
+    """No contraction: a few ulp of the largest operand magnitude per element, and rel-L2 <= 1e-5."""
+    got = np.asarray(got, dtype=np.float64).ravel()
+    ref = np.asarray(ref, dtype=np.float64).ravel()
+    assert np.all(np.isfinite(got)), f"{name}: non-finite output"
+    scale = np.abs(ref) if atol_scale is None else np.asarray(atol_scale, dtype=np.float64).ravel()
+    bound = ulps * 2.0 ** -23 * np.maximum(scale, 1e-30)
+    diff = np.abs(got - ref)
+    assert np.all(diff <= bound + 1e-37), f"{name}: max excess {np.max(diff - bound):.3e}"
+    denom = np.linalg.norm(ref)
+    rel = np.linalg.norm(got - ref) / denom if denom > 0 else 0.0
+    assert rel <= rel_l2, f"{name}: rel-L2 {rel:.3e}"
+    return rel
+
+
+def np_(t):
+    return t.detach().cpu().numpy()
+
+
+def sample(cfg, tid, total, count):
+    return synth.sample_indices(cfg, tid, total, count)
+
+
+def check_trace_item(item, cfg, layers, full, n_samples=20000, n_samples_wgrad=1500):
+    """Re-evaluate one recorded libcnn call with the oracle on the very tensors it consumed.
+    full=True compares whole tensors; otherwise a seeded sample of output elements."""
+    op = item[0]
+    i = item[1]
+    L = layers[i]
+    name = f"cfg{cfg}:{op}@layer{i}"
+    if op == "conv_fwd":
+        _, _, wi, x, w, y = item
+        x, w, y = np_(x), np_(w), np_(y)
+        if full:
+            ref, s = oracle.conv_fwd(x, w, L[5], L[6], with_abs=True)
+            return check_contraction(name, y, ref, s)
+        idx = sample(cfg, 1000 + i, y.size, n_samples)
+        ref, s = oracle.conv_fwd_at(x, w, idx, L[5], L[6])
+        return check_contraction(name, y.ravel()[idx], ref, s)
+    if op == "conv_bwd_data":
+        _, _, wi, dy, w, dx = item
+        dy, w, dx = np_(dy), np_(w), np_(dx)
+        H, W = dx.shape[2:]
+        if full:
+            ref, s = oracle.conv_bwd_data(dy, w, H, W, L[5], L[6], with_abs=True)
+            return check_contraction(name, dx, ref, s)
+        idx = sample(cfg, 2000 + i, dx.size, n_samples)
+        ref, s = oracle.conv_bwd_data_at(dy, w, H, W, idx, L[5], L[6])
+        return check_contraction(name, dx.ravel()[idx], ref, s)
+    if op == "conv_bwd_weight":
+        _, _, wi, x, dy, dw = item
+        x, dy, dw = np_(x), np_(dy), np_(dw)
+        if full:
+            ref, s = oracle.conv_bwd_weight(x, dy, L[3], L[4], L[5], L[6], with_abs=True)
+            return check_contraction(name, dw, ref, s)
+        idx = sample(cfg, 3000 + i, dw.size, n_samples_wgrad)
+        ref, s = oracle.conv_bwd_weight_at(x, dy, L[3], L[4], idx, L[5], L[6])
+        return check_contraction(name, dw.ravel()[idx], ref, s)
+    if op == "fc_fwd":
+        _, _, wi, x, w, y = item
+        x, w, y = np_(x), np_(w), np_(y)
+        if full:
+            ref, s = oracle.fc_fwd(x, w, with_abs=True)
+            return check_contraction(name, y, ref, s)
+        idx = sample(cfg, 4000 + i, y.size, n_samples)
+        ref, s = oracle.fc_fwd_at(x, w, idx)
+        return check_contraction(name, y.ravel()[idx], ref, s)
+    if op == "fc_bwd":
+        _, _, wi, x, w, dy, dx, dw = item
+        x, w, dy, dw = np_(x), np_(w), np_(dy), np_(dw)
+        if full:
+            ref, s = oracle.fc_bwd_weight(x, dy, with_abs=True)
+            r = check_contraction(name + ":dw", dw, ref, s)
+        else:
+            idx = sample(cfg, 5000 + i, dw.size, n_samples)
+            ref, s = oracle.fc_bwd_weight_at(x, dy, idx)
+            r = check_contraction(name + ":dw", dw.ravel()[idx], ref, s)
+        if dx is not None:
+            dx = np_(dx)
+            if full:
+                ref, s = oracle.fc_bwd_data(dy, w, with_abs=True)
+                r = max(r, check_contraction(name + ":dx", dx, ref, s))
+            else:
+                idx = sample(cfg, 6000 + i, dx.size, n_samples)
+                ref, s = oracle.fc_bwd_data_at(dy, w, idx)
+                r = max(r, check_contraction(name + ":dx", dx.ravel()[idx], ref, s))
+        return r
+    if op == "relu_fwd":
+        _, _, z, a = item
+        assert np.array_equal(np_(a).astype(np.float64), oracle.relu_fwd(np_(z))), name
+        return 0.0
+    if op == "relu_bwd":
+        _, _, z, da, dz = item
+        assert np.array_equal(np_(dz).astype(np.float64), oracle.relu_bwd(np_(z), np_(da))), name
+        return 0.0
+    if op == "pool_fwd":
+        _, _, x, y, arg = item
+        yo, ao = oracle.maxpool2_fwd(np_(x))
+        assert np.array_equal(np_(y).astype(np.float64), yo), name
+        assert np.array_equal(np_(arg).astype(np.int32), ao), name + ":argmax"
+        return 0.0
+    if op == "pool_bwd":
+        _, _, dy, arg, dx = item
+        H, W = dx.shape[2:]
+        assert np.array_equal(np_(dx).astype(np.float64), oracle.maxpool2_bwd(np_(dy), np_(arg).astype(np.int32), H, W)), name
+        return 0.0
+    if op == "sigmoid_fwd":
+        _, _, z, a = item
+        return check_elementwise(name, np_(a), oracle.sigmoid_fwd(np_(z)), ulps=8)
+    if op == "sigmoid_bwd":
+        _, _, a, da, dz = item
+        return check_elementwise(name, np_(dz), oracle.sigmoid_bwd(np_(a), np_(da)),
+                                 atol_scale=np.abs(np_(da)).astype(np.float64) * 0.25)
+    if op == "softmax_xent":
+        _, _, z, label, loss, dz = item
+        z_, lab = np_(z), np_(label)
+        lo, dzo = oracle.softmax_xent(z_, lab)
+        got_loss = float(np.mean(np_(loss).astype(np.float64)))
+        assert abs(got_loss - lo) <= 1e-5 * max(1.0, abs(lo)), (name, got_loss, lo)
+        d = np_(dz).astype(np.float64)
+        rel = np.linalg.norm(d - dzo) / np.linalg.norm(dzo)
+        assert rel <= REL_L2, f"{name}: rel-L2 {rel:.3e}"
+        # per element: a few ulp of the probability, scaled by 1/N
+        assert np.all(np.abs(d - dzo) <= 32 * 2.0 ** -23 * (np.abs(dzo) + 1.0 / z_.shape[0] * 1e-3) + 1e-12), name
+        return rel
+    raise AssertionError(f"unknown trace op {op}")

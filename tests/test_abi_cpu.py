@@ -1,0 +1,108 @@
+"""CPU-only checks of the boundary: the library loads, exports every symbol the header declares,
+and its host-side logic (validation, workspace planning) behaves -- no kernel is launched here."""
+import ctypes as C
+import os
+import re
+
+import pytest
+
+from paper_1602_06709_amd import binding, synth
+
+ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+
+
+@pytest.fixture(scope="module")
+def L():
+    binding.ensure_built()
+    return binding.lib()
+
+
+def test_every_declared_symbol_is_exported(L):
+    hdr = open(os.path.join(ROOT, "include", "cnn.h")).read()
+    hdr = re.sub(r"/\*.*?\*/", "", hdr, flags=re.S)
+    declared = set(re.findall(r"\b(cnn_[a-z0-9_]+)\s*\(", hdr))
+    assert len(declared) >= 27
+    for name in declared:
+        assert hasattr(L, name), f"{name} declared in include/cnn.h but not exported"
+    assert declared == set(binding.SIGNATURES), declared ^ set(binding.SIGNATURES)
+
+
+def test_status_strings(L):
+    assert L.cnn_strerror(0) == b"ok"
+    for code in (-1, -2, -3, -4):
+        assert L.cnn_strerror(code) not in (b"ok", b"unknown status")
+    assert L.cnn_strerror(-99) == b"unknown status"
+
+
+def test_validation_rejects_before_any_launch(L):
+    h = C.c_void_p()
+    assert L.cnn_create(C.byref(h), None) == 0
+    try:
+        buf = (C.c_float * 64)()
+        p = C.cast(buf, C.c_void_p)
+        # null tensor, zero / negative dims, stride 0, negative pad, kernel larger than the padded image
+        assert L.cnn_conv_fwd(h, 1, 1, 4, 4, 1, 3, 3, 1, 1, None, p, p) == -1
+        assert L.cnn_conv_fwd(h, 0, 1, 4, 4, 1, 3, 3, 1, 1, p, p, p) == -1
+        assert L.cnn_conv_fwd(h, 1, 1, 4, 4, 1, 3, 3, 0, 1, p, p, p) == -1
+        assert L.cnn_conv_bwd_data(h, 1, 1, 4, 4, 1, 3, 3, 1, -1, p, p, p) == -1
+        assert L.cnn_conv_bwd_weight(h, 1, 1, 2, 2, 1, 5, 5, 1, 0, p, p, p) == -1
+        assert L.cnn_fc_fwd(h, 4, 0, 8, p, p, p) == -1
+        assert L.cnn_fc_bwd(h, 4, 8, 8, p, p, None, p, p) == -1
+        assert L.cnn_fc_bwd(h, 4, 8, 8, None, p, p, None, p) == -1          # dw asked for without x
+        assert L.cnn_sgd_update(h, 0, p, p, None, 0.1, 0.0) == -1
+        assert L.cnn_relu_fwd(h, 8, None, p) == -1
+        assert L.cnn_maxpool2_fwd(h, 1, 3, 4, p, p, None) == -1            # odd height
+        assert L.cnn_softmax_xent(h, 0, 10, p, p, p, p) == -1
+        assert L.cnn_pack_act(h, 1, 3, 2, 2, 0, p, p) == -1
+        assert L.cnn_set_option(h, 12345, 1) == -1
+        assert L.cnn_set_workspace(h, None, 16) == -1
+        # more than 2^31-1 elements in a tensor: unsupported, not a crash
+        assert L.cnn_conv_fwd(h, 4096, 1024, 224, 224, 64, 3, 3, 1, 1, p, p, p) == -2
+        # weight gradient of a tiled shape without a workspace attached
+        assert L.cnn_conv_bwd_weight(h, 4, 64, 56, 56, 64, 3, 3, 1, 1, p, p, p) == -3
+        assert L.cnn_last_error(h) == b""
+    finally:
+        assert L.cnn_destroy(h) == 0
+    assert L.cnn_destroy(None) == -1
+
+
+def test_workspace_planning(L):
+    ws = L.cnn_workspace_bytes
+    # forward never needs scratch; unknown shapes need none (they run on the plain kernels)
+    assert ws(binding.OP_CONV_FWD, 64, 256, 56, 56, 256, 3, 3, 1, 1) == 0
+    assert ws(binding.OP_CONV_BWD_WEIGHT, 2, 3, 32, 32, 16, 3, 3, 1, 1) == 0
+    # backpropagation keeps one mirrored transpose of the weights
+    assert ws(binding.OP_CONV_BWD_DATA, 64, 256, 56, 56, 256, 3, 3, 1, 1) == 256 * 256 * 9 * 4
+    # weight gradient: a whole number of private copies of dw
+    b = ws(binding.OP_CONV_BWD_WEIGHT, 64, 256, 56, 56, 256, 3, 3, 1, 1)
+    assert b > 0 and b % (256 * 256 * 9 * 4) == 0
+    # split-K partials for the small-minibatch FC forward; none when there are tiles enough
+    b = ws(binding.OP_FC_FWD, 64, 25088, 1, 1, 4096, 1, 1, 1, 0)
+    assert b > 0 and b % (64 * 4096 * 4) == 0
+    assert ws(binding.OP_FC_FWD, 0, 25088, 1, 1, 4096, 1, 1, 1, 0) == 0
+    # every layer of every workload plans without error and stays far below the device memory
+    for cfg in (1, 2, 3, 4, 5):
+        wl = synth.workload(cfg)
+        shp = [tuple(wl.input_shape)] + synth.shapes(wl)
+        for i, Ly in enumerate(wl.layers):
+            if Ly[0] == "conv":
+                s = shp[i]
+                for op in (0, 1, 2):
+                    assert ws(op, s[0], Ly[1], s[2], s[3], Ly[2], Ly[3], Ly[4], Ly[5], Ly[6]) < (8 << 30)
+            elif Ly[0] == "fc":
+                for op in (3, 4):
+                    assert ws(op, shp[i][0], Ly[1], 1, 1, Ly[2], 1, 1, 1, 0) < (8 << 30)
+
+
+def test_packed_sizes(L):
+    assert L.cnn_packed_act_elems(2, 11, 3, 5, 8) == 2 * 2 * 3 * 5 * 8
+    assert L.cnn_packed_wt_elems(13, 11, 3, 2, 8, 0) == 11 * 2 * 3 * 2 * 8
+    assert L.cnn_packed_wt_elems(13, 11, 3, 2, 8, 1) == 13 * 2 * 3 * 2 * 8
+    assert L.cnn_packed_act_elems(2, 11, 3, 5, 0) == 0
+
+
+def test_missing_library_is_an_error(monkeypatch, tmp_path):
+    monkeypatch.setattr(binding, "_LIB", None)
+    monkeypatch.setattr(binding._build, "LIB", str(tmp_path / "nope.so"))
+    with pytest.raises(binding.CnnError):
+        binding.lib()
