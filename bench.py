@@ -1,0 +1,177 @@
+#!/usr/bin/env python3
+"""Benchmark of the hot path on one MI355X: one step = forward + loss + backward (+ SGD) of a workload.
+
+    python bench.py [--gpus 1] [--steps K] [--warmup W] [--config 3] [--no-cpu-baseline]
+
+Default workload (config 3): VGG-A, all conv + FC layers, per-GPU minibatch 64, fp32, forward + softmax
+cross-entropy + backward + SGD (lr 0.01, momentum 0.9), synthetic N(0,1) images, He-normal weights -- the
+workload BASELINE.json's metric ("VGG-A conv+FC fwd+bwd images/sec on 1 MI355X") is quoted on.
+Prints ONE JSON line.  Inputs are resident in HBM before the timed region starts.
+
+`roofline` describes the dominant kernel (largest share of the timed region): achieved = algorithmic
+FLOPs of its launches / their summed duration, measured with HIP events that the library records on
+its own stream around every kernel launch during the timed steps.
+`cpu_baseline` is the CPU oracle (the plain fp64 loop nest, untuned) timed on this machine's host cores on
+a bounded sample: one image through every layer of the same network, all passes.
+"""
+import argparse
+import json
+import os
+import sys
+import time
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+sys.path.insert(0, ROOT)
+
+PEAK_FP32_MFMA_TFLOPS = 157.3     # 256 CUs x 256 FLOP/clk x 2.4 GHz (published dense fp32 matrix peak)
+PEAK_HBM_GBS = 8000.0
+
+
+def main():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=10)
+    ap.add_argument("--warmup", type=int, default=3)
+    ap.add_argument("--config", type=int, default=3, choices=[1, 2, 3, 4, 5])
+    ap.add_argument("--batch", type=int, default=None, help="override the per-GPU minibatch")
+    ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--no-profile", action="store_true", help="leave the per-kernel events out of the timed region")
+    ap.add_argument("--per-kernel", action="store_true", help="print the per-kernel table to stderr")
+    args = ap.parse_args()
+    if args.gpus != 1 or int(os.environ.get("WORLD_SIZE", "1")) != 1:
+        print("bench.py: this build measures one GPU's share of the minibatch only; "
+              "nothing here uses a second GPU (run with --gpus 1).", file=sys.stderr)
+        sys.exit(2)
+
+    import numpy as np
+    import torch
+
+    from paper_1602_06709_amd import binding as cnn, synth
+    from paper_1602_06709_amd.net import Net
+
+    cnn.ensure_built()
+    torch.cuda.set_device(0)
+    wl = synth.workload(args.config, args.batch)
+    N = wl.input_shape[0]
+    ctx = cnn.Context()
+    net = Net(ctx, wl, synth.make_weights(wl))
+    net.set_input(synth.make_input(wl), synth.make_labels(wl) if wl.loss else None)
+    upstream = None if wl.loss else torch.from_numpy(synth.make_upstream(wl)).cuda()
+
+    def step():
+        if upstream is not None:
+            net.gact[-1].copy_(upstream)     # device-to-device; the gradient buffer is overwritten by backward
+        net.step()
+
+    for _ in range(args.warmup):
+        step()
+    torch.cuda.synchronize()
+    if not args.no_profile:
+        ctx.profile_reset()
+        ctx.profile(True)
+    t0 = time.perf_counter()
+    for _ in range(args.steps):
+        step()
+    torch.cuda.synchronize()
+    dt = time.perf_counter() - t0
+    ctx.profile(False)
+    ms_per_step = dt / args.steps * 1e3
+    loss = float(net.loss_per_sample.mean().item()) if wl.loss else None
+
+    # ---- algorithmic FLOPs of one step (Section 3.1 formula; first layer has no backpropagation)
+    shp = [tuple(wl.input_shape)] + synth.shapes(wl)
+    flops, first = 0.0, True
+    for i, L in enumerate(wl.layers):
+        if L[0] == "conv":
+            f = 2.0 * N * L[1] * L[2] * L[3] * L[4] * shp[i + 1][2] * shp[i + 1][3]
+        elif L[0] == "fc":
+            f = 2.0 * N * L[1] * L[2]
+        else:
+            continue
+        flops += f * (2 if first else 3)
+        first = False
+
+    # ---- per-kernel table from the library's own events
+    kern = {}
+    if not args.no_profile:
+        for name, fl, ms in ctx.profile_entries():
+            k = kern.setdefault(name, [0, 0.0, 0.0])
+            k[0] += 1; k[1] += fl; k[2] += ms
+    roofline = None
+    kernels_out = []
+    if kern:
+        tot_ms = sum(v[2] for v in kern.values())
+        for name, (cnt, fl, ms) in sorted(kern.items(), key=lambda kv: -kv[1][2]):
+            kernels_out.append({"kernel": name, "launches_per_step": cnt / args.steps, "avg_ms": ms / cnt,
+                                "tflops": fl / (ms * 1e-3) / 1e12 if fl else None, "share": ms / tot_ms})
+        if args.per_kernel:
+            for k in kernels_out:
+                print("%-62s n/step %5.1f avg %9.4f ms  %s  share %5.1f%%" % (
+                    k["kernel"], k["launches_per_step"], k["avg_ms"],
+                    ("%6.1f TF/s" % k["tflops"]) if k["tflops"] else "           ", 100 * k["share"]), file=sys.stderr)
+        dom = kernels_out[0]
+        cnt, fl, ms = kern[dom["kernel"]]
+        if fl > 0:
+            ach = fl / (ms * 1e-3) / 1e12
+            roofline = {"kernel": dom["kernel"], "bound": "mfma", "achieved": ach, "peak": PEAK_FP32_MFMA_TFLOPS,
+                        "unit": "TFLOP/s", "frac": ach / PEAK_FP32_MFMA_TFLOPS, "traffic": None,
+                        "launches": cnt, "avg_launch_ms": ms / cnt, "flops_per_launch": fl / cnt,
+                        "share_of_step": dom["share"]}
+        else:
+            roofline = {"kernel": dom["kernel"], "bound": "hbm", "achieved": None, "peak": PEAK_HBM_GBS, "unit": "GB/s",
+                        "frac": None, "traffic": None, "launches": cnt, "avg_launch_ms": ms / cnt}
+        # the SGD update against the HBM roof (12 B/param plain, 20 B/param with momentum)
+        for name, (cnt, fl, ms) in kern.items():
+            if name.startswith("k_sgd"):
+                bpp = 20 if "momentum" in name else 12
+                gbs = net.arena_elems * bpp / (ms / cnt * 1e-3) / 1e9
+                roofline["sgd_update"] = {"kernel": name, "bound": "hbm", "achieved": gbs, "peak": PEAK_HBM_GBS,
+                                          "unit": "GB/s", "frac": gbs / PEAK_HBM_GBS, "bytes_per_param": bpp,
+                                          "avg_launch_ms": ms / cnt}
+        # all contraction kernels together (conv fwd/bwd-data, weight gradient, FC GEMMs)
+        cfl = sum(v[1] for v in kern.values()); cms = sum(v[2] for v in kern.values() if v[1] > 0)
+        roofline["all_contractions"] = {"achieved": cfl / (cms * 1e-3) / 1e12, "frac": cfl / (cms * 1e-3) / 1e12 / PEAK_FP32_MFMA_TFLOPS,
+                                        "unit": "TFLOP/s", "share_of_step": cms / tot_ms}
+
+    # ---- CPU baseline: the oracle as it stands, one image through every layer, all passes
+    cpu = None
+    if not args.no_cpu_baseline:
+        import oracle
+        from oracle import net as onet
+        wl1 = synth.workload(args.config, 1)
+        w1 = synth.make_weights(wl1)
+        x1 = synth.make_input(wl1)
+        lab1 = synth.make_labels(wl1) if wl1.loss else None
+        up1 = None if wl1.loss else synth.make_upstream(wl1)
+        tim = {}
+        c0 = time.perf_counter()
+        onet.run_step(wl1.layers, x1, w1, lab1, up1, timings=tim)
+        cdt = time.perf_counter() - c0
+        cpu = {"value": 1.0 / cdt, "unit": "images/s", "cores": oracle.num_threads(), "kind": "oracle",
+               "sample": f"1 image through every layer of {wl.name} (forward, loss, weight gradients, backpropagation; "
+                         f"no SGD), {cdt:.1f} s of oracle time",
+               "gflops": flops / N / cdt / 1e9}
+
+    out = {
+        "metric": "VGG-A conv+FC fwd+bwd images/sec on 1 MI355X; % fp32 MFMA peak per layer" if args.config == 3
+                  else f"{wl.name} fwd+bwd images/sec on 1 MI355X",
+        "value": N * args.steps / dt, "unit": "images/s", "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
+        "ms_per_step": ms_per_step, "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
+        "dtype": "f32", "data": "synthetic",
+        "config": {"workload": f"{wl.name}_n{N}", "config_id": args.config, "per_gpu_minibatch": N,
+                   "passes": "fwd+loss+bwd" + ("+sgd" if wl.sgd else ""), "params": net.n_params,
+                   "lr": wl.lr, "momentum": wl.momentum},
+        "tflops": flops / (ms_per_step * 1e-3) / 1e12,
+        "frac_fp32_mfma_peak": flops / (ms_per_step * 1e-3) / 1e12 / PEAK_FP32_MFMA_TFLOPS,
+        "algorithmic_gflop_per_step": flops / 1e9,
+        "loss": loss,
+        "roofline": roofline,
+        "cpu_baseline": cpu,
+        "kernels": kernels_out,
+        "context": {"paper_vgg_a_training_images_per_s": 30, "paper_hardware": "2 x 16-core Xeon E5-2698v3 (Section 5.1)"},
+    }
+    print(json.dumps(out))
+
+
+if __name__ == "__main__":
+    main()

@@ -59,8 +59,11 @@ enum {
 
 /* options for cnn_set_option() */
 enum {
-    CNN_OPT_FORCE_DIRECT = 0 /* value != 0: route conv / fc calls to the plain one-thread-per-output kernels
-                                (kept as the any-shape fallback); default 0 */
+    CNN_OPT_FORCE_DIRECT = 0, /* value != 0: route conv / fc calls to the plain one-thread-per-output kernels
+                                 (kept as the any-shape fallback); default 0 */
+    CNN_OPT_PROFILE = 1       /* value != 0: bracket every kernel the library launches with a pair of HIP events
+                                 on the context's stream (host-side objects only); read back with cnn_profile_*.
+                                 Recording stops silently after 16384 entries until cnn_profile_reset(). default 0 */
 };
 
 typedef struct cnn_ctx cnn_ctx; /* opaque; owns nothing on the device */
@@ -75,6 +78,13 @@ int cnn_set_option(cnn_ctx* ctx, int option, int value);
 size_t cnn_workspace_bytes(int op, int N, int C, int H, int W, int K, int R, int S, int stride, int pad);
 const char* cnn_strerror(int status);
 const char* cnn_last_error(const cnn_ctx* ctx);
+
+/* Per-kernel timing (measurement aid, see CNN_OPT_PROFILE).  cnn_profile_get waits for entry `index` to finish
+ * and returns the kernel's name (static string naming the kernel and its tile geometry), the algorithmic FLOPs
+ * of that launch (Section 3.1 count; 0 for non-contraction kernels) and its duration in milliseconds. */
+int cnn_profile_count(const cnn_ctx* ctx);
+int cnn_profile_get(cnn_ctx* ctx, int index, const char** kernel_name, double* flops, float* ms);
+int cnn_profile_reset(cnn_ctx* ctx);
 
 /* ---- Section 2.1, Algorithm 1 "Forward Propagation":
  *   y[n][k][p][q] = sum_{c,r,s} x[n][c][p*stride + r - pad][q*stride + s - pad] * w[k][c][r][s]

@@ -42,6 +42,10 @@ def _p(a):
     return a.ctypes.data_as(C.c_void_p) if a is not None else None
 
 
+def num_threads():
+    return int(lib().oracle_num_threads())
+
+
 def out_dim(n, k, stride, pad):
     return int(lib().oracle_out_dim(int(n), int(k), int(stride), int(pad)))
 

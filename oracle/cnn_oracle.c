@@ -31,6 +31,7 @@
  * Build:  gcc -O2 -fopenmp -shared -fPIC -o liboracle.so cnn_oracle.c -lm
  */
 #include <math.h>
+#include <omp.h>
 #include <stddef.h>
 #include <stdint.h>
 #include <string.h>
@@ -42,6 +43,7 @@ static int out_dim(int in, int k, int stride, int pad) {
 }
 
 int oracle_out_dim(int in, int k, int stride, int pad) { return out_dim(in, k, stride, pad); }
+int oracle_num_threads(void) { return omp_get_max_threads(); }
 
 /* ------------------------------------------------------------------ */
 /* Section 2.1, Algorithm 1: forward propagation.                      */
@@ -55,7 +57,7 @@ void oracle_conv_fwd(int N, int C, int H, int W, int K, int R, int S, int stride
     const size_t ysz = (size_t)N * K * P * Q;
     memset(y, 0, ysz * sizeof(double));
     if (sabs) memset(sabs, 0, ysz * sizeof(double));
-#pragma omp parallel for schedule(dynamic, 1)
+#pragma omp parallel for collapse(2) schedule(dynamic, 1)
     for (int n = 0; n < N; ++n)
         for (int k = 0; k < K; ++k)
             for (int c = 0; c < C; ++c)
@@ -89,7 +91,7 @@ void oracle_conv_bwd_data(int N, int C, int H, int W, int K, int R, int S, int s
     const size_t xsz = (size_t)N * C * H * W;
     memset(dx, 0, xsz * sizeof(double));
     if (sabs) memset(sabs, 0, xsz * sizeof(double));
-#pragma omp parallel for schedule(dynamic, 1)
+#pragma omp parallel for collapse(2) schedule(dynamic, 1)
     for (int n = 0; n < N; ++n)
         for (int c = 0; c < C; ++c)
             for (int k = 0; k < K; ++k)
@@ -122,7 +124,7 @@ void oracle_conv_bwd_data(int N, int C, int H, int W, int K, int R, int S, int s
 void oracle_conv_bwd_weight(int N, int C, int H, int W, int K, int R, int S, int stride, int pad,
                             const float* x, const float* dy, double* dw, double* sabs) {
     const int P = out_dim(H, R, stride, pad), Q = out_dim(W, S, stride, pad);
-#pragma omp parallel for schedule(dynamic, 1)
+#pragma omp parallel for collapse(2) schedule(dynamic, 1)
     for (int k = 0; k < K; ++k)
         for (int c = 0; c < C; ++c)
             for (int r = 0; r < R; ++r)
@@ -432,15 +434,18 @@ void oracle_unpack_wt(int K, int C, int R, int S, int SW, int transpose, const f
 /* dz = (softmax(z) - onehot)/N.                                          */
 /* ------------------------------------------------------------------ */
 void oracle_relu_fwd(size_t n, const float* z, double* a) {
+#pragma omp parallel for schedule(static)
     for (size_t i = 0; i < n; ++i) a[i] = z[i] > 0.0f ? (double)z[i] : 0.0;
 }
 /* da -> dz using the forward INPUT z (mask z > 0) */
 void oracle_relu_bwd(size_t n, const float* z, const float* da, double* dz) {
+#pragma omp parallel for schedule(static)
     for (size_t i = 0; i < n; ++i) dz[i] = z[i] > 0.0f ? (double)da[i] : 0.0;
 }
 /* planes = N*C; H, W even.  arg[.] in 0..3 = first max in window row-major order */
 void oracle_maxpool2_fwd(size_t planes, int H, int W, const float* x, double* y, int32_t* arg) {
     const int P = H / 2, Q = W / 2;
+#pragma omp parallel for schedule(static)
     for (size_t pl = 0; pl < planes; ++pl)
         for (int p = 0; p < P; ++p)
             for (int q = 0; q < Q; ++q) {
@@ -456,6 +461,7 @@ void oracle_maxpool2_fwd(size_t planes, int H, int W, const float* x, double* y,
 void oracle_maxpool2_bwd(size_t planes, int H, int W, const float* dy, const int32_t* arg, double* dx) {
     const int P = H / 2, Q = W / 2;
     memset(dx, 0, planes * H * W * sizeof(double));
+#pragma omp parallel for schedule(static)
     for (size_t pl = 0; pl < planes; ++pl)
         for (int p = 0; p < P; ++p)
             for (int q = 0; q < Q; ++q) {
@@ -464,10 +470,12 @@ void oracle_maxpool2_bwd(size_t planes, int H, int W, const float* dy, const int
             }
 }
 void oracle_sigmoid_fwd(size_t n, const float* z, double* a) {
+#pragma omp parallel for schedule(static)
     for (size_t i = 0; i < n; ++i) a[i] = 1.0 / (1.0 + exp(-(double)z[i]));
 }
 /* da -> dz using the forward OUTPUT a */
 void oracle_sigmoid_bwd(size_t n, const float* a, const float* da, double* dz) {
+#pragma omp parallel for schedule(static)
     for (size_t i = 0; i < n; ++i) dz[i] = (double)da[i] * (double)a[i] * (1.0 - (double)a[i]);
 }
 /* z[N][O], label[N]; returns the mean loss; dz[N][O] (may be NULL) */

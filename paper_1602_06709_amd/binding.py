@@ -15,6 +15,7 @@ _LIB = None
 
 OP_CONV_FWD, OP_CONV_BWD_DATA, OP_CONV_BWD_WEIGHT, OP_FC_FWD, OP_FC_BWD = range(5)
 OPT_FORCE_DIRECT = 0
+OPT_PROFILE = 1
 
 _vp, _i, _sz, _f = C.c_void_p, C.c_int, C.c_size_t, C.c_float
 _CONV = [_vp] + [_i] * 9 + [_vp] * 3
@@ -28,6 +29,9 @@ SIGNATURES = {
     "cnn_workspace_bytes": (_sz, [_i] * 10),
     "cnn_strerror": (C.c_char_p, [_i]),
     "cnn_last_error": (C.c_char_p, [_vp]),
+    "cnn_profile_count": (_i, [_vp]),
+    "cnn_profile_get": (_i, [_vp, _i, C.POINTER(C.c_char_p), C.POINTER(C.c_double), C.POINTER(C.c_float)]),
+    "cnn_profile_reset": (_i, [_vp]),
     "cnn_conv_fwd": (_i, _CONV),
     "cnn_conv_bwd_data": (_i, _CONV),
     "cnn_conv_bwd_weight": (_i, _CONV),
@@ -125,6 +129,22 @@ class Context:
 
     def set_option(self, option, value):
         _check(lib().cnn_set_option(self._h, option, int(value)))
+
+    def profile(self, on):
+        """Turn per-kernel event timing on/off (entries accumulate until profile_reset)."""
+        self.set_option(OPT_PROFILE, 1 if on else 0)
+
+    def profile_reset(self):
+        _check(lib().cnn_profile_reset(self._h))
+
+    def profile_entries(self):
+        """[(kernel name, algorithmic flops, milliseconds)] of every kernel launched while profiling was on."""
+        out = []
+        name, fl, ms = C.c_char_p(), C.c_double(), C.c_float()
+        for i in range(lib().cnn_profile_count(self._h)):
+            _check(lib().cnn_profile_get(self._h, i, C.byref(name), C.byref(fl), C.byref(ms)), self._h)
+            out.append((name.value.decode(), fl.value, ms.value))
+        return out
 
     def reserve(self, nbytes):
         """Make the attached workspace at least nbytes (allocation happens here, never inside the library)."""

@@ -14,6 +14,23 @@ int hip_check(cnn_ctx* ctx, hipError_t e, const char* what) {
 }
 int launch_check(cnn_ctx* ctx, const char* what) { return hip_check(ctx, hipGetLastError(), what); }
 
+ProfScope::ProfScope(cnn_ctx* c, const char* name, double flops) : ctx(c), ent(nullptr) {
+    if (!c || !c->profile || c->prof_used >= 16384) return;
+    if (c->prof_used == c->prof.size()) {
+        ProfEntry e{name, flops, nullptr, nullptr};
+        if (hipEventCreate(&e.e0) != hipSuccess) return;
+        if (hipEventCreate(&e.e1) != hipSuccess) { (void)hipEventDestroy(e.e0); return; }
+        c->prof.push_back(e);
+    }
+    ent = &c->prof[c->prof_used++];
+    ent->name = name;
+    ent->flops = flops;
+    (void)hipEventRecord(ent->e0, c->stream);
+}
+ProfScope::~ProfScope() {
+    if (ent) (void)hipEventRecord(ent->e1, ctx->stream);
+}
+
 }  // namespace cnn
 
 namespace {
@@ -44,12 +61,18 @@ int cnn_create(cnn_ctx** out, void* hip_stream) {
     c->ws = nullptr;
     c->ws_bytes = 0;
     c->force_direct = 0;
+    c->profile = 0;
+    c->prof_used = 0;
     c->err[0] = 0;
     *out = c;
     return CNN_OK;
 }
 int cnn_destroy(cnn_ctx* ctx) {
     if (!ctx) return CNN_EINVAL;
+    for (ProfEntry& e : ctx->prof) {
+        (void)hipEventDestroy(e.e0);
+        (void)hipEventDestroy(e.e1);
+    }
     delete ctx;
     return CNN_OK;
 }
@@ -67,6 +90,7 @@ int cnn_set_workspace(cnn_ctx* ctx, void* dev_ptr, size_t bytes) {
 int cnn_set_option(cnn_ctx* ctx, int option, int value) {
     if (!ctx) return CNN_EINVAL;
     if (option == CNN_OPT_FORCE_DIRECT) { ctx->force_direct = value != 0; return CNN_OK; }
+    if (option == CNN_OPT_PROFILE) { ctx->profile = value != 0; return CNN_OK; }
     return CNN_EINVAL;
 }
 const char* cnn_strerror(int status) {
@@ -80,6 +104,26 @@ const char* cnn_strerror(int status) {
     }
 }
 const char* cnn_last_error(const cnn_ctx* ctx) { return ctx ? ctx->err : ""; }
+
+int cnn_profile_count(const cnn_ctx* ctx) { return ctx ? (int)ctx->prof_used : CNN_EINVAL; }
+int cnn_profile_get(cnn_ctx* ctx, int index, const char** kernel_name, double* flops, float* ms) {
+    if (!ctx || index < 0 || (size_t)index >= ctx->prof_used) return CNN_EINVAL;
+    ProfEntry& e = ctx->prof[index];
+    int st = cnn::hip_check(ctx, hipEventSynchronize(e.e1), "hipEventSynchronize(profile)");
+    if (st != CNN_OK) return st;
+    float t = 0.f;
+    st = cnn::hip_check(ctx, hipEventElapsedTime(&t, e.e0, e.e1), "hipEventElapsedTime(profile)");
+    if (st != CNN_OK) return st;
+    if (kernel_name) *kernel_name = e.name;
+    if (flops) *flops = e.flops;
+    if (ms) *ms = t;
+    return CNN_OK;
+}
+int cnn_profile_reset(cnn_ctx* ctx) {
+    if (!ctx) return CNN_EINVAL;
+    ctx->prof_used = 0;
+    return CNN_OK;
+}
 
 size_t cnn_workspace_bytes(int op, int N, int C, int H, int W, int K, int R, int S, int stride, int pad) {
     ConvShape s;

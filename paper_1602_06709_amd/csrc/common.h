@@ -6,11 +6,22 @@
 
 #include "../../include/cnn.h"
 
+#include <vector>
+
+struct ProfEntry {
+    const char* name;
+    double flops;
+    hipEvent_t e0, e1;
+};
+
 struct cnn_ctx {
     hipStream_t stream;
     void* ws;
     size_t ws_bytes;
     int force_direct;
+    int profile;
+    std::vector<ProfEntry> prof;      // entries [0, prof_used) are live; the rest is a pool of created events
+    size_t prof_used;
     char err[256];
 };
 
@@ -23,6 +34,18 @@ namespace cnn {
 inline int out_dim(int in, int k, int stride, int pad) {
     const int span = in + 2 * pad - k;
     return span < 0 ? 0 : span / stride + 1;
+}
+
+// Brackets the kernel launches made during its lifetime with a pair of events when profiling is on.
+struct ProfScope {
+    cnn_ctx* ctx;
+    ProfEntry* ent;
+    ProfScope(cnn_ctx* c, const char* name, double flops);
+    ~ProfScope();
+};
+
+inline double conv_flops(const ConvShape& s) {   // Section 3.1: 2 * MB * ifm * ofm * k_w * k_h * out_w * out_h per pass
+    return 2.0 * s.N * s.C * s.K * s.R * s.S * s.P * s.Q;
 }
 
 int hip_check(cnn_ctx* ctx, hipError_t e, const char* what);   // records text, returns CNN_OK / CNN_EHIP

@@ -15,6 +15,8 @@
 // The two halves of the 64-lane wave feed k = 0 and k = 1 of the MFMA: the low half walks channels
 // [0, CB/2) of the chunk and the high half [CB/2, CB), so both halves use the same immediate offsets.
 // The next chunk is fetched from HBM into registers while the current one is multiplied.
+#include <stdio.h>
+
 #include "common.h"
 
 namespace {
@@ -216,7 +218,14 @@ int launch(cnn_ctx* ctx, int N, int J, int M, int HI, int HO, const float* in, c
     const int row_tiles = (HO + G::TH - 1) / G::TH;
     const int img_tiles = (N + G::NB - 1) / G::NB;
     dim3 grid((unsigned)(row_tiles * img_tiles), (unsigned)((M + G::MB - 1) / G::MB));
-    hipLaunchKernelGGL(k_conv_s1<G>, grid, dim3(G::T), G::LDS_BYTES, ctx->stream, N, J, M, HI, HO, row_tiles, in, wt, out);
+    static char name[96] = "";
+    if (!name[0])
+        snprintf(name, sizeof(name), "k_conv_s1<%dx%d pad%d CB%d WM%d WN%d NT%d NB%d TH%d W%d>", G::R, G::S, G::PADE, G::CB,
+                 G::WM, G::WN, G::NT, G::NB, G::TH, G::WI);
+    {
+        cnn::ProfScope ps(ctx, name, 2.0 * N * J * M * G::RS * HO * G::WO);
+        hipLaunchKernelGGL(k_conv_s1<G>, grid, dim3(G::T), G::LDS_BYTES, ctx->stream, N, J, M, HI, HO, row_tiles, in, wt, out);
+    }
     return cnn::launch_check(ctx, "conv_s1");
 }
 
@@ -280,7 +289,10 @@ int mfma_conv_bwd_data(cnn_ctx* ctx, const ConvShape& s, const float* dy, const 
         if (e != hipSuccess) return hip_check(ctx, e, "hipFuncSetAttribute(transpose_flip)");
         tl_attr = tl_bytes;
     }
-    hipLaunchKernelGGL(k_transpose_flip, grid, dim3(256), tl_bytes, ctx->stream, s.K, s.C, RS, w, wT);
+    {
+        ProfScope ps(ctx, "k_transpose_flip", 0.0);
+        hipLaunchKernelGGL(k_transpose_flip, grid, dim3(256), tl_bytes, ctx->stream, s.K, s.C, RS, w, wT);
+    }
     int st = launch_check(ctx, "transpose_flip");
     if (st != CNN_OK) return st;
     return dispatch(ctx, 0, s.R, s.S, s.R - 1 - s.pad, s.N, s.K, s.C, s.P, s.Q, dy, wT, dx);

@@ -100,16 +100,19 @@ namespace cnn {
 
 int direct_conv_fwd(cnn_ctx* ctx, const ConvShape& s, const float* x, const float* w, float* y) {
     const size_t total = (size_t)s.N * s.K * s.P * s.Q;
+    ProfScope ps(ctx, "k_direct_conv_fwd", conv_flops(s));
     hipLaunchKernelGGL(k_direct_conv_fwd, dim3(grid_for(total, 256)), dim3(256), 0, ctx->stream, s, x, w, y);
     return launch_check(ctx, "direct_conv_fwd");
 }
 int direct_conv_bwd_data(cnn_ctx* ctx, const ConvShape& s, const float* dy, const float* w, float* dx) {
     const size_t total = (size_t)s.N * s.C * s.H * s.W;
+    ProfScope ps(ctx, "k_direct_conv_bwd_data", conv_flops(s));
     hipLaunchKernelGGL(k_direct_conv_bwd_data, dim3(grid_for(total, 256)), dim3(256), 0, ctx->stream, s, dy, w, dx);
     return launch_check(ctx, "direct_conv_bwd_data");
 }
 int direct_conv_bwd_weight(cnn_ctx* ctx, const ConvShape& s, const float* x, const float* dy, float* dw) {
     const size_t total = (size_t)s.K * s.C * s.R * s.S;
+    ProfScope ps(ctx, "k_direct_conv_bwd_weight", conv_flops(s));
     hipLaunchKernelGGL(k_direct_conv_bwd_weight, dim3((unsigned)total), dim3(256), 0, ctx->stream, s, x, dy, dw);
     return launch_check(ctx, "direct_conv_bwd_weight");
 }

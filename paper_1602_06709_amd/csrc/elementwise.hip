@@ -258,6 +258,7 @@ int cnn_sgd_update(cnn_ctx* ctx, size_t n, float* w, const float* dw, float* v, 
     if (!aligned16(w) || !aligned16(dw) || (v && !aligned16(v))) return CNN_EINVAL;
     const size_t n4 = n >> 2;
     const unsigned grid = stream_grid(n4, kBlock * 4);
+    cnn::ProfScope ps(ctx, v ? "k_sgd<momentum>" : "k_sgd<plain>", 0.0);
     if (v)
         hipLaunchKernelGGL(k_sgd<true>, dim3(grid), dim3(kBlock), 0, ctx->stream, n4, n,
                            reinterpret_cast<float4*>(w), reinterpret_cast<const float4*>(dw),
@@ -271,12 +272,14 @@ int cnn_sgd_update(cnn_ctx* ctx, size_t n, float* w, const float* dw, float* v, 
 
 int cnn_relu_fwd(cnn_ctx* ctx, size_t n, const float* z, float* a) {
     if (!ctx || !z || !a || n == 0 || !aligned16(z) || !aligned16(a)) return CNN_EINVAL;
+    cnn::ProfScope ps_k_relu_fwd(ctx, "k_relu_fwd", 0.0);
     hipLaunchKernelGGL(k_relu_fwd, dim3(stream_grid(n >> 2, kBlock * 2)), dim3(kBlock), 0, ctx->stream, n >> 2, n,
                        reinterpret_cast<const float4*>(z), reinterpret_cast<float4*>(a));
     return cnn::launch_check(ctx, "relu_fwd");
 }
 int cnn_relu_bwd(cnn_ctx* ctx, size_t n, const float* z, const float* da, float* dz) {
     if (!ctx || !z || !da || !dz || n == 0 || !aligned16(z) || !aligned16(da) || !aligned16(dz)) return CNN_EINVAL;
+    cnn::ProfScope ps_k_relu_bwd(ctx, "k_relu_bwd", 0.0);
     hipLaunchKernelGGL(k_relu_bwd, dim3(stream_grid(n >> 2, kBlock * 2)), dim3(kBlock), 0, ctx->stream, n >> 2, n,
                        reinterpret_cast<const float4*>(z), reinterpret_cast<const float4*>(da),
                        reinterpret_cast<float4*>(dz));
@@ -284,11 +287,13 @@ int cnn_relu_bwd(cnn_ctx* ctx, size_t n, const float* z, const float* da, float*
 }
 int cnn_sigmoid_fwd(cnn_ctx* ctx, size_t n, const float* z, float* a) {
     if (!ctx || !z || !a || n == 0) return CNN_EINVAL;
+    cnn::ProfScope ps_k_sigmoid_fwd(ctx, "k_sigmoid_fwd", 0.0);
     hipLaunchKernelGGL(k_sigmoid_fwd, dim3(stream_grid(n, kBlock * 4)), dim3(kBlock), 0, ctx->stream, n, z, a);
     return cnn::launch_check(ctx, "sigmoid_fwd");
 }
 int cnn_sigmoid_bwd(cnn_ctx* ctx, size_t n, const float* a, const float* da, float* dz) {
     if (!ctx || !a || !da || !dz || n == 0) return CNN_EINVAL;
+    cnn::ProfScope ps_k_sigmoid_bwd(ctx, "k_sigmoid_bwd", 0.0);
     hipLaunchKernelGGL(k_sigmoid_bwd, dim3(stream_grid(n, kBlock * 4)), dim3(kBlock), 0, ctx->stream, n, a, da, dz);
     return cnn::launch_check(ctx, "sigmoid_bwd");
 }
@@ -296,6 +301,7 @@ int cnn_maxpool2_fwd(cnn_ctx* ctx, size_t planes, int H, int W, const float* x, 
     if (!ctx || !x || !y || planes == 0 || H < 2 || W < 2 || (H & 1) || (W & 1)) return CNN_EINVAL;
     if (reinterpret_cast<uintptr_t>(x) & 7u) return CNN_EINVAL;
     const size_t total = planes * (size_t)(H / 2) * (W / 2);
+    cnn::ProfScope ps_k_maxpool2_fwd(ctx, "k_maxpool2_fwd", 0.0);
     hipLaunchKernelGGL(k_maxpool2_fwd, dim3(stream_grid(total, kBlock * 2)), dim3(kBlock), 0, ctx->stream, total, H, W,
                        x, y, arg);
     return cnn::launch_check(ctx, "maxpool2_fwd");
@@ -304,12 +310,14 @@ int cnn_maxpool2_bwd(cnn_ctx* ctx, size_t planes, int H, int W, const float* dy,
     if (!ctx || !dy || !arg || !dx || planes == 0 || H < 2 || W < 2 || (H & 1) || (W & 1)) return CNN_EINVAL;
     if (reinterpret_cast<uintptr_t>(dx) & 7u) return CNN_EINVAL;
     const size_t total = planes * (size_t)(H / 2) * (W / 2);
+    cnn::ProfScope ps_k_maxpool2_bwd(ctx, "k_maxpool2_bwd", 0.0);
     hipLaunchKernelGGL(k_maxpool2_bwd, dim3(stream_grid(total, kBlock * 2)), dim3(kBlock), 0, ctx->stream, total, H, W,
                        dy, arg, dx);
     return cnn::launch_check(ctx, "maxpool2_bwd");
 }
 int cnn_softmax_xent(cnn_ctx* ctx, int N, int O, const float* z, const int32_t* label, float* loss, float* dz) {
     if (!ctx || !z || !label || N <= 0 || O <= 0) return CNN_EINVAL;
+    cnn::ProfScope ps_k_softmax_xent(ctx, "k_softmax_xent", 0.0);
     hipLaunchKernelGGL(k_softmax_xent, dim3(N), dim3(kBlock), 0, ctx->stream, N, O, z, label, loss, dz);
     return cnn::launch_check(ctx, "softmax_xent");
 }
@@ -325,6 +333,7 @@ size_t cnn_packed_wt_elems(int K, int C, int R, int S, int SW, int transpose) {
 int cnn_pack_act(cnn_ctx* ctx, int N, int C, int H, int W, int SW, const float* nchw, float* packed) {
     const size_t total = cnn_packed_act_elems(N, C, H, W, SW);
     if (!ctx || !nchw || !packed || total == 0) return CNN_EINVAL;
+    cnn::ProfScope ps_k_pack_blocked(ctx, "k_pack_blocked", 0.0);
     hipLaunchKernelGGL(k_pack_blocked, dim3(stream_grid(total, kBlock * 4)), dim3(kBlock), 0, ctx->stream, total, C,
                        H * W, SW, nchw, packed);
     return cnn::launch_check(ctx, "pack_act");
@@ -332,6 +341,7 @@ int cnn_pack_act(cnn_ctx* ctx, int N, int C, int H, int W, int SW, const float* 
 int cnn_unpack_act(cnn_ctx* ctx, int N, int C, int H, int W, int SW, const float* packed, float* nchw) {
     if (!ctx || !nchw || !packed || cnn_packed_act_elems(N, C, H, W, SW) == 0) return CNN_EINVAL;
     const size_t total = (size_t)N * C * H * W;
+    cnn::ProfScope ps_k_unpack_blocked(ctx, "k_unpack_blocked", 0.0);
     hipLaunchKernelGGL(k_unpack_blocked, dim3(stream_grid(total, kBlock * 4)), dim3(kBlock), 0, ctx->stream, total, C,
                        H * W, SW, packed, nchw);
     return cnn::launch_check(ctx, "unpack_act");
@@ -339,6 +349,7 @@ int cnn_unpack_act(cnn_ctx* ctx, int N, int C, int H, int W, int SW, const float
 int cnn_pack_wt(cnn_ctx* ctx, int K, int C, int R, int S, int SW, int transpose, const float* kcrs, float* packed) {
     const size_t total = cnn_packed_wt_elems(K, C, R, S, SW, transpose);
     if (!ctx || !kcrs || !packed || total == 0) return CNN_EINVAL;
+    cnn::ProfScope ps(ctx, "k_pack_wt", 0.0);
     if (transpose)
         hipLaunchKernelGGL(k_pack_blocked, dim3(stream_grid(total, kBlock * 4)), dim3(kBlock), 0, ctx->stream, total,
                            C, R * S, SW, kcrs, packed);
@@ -350,6 +361,7 @@ int cnn_pack_wt(cnn_ctx* ctx, int K, int C, int R, int S, int SW, int transpose,
 int cnn_unpack_wt(cnn_ctx* ctx, int K, int C, int R, int S, int SW, int transpose, const float* packed, float* kcrs) {
     if (!ctx || !kcrs || !packed || cnn_packed_wt_elems(K, C, R, S, SW, transpose) == 0) return CNN_EINVAL;
     const size_t total = (size_t)K * C * R * S;
+    cnn::ProfScope ps(ctx, "k_unpack_wt", 0.0);
     if (transpose)
         hipLaunchKernelGGL(k_unpack_blocked, dim3(stream_grid(total, kBlock * 4)), dim3(kBlock), 0, ctx->stream, total,
                            C, R * S, SW, packed, kcrs);

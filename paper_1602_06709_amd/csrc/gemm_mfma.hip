@@ -10,6 +10,8 @@
 // as [row][KC+1] (odd stride across the 32 lanes), row-contiguous tiles as [k][rows].  The output has
 // lane = column n (coalesced stores).  A small minibatch leaves few output tiles, so the contraction is
 // split across workgroups and the partial products are added by a second kernel in a fixed order.
+#include <stdio.h>
+
 #include "common.h"
 
 namespace {
@@ -192,13 +194,22 @@ template <class G>
 int launch(cnn_ctx* ctx, const GemmPlan& p, int M, int Nn, int Kd, const float* A, const float* B, float* C) {
     float* dst = p.nsplit > 1 ? reinterpret_cast<float*>(ctx->ws) : C;
     dim3 grid((unsigned)((Nn + G::TN - 1) / G::TN), (unsigned)((M + G::TM - 1) / G::TM), (unsigned)p.nsplit);
-    hipLaunchKernelGGL(k_gemm<G>, grid, dim3(G::T), 0, ctx->stream, M, Nn, Kd, p.k_per_split, A, B, dst);
+    static char name[96] = "";
+    if (!name[0])
+        snprintf(name, sizeof(name), "k_gemm<%dx%d %s%s>", G::TM, G::TN, G::AKM ? "At" : "A", G::BKM ? "B" : "Bt");
+    {
+        cnn::ProfScope ps(ctx, name, 2.0 * M * Nn * Kd);
+        hipLaunchKernelGGL(k_gemm<G>, grid, dim3(G::T), 0, ctx->stream, M, Nn, Kd, p.k_per_split, A, B, dst);
+    }
     int st = cnn::launch_check(ctx, "gemm");
     if (st != CNN_OK || p.nsplit == 1) return st;
     const size_t MN = (size_t)M * Nn;
     size_t g = (MN + 255) / 256;
     if (g > 4096) g = 4096;
-    hipLaunchKernelGGL(k_splitk_reduce, dim3((unsigned)g), dim3(256), 0, ctx->stream, p.nsplit, MN, dst, C);
+    {
+        cnn::ProfScope ps(ctx, "k_splitk_reduce", 0.0);
+        hipLaunchKernelGGL(k_splitk_reduce, dim3((unsigned)g), dim3(256), 0, ctx->stream, p.nsplit, MN, dst, C);
+    }
     return cnn::launch_check(ctx, "splitk_reduce");
 }
 

@@ -15,6 +15,8 @@
 // Row strides are odd so the 32 lanes of an operand (32 features) read 32 different banks.
 // Narrow images are processed NBI at a time (one ring each) to keep >= 48 pixels per step.
 // Wide rows are cut into column tiles of TW; each column tile is one more split.
+#include <stdio.h>
+
 #include "common.h"
 
 namespace {
@@ -257,15 +259,25 @@ int launch(cnn_ctx* ctx, const ConvShape& s, const float* x, const float* dy, fl
     }
     float* partial = reinterpret_cast<float*>(ctx->ws);
     dim3 grid((unsigned)(p.nsplit * p.col_tiles), (unsigned)p.ctiles, (unsigned)p.ktiles);
-    hipLaunchKernelGGL(k_wgrad<G>, grid, dim3(G::T), G::LDS_BYTES, ctx->stream, s.N, s.C, s.K, s.H, s.W, s.P, s.Q,
-                       p.rows_per_split, p.total_rows, x, dy, partial);
+    static char name[96] = "";
+    if (!name[0])
+        snprintf(name, sizeof(name), "k_wgrad<%dx%d pad%d TW%d NBI%d KW%d CW%d RW%d>", G::R, G::S, G::PAD, G::TW, G::NBI,
+                 G::KW, G::CW, G::RW);
+    {
+        cnn::ProfScope ps(ctx, name, cnn::conv_flops(s));
+        hipLaunchKernelGGL(k_wgrad<G>, grid, dim3(G::T), G::LDS_BYTES, ctx->stream, s.N, s.C, s.K, s.H, s.W, s.P, s.Q,
+                           p.rows_per_split, p.total_rows, x, dy, partial);
+    }
     int st = cnn::launch_check(ctx, "wgrad");
     if (st != CNN_OK) return st;
     const size_t total = (size_t)G::RS * s.K * s.C;
     size_t g = (total + 255) / 256;
     if (g > 4096) g = 4096;
-    hipLaunchKernelGGL(k_wgrad_reduce, dim3((unsigned)g), dim3(256), 0, ctx->stream, p.nsplit * p.col_tiles, G::RS,
-                       s.K * s.C, partial, dw);
+    {
+        cnn::ProfScope ps(ctx, "k_wgrad_reduce", 0.0);
+        hipLaunchKernelGGL(k_wgrad_reduce, dim3((unsigned)g), dim3(256), 0, ctx->stream, p.nsplit * p.col_tiles, G::RS,
+                           s.K * s.C, partial, dw);
+    }
     return cnn::launch_check(ctx, "wgrad_reduce");
 }
 
