@@ -59,7 +59,8 @@ class CnnError(RuntimeError):
 
 
 def library_path():
-    return _build.LIB
+    """The in-tree library; LIBCNN_PATH points tuning runs at an alternative build of the same sources."""
+    return os.environ.get("LIBCNN_PATH") or _build.LIB
 
 
 def ensure_built():
@@ -161,6 +162,7 @@ def cnn_conv_fwd(ctx, x, w, stride=1, pad=0, out=None):
     N, Cc, H, W = x.shape
     K, C2, R, S = w.shape
     assert Cc == C2
+    ctx.reserve_for(OP_CONV_FWD, N, Cc, H, W, K, R, S, stride, pad)
     y = out if out is not None else torch.empty((N, K, out_dim(H, R, stride, pad), out_dim(W, S, stride, pad)),
                                                 dtype=torch.float32, device=x.device)
     _check(lib().cnn_conv_fwd(ctx.handle, N, Cc, H, W, K, R, S, stride, pad, _t(x), _t(w), _t(y)), ctx.handle)

@@ -36,8 +36,8 @@ def is_current():
     return os.path.exists(LIB) and os.path.getmtime(LIB) >= _deps_mtime()
 
 
-def _compile(src, force, extra):
-    obj = os.path.join(OBJ, os.path.basename(src)[:-4] + ".o")
+def _compile(src, force, extra, objdir=None):
+    obj = os.path.join(objdir or OBJ, os.path.basename(src)[:-4] + ".o")
     hdr_m = max(os.path.getmtime(HEADER), os.path.getmtime(os.path.join(CSRC, "common.h")))
     if not force and os.path.exists(obj) and os.path.getmtime(obj) >= max(os.path.getmtime(src), hdr_m):
         return obj
@@ -45,12 +45,13 @@ def _compile(src, force, extra):
     return obj
 
 
-def build(force=False, extra=(), jobs=4):
-    os.makedirs(OBJ, exist_ok=True)
+def build(force=False, extra=(), jobs=4, out=None, objdir=None):
+    """out / objdir: build a variant (extra -D flags) somewhere else without touching the in-tree library."""
+    os.makedirs(objdir or OBJ, exist_ok=True)
     with ThreadPoolExecutor(max_workers=jobs) as ex:
-        objs = list(ex.map(lambda s: _compile(s, force, list(extra)), sources()))
-    subprocess.run(["hipcc", "--offload-arch=gfx950", "-shared", "-fPIC", "-o", LIB, *objs], check=True)
-    return LIB
+        objs = list(ex.map(lambda s: _compile(s, force, list(extra), objdir), sources()))
+    subprocess.run(["hipcc", "--offload-arch=gfx950", "-shared", "-fPIC", "-o", out or LIB, *objs], check=True)
+    return out or LIB
 
 
 if __name__ == "__main__":

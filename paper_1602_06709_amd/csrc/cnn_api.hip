@@ -129,8 +129,12 @@ size_t cnn_workspace_bytes(int op, int N, int C, int H, int W, int K, int R, int
     ConvShape s;
     if (make_shape(N, C, H, W, K, R, S, stride, pad, &s) != CNN_OK) return 0;
     switch (op) {
+        case CNN_OP_CONV_FWD: return cnn::mfma_conv_fwd_ws(s);
         case CNN_OP_CONV_BWD_DATA: return cnn::mfma_conv_bwd_data_ws(s);
-        case CNN_OP_CONV_BWD_WEIGHT: return cnn::mfma_conv_bwd_weight_ws(s);
+        case CNN_OP_CONV_BWD_WEIGHT: {
+            const size_t a = cnn::mfma_conv_bwd_weight_ws(s);
+            return a ? a : cnn::smallc_conv_bwd_weight_ws(s);
+        }
         case CNN_OP_FC_FWD: return cnn::mfma_gemm_ws(N, K, C);
         case CNN_OP_FC_BWD: {
             const size_t a = cnn::mfma_gemm_ws(N, C, K), b = cnn::mfma_gemm_ws(K, C, N);
@@ -174,6 +178,8 @@ int cnn_conv_bwd_weight(cnn_ctx* ctx, int N, int C, int H, int W, int K, int R, 
     if (st != CNN_OK) return st;
     if (!ctx->force_direct) {
         st = cnn::mfma_conv_bwd_weight(ctx, s, x, dy, dw);
+        if (st != CNN_EUNSUPPORTED) return st;
+        st = cnn::smallc_conv_bwd_weight(ctx, s, x, dy, dw);
         if (st != CNN_EUNSUPPORTED) return st;
     }
     return cnn::direct_conv_bwd_weight(ctx, s, x, dy, dw);

@@ -62,6 +62,10 @@ int mfma_conv_bwd_data(cnn_ctx*, const ConvShape&, const float* dy, const float*
 int mfma_conv_bwd_weight(cnn_ctx*, const ConvShape&, const float* x, const float* dy, float* dw);
 size_t mfma_conv_bwd_weight_ws(const ConvShape&);
 size_t mfma_conv_bwd_data_ws(const ConvShape&);
+size_t mfma_conv_fwd_ws(const ConvShape&);
+// few input feature maps (first layers), any kernel size / stride
+int smallc_conv_bwd_weight(cnn_ctx*, const ConvShape&, const float* x, const float* dy, float* dw);
+size_t smallc_conv_bwd_weight_ws(const ConvShape&);
 
 // C[M][Nn] = op(A) * op(B); row-major operands.
 //   a_kmajor == 0: A is [M][Kd] (contraction index contiguous);  != 0: A is [Kd][M]

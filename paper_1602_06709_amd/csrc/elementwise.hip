@@ -13,46 +13,43 @@ inline unsigned stream_grid(size_t work_items, int per_block) {
 }
 
 // ---------------------------------------------------------------- SGD
-// v <- mu*v + g ; w <- w - lr*v.  16-byte accesses, four independent vectors in flight per thread.
+// v <- mu*v + g ; w <- w - lr*v.  Each workgroup owns contiguous chunks of 8 x 256 float4 per array: all 24
+// loads of a chunk are issued before the first store (long read bursts, then long write bursts), g is read and
+// w, v are written with non-temporal hints (nothing here is reused before it leaves the caches).
+typedef float v4f __attribute__((ext_vector_type(4)));
+constexpr int kSgdU = 8;
+
 template <bool MOMENTUM>
-__global__ void __launch_bounds__(kBlock) k_sgd(size_t n4, size_t n, float4* __restrict__ w,
-                                               const float4* __restrict__ g, float4* __restrict__ v,
-                                               float lr, float mu) {
-    const size_t stride = (size_t)gridDim.x * kBlock;
-    size_t i = blockIdx.x * (size_t)kBlock + threadIdx.x;
-    for (; i + 3 * stride < n4; i += 4 * stride) {
-        float4 wv[4], gv[4], vv[4];
+__global__ void __launch_bounds__(kBlock) k_sgd(size_t n4, size_t n, v4f* __restrict__ w, const v4f* __restrict__ g,
+                                               v4f* __restrict__ v, float lr, float mu) {
+    const size_t per_block = (size_t)kSgdU * kBlock;
+    for (size_t base = blockIdx.x * per_block; base < n4; base += (size_t)gridDim.x * per_block) {
+        v4f wv[kSgdU], gv[kSgdU], vv[kSgdU];
 #pragma unroll
-        for (int u = 0; u < 4; ++u) {
-            wv[u] = w[i + u * stride];
-            gv[u] = g[i + u * stride];
-            if (MOMENTUM) vv[u] = v[i + u * stride];
-        }
-#pragma unroll
-        for (int u = 0; u < 4; ++u) {
-            float4 vel = gv[u];
-            if (MOMENTUM) {
-                vel.x = fmaf(mu, vv[u].x, gv[u].x); vel.y = fmaf(mu, vv[u].y, gv[u].y);
-                vel.z = fmaf(mu, vv[u].z, gv[u].z); vel.w = fmaf(mu, vv[u].w, gv[u].w);
-                v[i + u * stride] = vel;
+        for (int u = 0; u < kSgdU; ++u) {
+            const size_t i = base + u * kBlock + threadIdx.x;
+            if (i < n4) {
+                wv[u] = w[i];
+                gv[u] = __builtin_nontemporal_load(&g[i]);
+                if (MOMENTUM) vv[u] = v[i];
             }
-            float4 o;
-            o.x = fmaf(-lr, vel.x, wv[u].x); o.y = fmaf(-lr, vel.y, wv[u].y);
-            o.z = fmaf(-lr, vel.z, wv[u].z); o.w = fmaf(-lr, vel.w, wv[u].w);
-            w[i + u * stride] = o;
         }
-    }
-    for (; i < n4; i += stride) {
-        float4 wv = w[i], vel = g[i];
-        if (MOMENTUM) {
-            const float4 vv = v[i];
-            vel.x = fmaf(mu, vv.x, vel.x); vel.y = fmaf(mu, vv.y, vel.y);
-            vel.z = fmaf(mu, vv.z, vel.z); vel.w = fmaf(mu, vv.w, vel.w);
-            v[i] = vel;
+#pragma unroll
+        for (int u = 0; u < kSgdU; ++u) {
+            const size_t i = base + u * kBlock + threadIdx.x;
+            if (i < n4) {
+                v4f vel = gv[u];
+                if (MOMENTUM) {
+                    vel.x = fmaf(mu, vv[u].x, gv[u].x); vel.y = fmaf(mu, vv[u].y, gv[u].y);
+                    vel.z = fmaf(mu, vv[u].z, gv[u].z); vel.w = fmaf(mu, vv[u].w, gv[u].w);
+                    __builtin_nontemporal_store(vel, &v[i]);
+                }
+                v4f o;
+                o.x = fmaf(-lr, vel.x, wv[u].x); o.y = fmaf(-lr, vel.y, wv[u].y);
+                o.z = fmaf(-lr, vel.z, wv[u].z); o.w = fmaf(-lr, vel.w, wv[u].w);
+                __builtin_nontemporal_store(o, &w[i]);
+            }
         }
-        wv.x = fmaf(-lr, vel.x, wv.x); wv.y = fmaf(-lr, vel.y, wv.y);
-        wv.z = fmaf(-lr, vel.z, wv.z); wv.w = fmaf(-lr, vel.w, wv.w);
-        w[i] = wv;
     }
     // scalar tail (n not a multiple of 4)
     if (blockIdx.x == 0 && threadIdx.x < (n & 3)) {
@@ -257,16 +254,15 @@ int cnn_sgd_update(cnn_ctx* ctx, size_t n, float* w, const float* dw, float* v, 
     if (!ctx || !w || !dw || n == 0) return CNN_EINVAL;
     if (!aligned16(w) || !aligned16(dw) || (v && !aligned16(v))) return CNN_EINVAL;
     const size_t n4 = n >> 2;
-    const unsigned grid = stream_grid(n4, kBlock * 4);
+    const unsigned grid = stream_grid(n4, kBlock * kSgdU);
     cnn::ProfScope ps(ctx, v ? "k_sgd<momentum>" : "k_sgd<plain>", 0.0);
     if (v)
         hipLaunchKernelGGL(k_sgd<true>, dim3(grid), dim3(kBlock), 0, ctx->stream, n4, n,
-                           reinterpret_cast<float4*>(w), reinterpret_cast<const float4*>(dw),
-                           reinterpret_cast<float4*>(v), lr, momentum);
+                           reinterpret_cast<v4f*>(w), reinterpret_cast<const v4f*>(dw), reinterpret_cast<v4f*>(v), lr,
+                           momentum);
     else
         hipLaunchKernelGGL(k_sgd<false>, dim3(grid), dim3(kBlock), 0, ctx->stream, n4, n,
-                           reinterpret_cast<float4*>(w), reinterpret_cast<const float4*>(dw),
-                           (float4*)nullptr, lr, 0.f);
+                           reinterpret_cast<v4f*>(w), reinterpret_cast<const v4f*>(dw), (v4f*)nullptr, lr, 0.f);
     return cnn::launch_check(ctx, "sgd_update");
 }
 

@@ -70,7 +70,10 @@ def test_workspace_planning(L):
     ws = L.cnn_workspace_bytes
     # forward never needs scratch; unknown shapes need none (they run on the plain kernels)
     assert ws(binding.OP_CONV_FWD, 64, 256, 56, 56, 256, 3, 3, 1, 1) == 0
-    assert ws(binding.OP_CONV_BWD_WEIGHT, 2, 3, 32, 32, 16, 3, 3, 1, 1) == 0
+    assert ws(binding.OP_CONV_BWD_WEIGHT, 2, 5, 9, 13, 7, 3, 2, 2, 1) == 0
+    # first-layer weight gradient: private copies of dw, one per split of the minibatch's rows
+    b = ws(binding.OP_CONV_BWD_WEIGHT, 2, 3, 32, 32, 16, 3, 3, 1, 1)
+    assert b > 0 and b % (16 * 3 * 9 * 4) == 0
     # backpropagation keeps one mirrored transpose of the weights
     assert ws(binding.OP_CONV_BWD_DATA, 64, 256, 56, 56, 256, 3, 3, 1, 1) == 256 * 256 * 9 * 4
     # weight gradient: a whole number of private copies of dw

@@ -90,7 +90,9 @@ def test_conv_three_passes_tiled_geometries(cnn, ctx, case):
 def test_conv_generic_shapes_fall_back_and_match(cnn, ctx):
     # strides, rectangular images, 11x11/4 and 1x1: served by whichever kernel applies
     for (N, C, H, W, K, R, S, st, pad) in [(2, 3, 39, 39, 8, 11, 11, 4, 0), (1, 5, 9, 13, 7, 3, 2, 2, 1),
-                                           (2, 4, 6, 6, 4, 1, 1, 1, 0), (1, 3, 224, 224, 8, 3, 3, 1, 1)]:
+                                           (2, 4, 6, 6, 4, 1, 1, 1, 0), (1, 3, 224, 224, 8, 3, 3, 1, 1),
+                                           (2, 3, 224, 224, 64, 3, 3, 1, 1), (3, 3, 231, 231, 96, 11, 11, 4, 0),
+                                           (2, 3, 30, 30, 40, 3, 3, 1, 1), (1, 3, 24, 36, 20, 3, 3, 1, 0)]:
         say("generic conv", (N, C, H, W, K, R, S, st, pad))
         x = synth.randn(91, 1, (N, C, H, W)); w = synth.randn(91, 2, (K, C, R, S))
         y = cnn.cnn_conv_fwd(ctx, dev(x), dev(w), st, pad)
