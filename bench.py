@@ -37,6 +37,10 @@ def main():
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-profile", action="store_true", help="leave the per-kernel events out of the timed region")
     ap.add_argument("--per-kernel", action="store_true", help="print the per-kernel table to stderr")
+    ap.add_argument("--calibrate-copy", action="store_true",
+                    help="instead of the benchmark: three plain 1 GiB device-to-device copies (libcnn's identity "
+                         "re-layout, SW=1), the known-size kernel that rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE "
+                         "readings are scaled by")
     args = ap.parse_args()
     if args.gpus != 1 or int(os.environ.get("WORLD_SIZE", "1")) != 1:
         print("bench.py: this build measures one GPU's share of the minibatch only; "
@@ -51,6 +55,17 @@ def main():
 
     cnn.ensure_built()
     torch.cuda.set_device(0)
+    if args.calibrate_copy:
+        ctx = cnn.Context()
+        n = 1 << 28                                   # 2^28 floats = 1 GiB read + 1 GiB written per launch
+        src = torch.ones((1, n // 4096, 64, 64), dtype=torch.float32, device="cuda")
+        for _ in range(3):
+            dst = cnn.cnn_pack_act(ctx, src, 1)       # SW = 1: the identity permutation, a plain copy
+        torch.cuda.synchronize()
+        assert bool((dst.view(-1)[:: 1 << 20] == 1).all())
+        print(json.dumps({"calibrate_copy": {"kernel": "k_pack_blocked", "launches": 3, "bytes_read_per_launch": 4 * n,
+                                             "bytes_written_per_launch": 4 * n}}))
+        return
     wl = synth.workload(args.config, args.batch)
     N = wl.input_shape[0]
     ctx = cnn.Context()

@@ -99,6 +99,16 @@ int cnn_conv_fwd(cnn_ctx* ctx, int N, int C, int H, int W, int K, int R, int S, 
 int cnn_conv_bwd_data(cnn_ctx* ctx, int N, int C, int H, int W, int K, int R, int S, int stride, int pad,
                       const float* dy, const float* w, float* dx);
 
+/* ---- The same two passes with the neighbouring ReLU folded into the store (saves one pass over the tensor each):
+ *   cnn_conv_fwd_relu:       a = max(conv_fwd(x, w), 0)
+ *   cnn_conv_bwd_data_relu:  dz = conv_bwd_data(dy, w) where x_act > 0, else 0.  x_act (N*C*H*W) is this layer's
+ *                            forward input when that input is a ReLU output, so dz is the gradient in front of
+ *                            that ReLU (ReLU'(0) = 0).  Same workspace needs as the plain calls. */
+int cnn_conv_fwd_relu(cnn_ctx* ctx, int N, int C, int H, int W, int K, int R, int S, int stride, int pad,
+                      const float* x, const float* w, float* a);
+int cnn_conv_bwd_data_relu(cnn_ctx* ctx, int N, int C, int H, int W, int K, int R, int S, int stride, int pad,
+                           const float* dy, const float* w, const float* x_act, float* dz);
+
 /* ---- Section 2.1 "Weight-gradient Update", summed over the per-GPU minibatch (no 1/N):
  *   dw[k][c][r][s] = sum_{n,p,q} x[n][c][p*stride + r - pad][q*stride + s - pad] * dy[n][k][p][q]
  *   x, dy in; dw: K*C*R*S out.  Needs workspace (partial sums of the split contraction,
@@ -141,6 +151,10 @@ int cnn_relu_fwd(cnn_ctx* ctx, size_t n, const float* z, float* a);
 int cnn_relu_bwd(cnn_ctx* ctx, size_t n, const float* z, const float* da, float* dz);
 int cnn_maxpool2_fwd(cnn_ctx* ctx, size_t planes, int H, int W, const float* x, float* y, uint8_t* arg);
 int cnn_maxpool2_bwd(cnn_ctx* ctx, size_t planes, int H, int W, const float* dy, const uint8_t* arg, float* dx);
+/* cnn_maxpool2_bwd followed by cnn_relu_bwd in one pass, for a pool that directly follows a ReLU: y is the pool's
+ * forward output (so y > 0 exactly where the ReLU input at the argmax was positive); dz is [planes][H][W]. */
+int cnn_maxpool2_relu_bwd(cnn_ctx* ctx, size_t planes, int H, int W, const float* dy, const uint8_t* arg,
+                          const float* y, float* dz);
 int cnn_sigmoid_fwd(cnn_ctx* ctx, size_t n, const float* z, float* a);
 int cnn_sigmoid_bwd(cnn_ctx* ctx, size_t n, const float* a, const float* da, float* dz);
 int cnn_softmax_xent(cnn_ctx* ctx, int N, int O, const float* z, const int32_t* label,

@@ -35,6 +35,9 @@ SIGNATURES = {
     "cnn_conv_fwd": (_i, _CONV),
     "cnn_conv_bwd_data": (_i, _CONV),
     "cnn_conv_bwd_weight": (_i, _CONV),
+    "cnn_conv_fwd_relu": (_i, _CONV),
+    "cnn_conv_bwd_data_relu": (_i, [_vp] + [_i] * 9 + [_vp] * 4),
+    "cnn_maxpool2_relu_bwd": (_i, [_vp, _sz, _i, _i, _vp, _vp, _vp, _vp]),
     "cnn_fc_fwd": (_i, [_vp, _i, _i, _i, _vp, _vp, _vp]),
     "cnn_fc_bwd": (_i, [_vp, _i, _i, _i, _vp, _vp, _vp, _vp, _vp]),
     "cnn_sgd_update": (_i, [_vp, _sz, _vp, _vp, _vp, _f, _f]),
@@ -158,24 +161,38 @@ class Context:
 
 
 # ---------------------------------------------------------------- contractions
-def cnn_conv_fwd(ctx, x, w, stride=1, pad=0, out=None):
+def cnn_conv_fwd(ctx, x, w, stride=1, pad=0, out=None, relu=False):
     N, Cc, H, W = x.shape
     K, C2, R, S = w.shape
     assert Cc == C2
     ctx.reserve_for(OP_CONV_FWD, N, Cc, H, W, K, R, S, stride, pad)
     y = out if out is not None else torch.empty((N, K, out_dim(H, R, stride, pad), out_dim(W, S, stride, pad)),
                                                 dtype=torch.float32, device=x.device)
-    _check(lib().cnn_conv_fwd(ctx.handle, N, Cc, H, W, K, R, S, stride, pad, _t(x), _t(w), _t(y)), ctx.handle)
+    fn = lib().cnn_conv_fwd_relu if relu else lib().cnn_conv_fwd
+    _check(fn(ctx.handle, N, Cc, H, W, K, R, S, stride, pad, _t(x), _t(w), _t(y)), ctx.handle)
     return y
 
 
-def cnn_conv_bwd_data(ctx, dy, w, H, W, stride=1, pad=0, out=None):
+def cnn_conv_fwd_relu(ctx, x, w, stride=1, pad=0, out=None):
+    return cnn_conv_fwd(ctx, x, w, stride, pad, out, relu=True)
+
+
+def cnn_conv_bwd_data_relu(ctx, dy, w, x_act, stride=1, pad=0, out=None):
+    return cnn_conv_bwd_data(ctx, dy, w, x_act.shape[2], x_act.shape[3], stride, pad, out, x_act=x_act)
+
+
+def cnn_conv_bwd_data(ctx, dy, w, H, W, stride=1, pad=0, out=None, x_act=None):
     K, Cc, R, S = w.shape
     N = dy.shape[0]
     assert tuple(dy.shape) == (N, K, out_dim(H, R, stride, pad), out_dim(W, S, stride, pad))
     ctx.reserve_for(OP_CONV_BWD_DATA, N, Cc, H, W, K, R, S, stride, pad)
     dx = out if out is not None else torch.empty((N, Cc, H, W), dtype=torch.float32, device=dy.device)
-    _check(lib().cnn_conv_bwd_data(ctx.handle, N, Cc, H, W, K, R, S, stride, pad, _t(dy), _t(w), _t(dx)), ctx.handle)
+    if x_act is None:
+        _check(lib().cnn_conv_bwd_data(ctx.handle, N, Cc, H, W, K, R, S, stride, pad, _t(dy), _t(w), _t(dx)), ctx.handle)
+    else:
+        assert tuple(x_act.shape) == (N, Cc, H, W)
+        _check(lib().cnn_conv_bwd_data_relu(ctx.handle, N, Cc, H, W, K, R, S, stride, pad, _t(dy), _t(w), _t(x_act),
+                                            _t(dx)), ctx.handle)
     return dx
 
 
@@ -281,6 +298,13 @@ def cnn_maxpool2_bwd(ctx, dy, arg, H, W, out=None):
     dx = out if out is not None else torch.empty((N, Cc, H, W), dtype=torch.float32, device=dy.device)
     _check(lib().cnn_maxpool2_bwd(ctx.handle, N * Cc, H, W, _t(dy), _t(arg, torch.uint8), _t(dx)), ctx.handle)
     return dx
+
+
+def cnn_maxpool2_relu_bwd(ctx, dy, arg, y, H, W, out=None):
+    N, Cc = dy.shape[:2]
+    dz = out if out is not None else torch.empty((N, Cc, H, W), dtype=torch.float32, device=dy.device)
+    _check(lib().cnn_maxpool2_relu_bwd(ctx.handle, N * Cc, H, W, _t(dy), _t(arg, torch.uint8), _t(y), _t(dz)), ctx.handle)
+    return dz
 
 
 def cnn_sigmoid_fwd(ctx, z, out=None):

@@ -144,30 +144,47 @@ size_t cnn_workspace_bytes(int op, int N, int C, int H, int W, int K, int R, int
     }
 }
 
-int cnn_conv_fwd(cnn_ctx* ctx, int N, int C, int H, int W, int K, int R, int S, int stride, int pad,
-                 const float* x, const float* w, float* y) {
+static int conv_fwd_impl(cnn_ctx* ctx, int N, int C, int H, int W, int K, int R, int S, int stride, int pad,
+                         const float* x, const float* w, float* y, int relu) {
     if (!ctx || !x || !w || !y || !aligned16(x) || !aligned16(w) || !aligned16(y)) return CNN_EINVAL;
     ConvShape s;
     int st = make_shape(N, C, H, W, K, R, S, stride, pad, &s);
     if (st != CNN_OK) return st;
     if (!ctx->force_direct) {
-        st = cnn::mfma_conv_fwd(ctx, s, x, w, y);
+        st = cnn::mfma_conv_fwd(ctx, s, x, w, y, relu);
         if (st != CNN_EUNSUPPORTED) return st;
     }
-    return cnn::direct_conv_fwd(ctx, s, x, w, y);
+    return cnn::direct_conv_fwd(ctx, s, x, w, y, relu);
+}
+int cnn_conv_fwd(cnn_ctx* ctx, int N, int C, int H, int W, int K, int R, int S, int stride, int pad,
+                 const float* x, const float* w, float* y) {
+    return conv_fwd_impl(ctx, N, C, H, W, K, R, S, stride, pad, x, w, y, 0);
+}
+int cnn_conv_fwd_relu(cnn_ctx* ctx, int N, int C, int H, int W, int K, int R, int S, int stride, int pad,
+                      const float* x, const float* w, float* a) {
+    return conv_fwd_impl(ctx, N, C, H, W, K, R, S, stride, pad, x, w, a, 1);
 }
 
-int cnn_conv_bwd_data(cnn_ctx* ctx, int N, int C, int H, int W, int K, int R, int S, int stride, int pad,
-                      const float* dy, const float* w, float* dx) {
+static int conv_bwd_data_impl(cnn_ctx* ctx, int N, int C, int H, int W, int K, int R, int S, int stride, int pad,
+                              const float* dy, const float* w, const float* act, float* dx) {
     if (!ctx || !dy || !w || !dx || !aligned16(dy) || !aligned16(w) || !aligned16(dx)) return CNN_EINVAL;
     ConvShape s;
     int st = make_shape(N, C, H, W, K, R, S, stride, pad, &s);
     if (st != CNN_OK) return st;
     if (!ctx->force_direct) {
-        st = cnn::mfma_conv_bwd_data(ctx, s, dy, w, dx);
+        st = cnn::mfma_conv_bwd_data(ctx, s, dy, w, dx, act);
         if (st != CNN_EUNSUPPORTED) return st;
     }
-    return cnn::direct_conv_bwd_data(ctx, s, dy, w, dx);
+    return cnn::direct_conv_bwd_data(ctx, s, dy, w, dx, act);
+}
+int cnn_conv_bwd_data(cnn_ctx* ctx, int N, int C, int H, int W, int K, int R, int S, int stride, int pad,
+                      const float* dy, const float* w, float* dx) {
+    return conv_bwd_data_impl(ctx, N, C, H, W, K, R, S, stride, pad, dy, w, nullptr, dx);
+}
+int cnn_conv_bwd_data_relu(cnn_ctx* ctx, int N, int C, int H, int W, int K, int R, int S, int stride, int pad,
+                           const float* dy, const float* w, const float* x_act, float* dz) {
+    if (!x_act || !aligned16(x_act)) return CNN_EINVAL;
+    return conv_bwd_data_impl(ctx, N, C, H, W, K, R, S, stride, pad, dy, w, x_act, dz);
 }
 
 int cnn_conv_bwd_weight(cnn_ctx* ctx, int N, int C, int H, int W, int K, int R, int S, int stride, int pad,
@@ -195,7 +212,7 @@ int cnn_fc_fwd(cnn_ctx* ctx, int N, int I, int O, const float* x, const float* w
         st = cnn::mfma_gemm(ctx, N, O, I, x, 0, w, 0, y);   // y[n][o] = sum_i x[n][i] w[o][i]
         if (st != CNN_EUNSUPPORTED) return st;
     }
-    return cnn::direct_conv_fwd(ctx, s, x, w, y);
+    return cnn::direct_conv_fwd(ctx, s, x, w, y, 0);
 }
 
 int cnn_fc_bwd(cnn_ctx* ctx, int N, int I, int O, const float* x, const float* w, const float* dy, float* dx,
@@ -215,7 +232,7 @@ int cnn_fc_bwd(cnn_ctx* ctx, int N, int I, int O, const float* x, const float* w
     if (dx) {
         st = CNN_EUNSUPPORTED;
         if (!ctx->force_direct) st = cnn::mfma_gemm(ctx, N, I, O, dy, 0, w, 1, dx);   // dx[n][i] = sum_o dy[n][o] w[o][i]
-        if (st == CNN_EUNSUPPORTED) st = cnn::direct_conv_bwd_data(ctx, s, dy, w, dx);
+        if (st == CNN_EUNSUPPORTED) st = cnn::direct_conv_bwd_data(ctx, s, dy, w, dx, nullptr);
         if (st != CNN_OK) return st;
     }
     return CNN_OK;

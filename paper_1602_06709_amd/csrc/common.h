@@ -52,13 +52,13 @@ int hip_check(cnn_ctx* ctx, hipError_t e, const char* what);   // records text, 
 int launch_check(cnn_ctx* ctx, const char* what);              // hipGetLastError after a launch
 
 // ---- plain one-thread-per-output kernels: any shape, slow; the fallback of every contraction
-int direct_conv_fwd(cnn_ctx*, const ConvShape&, const float* x, const float* w, float* y);
-int direct_conv_bwd_data(cnn_ctx*, const ConvShape&, const float* dy, const float* w, float* dx);
+int direct_conv_fwd(cnn_ctx*, const ConvShape&, const float* x, const float* w, float* y, int relu);
+int direct_conv_bwd_data(cnn_ctx*, const ConvShape&, const float* dy, const float* w, float* dx, const float* act);
 int direct_conv_bwd_weight(cnn_ctx*, const ConvShape&, const float* x, const float* dy, float* dw);
 
 // ---- MFMA paths; each returns CNN_EUNSUPPORTED (without launching) for shapes it does not cover
-int mfma_conv_fwd(cnn_ctx*, const ConvShape&, const float* x, const float* w, float* y);
-int mfma_conv_bwd_data(cnn_ctx*, const ConvShape&, const float* dy, const float* w, float* dx);
+int mfma_conv_fwd(cnn_ctx*, const ConvShape&, const float* x, const float* w, float* y, int relu);
+int mfma_conv_bwd_data(cnn_ctx*, const ConvShape&, const float* dy, const float* w, float* dx, const float* act);
 int mfma_conv_bwd_weight(cnn_ctx*, const ConvShape&, const float* x, const float* dy, float* dw);
 size_t mfma_conv_bwd_weight_ws(const ConvShape&);
 size_t mfma_conv_bwd_data_ws(const ConvShape&);

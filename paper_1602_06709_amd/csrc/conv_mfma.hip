@@ -25,6 +25,9 @@ namespace {
 
 typedef float f32x16 __attribute__((ext_vector_type(16)));
 
+// epilogues: plain store; ReLU of the result; result where aux > 0 else 0 (ReLU derivative, aux = the ReLU's output)
+enum { EPI_NONE = 0, EPI_RELU = 1, EPI_MASK = 2 };
+
 // VEC = 4: filter rows are fetched as float4 (needs J % CB == 0 and 16-byte aligned rows); VEC = 1: element-wise
 // fetch with the channels past J zero-filled (first layers: J = 3).
 template <int R_, int S_, int PADE_, int CB_, int WM_, int WN_, int NT_, int NB_, int TH_, int WI_, int VEC_ = 4>
@@ -63,8 +66,9 @@ struct ConvCfg {
 
 template <class G>
 __global__ void __launch_bounds__(G::T, 2)
-k_conv_s1(int N, int J, int M, int HI, int HO, int row_tiles, int chunks_per_split,
-          const float* __restrict__ in, const float* __restrict__ wt, float* __restrict__ out_base) {
+k_conv_s1(int N, int J, int M, int HI, int HO, int row_tiles, int chunks_per_split, int epi,
+          const float* __restrict__ in, const float* __restrict__ wt, const float* __restrict__ aux,
+          float* __restrict__ out_base) {
     constexpr int R = G::R, S = G::S, RS = G::RS, CB = G::CB, NT = G::NT, T = G::T;
     extern __shared__ float lds[];
     float* wl = lds;
@@ -75,8 +79,15 @@ k_conv_s1(int N, int J, int M, int HI, int HO, int row_tiles, int chunks_per_spl
     const int half = lane >> 5, l32 = lane & 31;
     const int wm = wave % G::WM, wn = wave / G::WM;
 
-    const int ptile = blockIdx.x;
-    const int m0 = blockIdx.y * G::MB;
+    // Workgroups are handed to the 8 XCDs round-robin by linear id.  Give each XCD (its own L2) a contiguous range
+    // of pixel tiles and run the output-feature tiles of one pixel tile back to back on it, so the input tile, and
+    // the halo rows it shares with the next tile, come from HBM once instead of once per feature tile.
+    const int ptiles = row_tiles * ((N + G::NB - 1) / G::NB), mtiles = (M + G::MB - 1) / G::MB;
+    const int per_xcd = (ptiles + 7) / 8;
+    const int xcd = blockIdx.x & 7, seq = blockIdx.x >> 3;
+    const int ptile = xcd * per_xcd + seq / mtiles;
+    if (seq / mtiles >= per_xcd || ptile >= ptiles) return;      // whole workgroup leaves: no barrier is left behind
+    const int m0 = (seq % mtiles) * G::MB;
     const int n0 = (ptile / row_tiles) * G::NB;
     const int p0 = (ptile % row_tiles) * G::TH;
 
@@ -223,11 +234,17 @@ k_conv_s1(int N, int J, int M, int HI, int HO, int row_tiles, int chunks_per_spl
         const int nb = i / (G::TH * G::WO), rem = i % (G::TH * G::WO);
         const int p = p0 + rem / G::WO, q = rem % G::WO;
         if (n0 + nb >= N || p >= HO) continue;
-        float* o = out + ((size_t)(n0 + nb) * M) * out_plane + (size_t)p * G::WO + q;
+        const size_t o0 = ((size_t)(n0 + nb) * M) * out_plane + (size_t)p * G::WO + q;
+        float* o = out + o0;
 #pragma unroll
         for (int v = 0; v < 16; ++v) {
             const int m = m0 + wm * 32 + 8 * (v / 4) + 4 * half + (v % 4);
-            if (m < M) o[(size_t)m * out_plane] = acc[j][v];
+            if (m < M) {
+                float r = acc[j][v];
+                if (epi == EPI_RELU) r = r > 0.f ? r : 0.f;                                   // fused ReLU
+                else if (epi == EPI_MASK) r = aux[o0 + (size_t)m * out_plane] > 0.f ? r : 0.f;   // fused ReLU derivative
+                o[(size_t)m * out_plane] = r;
+            }
         }
     }
 }
@@ -253,8 +270,8 @@ __global__ void __launch_bounds__(256) k_transpose_flip(int K, int C, int RS, co
 }
 
 // out[i] = sum over slices of partial[slice][i], in slice order.
-__global__ void __launch_bounds__(256) k_slice_reduce(int nslice, size_t n, const float* __restrict__ partial,
-                                                     float* __restrict__ out) {
+__global__ void __launch_bounds__(256) k_slice_reduce(int nslice, size_t n, int epi, const float* __restrict__ partial,
+                                                     const float* __restrict__ aux, float* __restrict__ out) {
     for (size_t i = blockIdx.x * (size_t)256 + threadIdx.x; i < n; i += (size_t)gridDim.x * 256) {
         float s0 = 0.f, s1 = 0.f;
         int s = 0;
@@ -263,13 +280,16 @@ __global__ void __launch_bounds__(256) k_slice_reduce(int nslice, size_t n, cons
             s1 += partial[(size_t)(s + 1) * n + i];
         }
         if (s < nslice) s0 += partial[(size_t)s * n + i];
-        out[i] = s0 + s1;
+        float r = s0 + s1;
+        if (epi == EPI_RELU) r = r > 0.f ? r : 0.f;
+        else if (epi == EPI_MASK) r = aux[i] > 0.f ? r : 0.f;
+        out[i] = r;
     }
 }
 
 struct LaunchArgs {
-    int N, J, M, HI, HO, nsplit, chunks_per_split;
-    const float *in, *wt;
+    int N, J, M, HI, HO, nsplit, chunks_per_split, epi;
+    const float *in, *wt, *aux;
     float* out;       // final output, or the partial buffer when nsplit > 1
 };
 typedef int (*LaunchFn)(cnn_ctx*, const LaunchArgs&);
@@ -285,7 +305,7 @@ int launch(cnn_ctx* ctx, const LaunchArgs& a) {
     }
     const int row_tiles = (a.HO + G::TH - 1) / G::TH;
     const int img_tiles = (a.N + G::NB - 1) / G::NB;
-    dim3 grid((unsigned)(row_tiles * img_tiles), (unsigned)((a.M + G::MB - 1) / G::MB), (unsigned)a.nsplit);
+    dim3 grid((unsigned)(8 * ((row_tiles * img_tiles + 7) / 8) * ((a.M + G::MB - 1) / G::MB)), 1, (unsigned)a.nsplit);
     static char name[96] = "";
     if (!name[0])
         snprintf(name, sizeof(name), "k_conv_s1<%dx%d pad%d CB%d WM%d WN%d NT%d NB%d TH%d W%d%s>", G::R, G::S, G::PADE, G::CB,
@@ -293,7 +313,7 @@ int launch(cnn_ctx* ctx, const LaunchArgs& a) {
     {
         cnn::ProfScope ps(ctx, name, 2.0 * a.N * a.J * a.M * G::RS * a.HO * G::WO);
         hipLaunchKernelGGL(k_conv_s1<G>, grid, dim3(G::T), G::LDS_BYTES, ctx->stream, a.N, a.J, a.M, a.HI, a.HO, row_tiles,
-                           a.chunks_per_split, a.in, a.wt, a.out);
+                           a.chunks_per_split, a.epi, a.in, a.wt, a.aux, a.out);
     }
     return cnn::launch_check(ctx, "conv_s1");
 }
@@ -362,8 +382,10 @@ bool make_plan(int R, int S, int pade, int N, int J, int M, int HI, int WI, Conv
 
 // ws: scratch for the partial outputs (only touched when the plan slices the contraction)
 int run_plan(cnn_ctx* ctx, const ConvPlan& p, int N, int J, int M, int HI, int HO, int WO, const float* in, const float* wt,
-             float* out, float* ws) {
-    LaunchArgs a{N, J, M, HI, HO, p.nsplit, p.chunks_per_split, in, wt, p.nsplit > 1 ? ws : out};
+             float* out, float* ws, int epi, const float* aux) {
+    // with a sliced contraction the epilogue belongs to the kernel that adds the slices
+    LaunchArgs a{N, J, M, HI, HO, p.nsplit, p.chunks_per_split, p.nsplit > 1 ? EPI_NONE : epi, in, wt, aux,
+                 p.nsplit > 1 ? ws : out};
     int st = (p.use_small ? p.g->small : p.g->big)(ctx, a);
     if (st != CNN_OK || p.nsplit == 1) return st;
     const size_t n = (size_t)N * M * HO * WO;
@@ -371,7 +393,7 @@ int run_plan(cnn_ctx* ctx, const ConvPlan& p, int N, int J, int M, int HI, int H
     if (g > 8192) g = 8192;
     {
         cnn::ProfScope ps(ctx, "k_slice_reduce", 0.0);
-        hipLaunchKernelGGL(k_slice_reduce, dim3((unsigned)g), dim3(256), 0, ctx->stream, p.nsplit, n, ws, out);
+        hipLaunchKernelGGL(k_slice_reduce, dim3((unsigned)g), dim3(256), 0, ctx->stream, p.nsplit, n, epi, ws, aux, out);
     }
     return cnn::launch_check(ctx, "slice_reduce");
 }
@@ -386,11 +408,12 @@ size_t mfma_conv_fwd_ws(const ConvShape& s) {
     return p.partial_bytes;
 }
 
-int mfma_conv_fwd(cnn_ctx* ctx, const ConvShape& s, const float* x, const float* w, float* y) {
+int mfma_conv_fwd(cnn_ctx* ctx, const ConvShape& s, const float* x, const float* w, float* y, int relu) {
     ConvPlan p;
     if (s.stride != 1 || s.H != s.W || !make_plan(s.R, s.S, s.pad, s.N, s.C, s.K, s.H, s.W, &p)) return CNN_EUNSUPPORTED;
     if (p.partial_bytes && (!ctx->ws || ctx->ws_bytes < p.partial_bytes)) return CNN_EWORKSPACE;
-    return run_plan(ctx, p, s.N, s.C, s.K, s.H, s.P, s.Q, x, w, y, reinterpret_cast<float*>(ctx->ws));
+    return run_plan(ctx, p, s.N, s.C, s.K, s.H, s.P, s.Q, x, w, y, reinterpret_cast<float*>(ctx->ws),
+                    relu ? EPI_RELU : EPI_NONE, nullptr);
 }
 
 static bool bwd_plan(const ConvShape& s, ConvPlan* p) {
@@ -410,7 +433,8 @@ size_t mfma_conv_bwd_data_ws(const ConvShape& s) {
 }
 
 // dx = forward convolution of dy (P x Q, K channels) with the mirrored transpose-weights, pad' = R-1-pad.
-int mfma_conv_bwd_data(cnn_ctx* ctx, const ConvShape& s, const float* dy, const float* w, float* dx) {
+// act != NULL: dx is zeroed where act <= 0 (act = the ReLU output that was this layer's forward input).
+int mfma_conv_bwd_data(cnn_ctx* ctx, const ConvShape& s, const float* dy, const float* w, float* dx, const float* act) {
     ConvPlan p;
     if (!bwd_plan(s, &p)) return CNN_EUNSUPPORTED;      // decided before the workspace is touched
     if (!ctx->ws || ctx->ws_bytes < wt_bytes(s) + p.partial_bytes) return CNN_EWORKSPACE;
@@ -432,7 +456,7 @@ int mfma_conv_bwd_data(cnn_ctx* ctx, const ConvShape& s, const float* dy, const 
     }
     int st = launch_check(ctx, "transpose_flip");
     if (st != CNN_OK) return st;
-    return run_plan(ctx, p, s.N, s.K, s.C, s.P, s.H, s.W, dy, wT, dx, partial);
+    return run_plan(ctx, p, s.N, s.K, s.C, s.P, s.H, s.W, dy, wT, dx, partial, act ? EPI_MASK : EPI_NONE, act);
 }
 
 }  // namespace cnn

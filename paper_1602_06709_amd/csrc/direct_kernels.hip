@@ -4,7 +4,7 @@
 
 namespace {
 
-__global__ void k_direct_conv_fwd(ConvShape s, const float* __restrict__ x, const float* __restrict__ w,
+__global__ void k_direct_conv_fwd(ConvShape s, int relu, const float* __restrict__ x, const float* __restrict__ w,
                                   float* __restrict__ y) {
     const size_t total = (size_t)s.N * s.K * s.P * s.Q;
     for (size_t i = blockIdx.x * (size_t)blockDim.x + threadIdx.x; i < total; i += (size_t)gridDim.x * blockDim.x) {
@@ -25,12 +25,12 @@ __global__ void k_direct_conv_fwd(ConvShape s, const float* __restrict__ x, cons
                                w[(((size_t)k * s.C + c) * s.R + r) * s.S + t], acc);
                 }
             }
-        y[i] = acc;
+        y[i] = (relu && acc < 0.f) ? 0.f : acc;
     }
 }
 
 __global__ void k_direct_conv_bwd_data(ConvShape s, const float* __restrict__ dy, const float* __restrict__ w,
-                                       float* __restrict__ dx) {
+                                       const float* __restrict__ act, float* __restrict__ dx) {
     const size_t total = (size_t)s.N * s.C * s.H * s.W;
     for (size_t i = blockIdx.x * (size_t)blockDim.x + threadIdx.x; i < total; i += (size_t)gridDim.x * blockDim.x) {
         size_t f = i;
@@ -54,7 +54,7 @@ __global__ void k_direct_conv_bwd_data(ConvShape s, const float* __restrict__ dy
                                w[(((size_t)k * s.C + c) * s.R + r) * s.S + t], acc);
                 }
             }
-        dx[i] = acc;
+        dx[i] = (act && !(act[i] > 0.f)) ? 0.f : acc;
     }
 }
 
@@ -98,16 +98,16 @@ inline unsigned grid_for(size_t total, int block) {
 
 namespace cnn {
 
-int direct_conv_fwd(cnn_ctx* ctx, const ConvShape& s, const float* x, const float* w, float* y) {
+int direct_conv_fwd(cnn_ctx* ctx, const ConvShape& s, const float* x, const float* w, float* y, int relu) {
     const size_t total = (size_t)s.N * s.K * s.P * s.Q;
     ProfScope ps(ctx, "k_direct_conv_fwd", conv_flops(s));
-    hipLaunchKernelGGL(k_direct_conv_fwd, dim3(grid_for(total, 256)), dim3(256), 0, ctx->stream, s, x, w, y);
+    hipLaunchKernelGGL(k_direct_conv_fwd, dim3(grid_for(total, 256)), dim3(256), 0, ctx->stream, s, relu, x, w, y);
     return launch_check(ctx, "direct_conv_fwd");
 }
-int direct_conv_bwd_data(cnn_ctx* ctx, const ConvShape& s, const float* dy, const float* w, float* dx) {
+int direct_conv_bwd_data(cnn_ctx* ctx, const ConvShape& s, const float* dy, const float* w, float* dx, const float* act) {
     const size_t total = (size_t)s.N * s.C * s.H * s.W;
     ProfScope ps(ctx, "k_direct_conv_bwd_data", conv_flops(s));
-    hipLaunchKernelGGL(k_direct_conv_bwd_data, dim3(grid_for(total, 256)), dim3(256), 0, ctx->stream, s, dy, w, dx);
+    hipLaunchKernelGGL(k_direct_conv_bwd_data, dim3(grid_for(total, 256)), dim3(256), 0, ctx->stream, s, dy, w, act, dx);
     return launch_check(ctx, "direct_conv_bwd_data");
 }
 int direct_conv_bwd_weight(cnn_ctx* ctx, const ConvShape& s, const float* x, const float* dy, float* dw) {

@@ -154,6 +154,27 @@ __global__ void __launch_bounds__(kBlock) k_maxpool2_bwd(size_t total, int H, in
     }
 }
 
+// max-pool backward fused with the ReLU that preceded the pool: the gradient reaches the argmax position only if the
+// pooled value (= the ReLU output there) is positive.  Equals cnn_maxpool2_bwd followed by cnn_relu_bwd.
+__global__ void __launch_bounds__(kBlock) k_maxpool2_relu_bwd(size_t total, int H, int W, const float* __restrict__ dy,
+                                                             const uint8_t* __restrict__ arg,
+                                                             const float* __restrict__ y, float* __restrict__ dz) {
+    const int P = H / 2, Q = W / 2;
+    const size_t stride = (size_t)gridDim.x * kBlock;
+    for (size_t i = blockIdx.x * (size_t)kBlock + threadIdx.x; i < total; i += stride) {
+        size_t f = i;
+        const int q = f % Q; f /= Q;
+        const int p = f % P; f /= P;
+        const float g = y[i] > 0.f ? dy[i] : 0.f;
+        const int a = arg[i];
+        float2 top, bot;
+        top.x = a == 0 ? g : 0.f; top.y = a == 1 ? g : 0.f;
+        bot.x = a == 2 ? g : 0.f; bot.y = a == 3 ? g : 0.f;
+        *reinterpret_cast<float2*>(dz + (f * H + 2 * p) * W + 2 * q) = top;
+        *reinterpret_cast<float2*>(dz + (f * H + 2 * p + 1) * W + 2 * q) = bot;
+    }
+}
+
 // softmax cross-entropy: one workgroup per sample; max and sum by LDS tree reduction.
 __global__ void __launch_bounds__(kBlock) k_softmax_xent(int N, int O, const float* __restrict__ z,
                                                         const int32_t* __restrict__ label,
@@ -310,6 +331,16 @@ int cnn_maxpool2_bwd(cnn_ctx* ctx, size_t planes, int H, int W, const float* dy,
     hipLaunchKernelGGL(k_maxpool2_bwd, dim3(stream_grid(total, kBlock * 2)), dim3(kBlock), 0, ctx->stream, total, H, W,
                        dy, arg, dx);
     return cnn::launch_check(ctx, "maxpool2_bwd");
+}
+int cnn_maxpool2_relu_bwd(cnn_ctx* ctx, size_t planes, int H, int W, const float* dy, const uint8_t* arg,
+                          const float* y, float* dz) {
+    if (!ctx || !dy || !arg || !y || !dz || planes == 0 || H < 2 || W < 2 || (H & 1) || (W & 1)) return CNN_EINVAL;
+    if (reinterpret_cast<uintptr_t>(dz) & 7u) return CNN_EINVAL;
+    const size_t total = planes * (size_t)(H / 2) * (W / 2);
+    cnn::ProfScope ps(ctx, "k_maxpool2_relu_bwd", 0.0);
+    hipLaunchKernelGGL(k_maxpool2_relu_bwd, dim3(stream_grid(total, kBlock * 2)), dim3(kBlock), 0, ctx->stream, total, H,
+                       W, dy, arg, y, dz);
+    return cnn::launch_check(ctx, "maxpool2_relu_bwd");
 }
 int cnn_softmax_xent(cnn_ctx* ctx, int N, int O, const float* z, const int32_t* label, float* loss, float* dz) {
     if (!ctx || !z || !label || N <= 0 || O <= 0) return CNN_EINVAL;

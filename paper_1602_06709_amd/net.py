@@ -14,8 +14,11 @@ from . import synth
 
 
 class Net:
-    def __init__(self, ctx, wl: synth.Workload, weights=None, record=False):
-        self.ctx, self.wl, self.record = ctx, wl, record
+    def __init__(self, ctx, wl: synth.Workload, weights=None, record=False, fuse=True):
+        """fuse=True folds every ReLU that follows a convolution into the convolution's store, and its derivative
+        into the store of whatever produces the gradient in front of it (the next convolution's backpropagation or
+        the max-pool backward); fuse=False calls one entry point per layer."""
+        self.ctx, self.wl, self.record, self.fuse = ctx, wl, record, fuse
         self.layers = list(wl.layers)
         dev = torch.device("cuda")
         wshapes = synth.weight_shapes(wl)
@@ -82,13 +85,27 @@ class Net:
         return self.x if j < 0 else self.act[j]
 
     # ------------------------------------------------------------ passes
+    def _fused_relu_after(self, i):
+        """conv at i whose ReLU (i+1) is folded into its store"""
+        return (self.fuse and self.layers[i][0] == "conv" and i + 1 < len(self.layers)
+                and self.layers[i + 1][0] == "relu")
+
     def forward(self):
         ctx, wi = self.ctx, 0
+        skip = set()
         for i, L in enumerate(self.layers):
             xin, kind = self._input_of(i), L[0]
+            if i in skip:
+                continue
             if kind == "conv":
-                B.cnn_conv_fwd(ctx, xin, self.w[wi], L[5], L[6], out=self.act[i])
-                self._rec("conv_fwd", i, wi, xin, self.w[wi], self.act[i]); wi += 1
+                if self._fused_relu_after(i):
+                    B.cnn_conv_fwd_relu(ctx, xin, self.w[wi], L[5], L[6], out=self.act[i + 1])
+                    self._rec("conv_fwd_relu", i, wi, xin, self.w[wi], self.act[i + 1])
+                    skip.add(i + 1)
+                else:
+                    B.cnn_conv_fwd(ctx, xin, self.w[wi], L[5], L[6], out=self.act[i])
+                    self._rec("conv_fwd", i, wi, xin, self.w[wi], self.act[i])
+                wi += 1
             elif kind == "fc":
                 B.cnn_fc_fwd(ctx, xin, self.w[wi], out=self.act[i])
                 self._rec("fc_fwd", i, wi, xin, self.w[wi], self.act[i]); wi += 1
@@ -114,30 +131,48 @@ class Net:
         """Expects gact[-1] to hold the gradient of the last activation (from loss() or set_upstream())."""
         ctx = self.ctx
         wi = len(self.w)
+        skip = set()
         for i in range(len(self.layers) - 1, -1, -1):
             L, kind = self.layers[i], self.layers[i][0]
             xin, dy = self._input_of(i), self.gact[i]
             first = i == 0
             dxb = None if first else self.gact[i - 1]
-            if kind == "conv":
+            if kind == "conv" or kind == "fc":
                 wi -= 1
+            if i in skip:
+                continue
+            # is the input of layer i the output of a ReLU that was folded into the convolution before it?
+            relu_in = (not first) and i >= 2 and self.layers[i - 1][0] == "relu" and self._fused_relu_after(i - 2)
+            if kind == "conv":
                 B.cnn_conv_bwd_weight(ctx, xin, dy, L[3], L[4], L[5], L[6], out=self.dw[wi])
                 self._rec("conv_bwd_weight", i, wi, xin, dy, self.dw[wi])
                 if not first:
-                    B.cnn_conv_bwd_data(ctx, dy, self.w[wi], xin.shape[2], xin.shape[3], L[5], L[6], out=dxb)
-                    self._rec("conv_bwd_data", i, wi, dy, self.w[wi], dxb)
+                    if relu_in:      # gradient in front of that ReLU, straight into the earlier convolution's slot
+                        B.cnn_conv_bwd_data_relu(ctx, dy, self.w[wi], xin, L[5], L[6], out=self.gact[i - 2])
+                        self._rec("conv_bwd_data_relu", i, wi, dy, self.w[wi], xin, self.gact[i - 2])
+                        skip.add(i - 1)
+                    else:
+                        B.cnn_conv_bwd_data(ctx, dy, self.w[wi], xin.shape[2], xin.shape[3], L[5], L[6], out=dxb)
+                        self._rec("conv_bwd_data", i, wi, dy, self.w[wi], dxb)
             elif kind == "fc":
-                wi -= 1
                 B.cnn_fc_bwd(ctx, xin, self.w[wi], dy, need_dx=not first, need_dw=True,
                              dx_out=None if first else dxb.view(xin.shape), dw_out=self.dw[wi])
                 self._rec("fc_bwd", i, wi, xin, self.w[wi], dy, None if first else dxb.view(xin.shape), self.dw[wi])
             elif kind == "relu":
-                B.cnn_relu_bwd(ctx, xin, dy, out=dxb); self._rec("relu_bwd", i, xin, dy, dxb)
+                # with the forward ReLU folded into the convolution only its output exists; a > 0 <=> z > 0
+                mask = self.act[i] if (i >= 1 and self._fused_relu_after(i - 1)) else xin
+                B.cnn_relu_bwd(ctx, mask, dy, out=dxb); self._rec("relu_bwd", i, mask, dy, dxb)
             elif kind == "sigmoid":
                 B.cnn_sigmoid_bwd(ctx, self.act[i], dy, out=dxb); self._rec("sigmoid_bwd", i, self.act[i], dy, dxb)
             elif kind == "pool":
-                B.cnn_maxpool2_bwd(ctx, dy, self.arg[i], xin.shape[2], xin.shape[3], out=dxb)
-                self._rec("pool_bwd", i, dy, self.arg[i], dxb)
+                if relu_in:
+                    B.cnn_maxpool2_relu_bwd(ctx, dy, self.arg[i], self.act[i], xin.shape[2], xin.shape[3],
+                                            out=self.gact[i - 2])
+                    self._rec("pool_relu_bwd", i, dy, self.arg[i], self.act[i], self.gact[i - 2])
+                    skip.add(i - 1)
+                else:
+                    B.cnn_maxpool2_bwd(ctx, dy, self.arg[i], xin.shape[2], xin.shape[3], out=dxb)
+                    self._rec("pool_bwd", i, dy, self.arg[i], dxb)
             # flatten: nothing to do, gact[i] aliases gact[i-1]
         return None
 

@@ -62,6 +62,33 @@ def check_trace_item(item, cfg, layers, full, n_samples=20000, n_samples_wgrad=1
         idx = sample(cfg, 1000 + i, y.size, n_samples)
         ref, s = oracle.conv_fwd_at(x, w, idx, L[5], L[6])
         return check_contraction(name, y.ravel()[idx], ref, s)
+    if op == "conv_fwd_relu":
+        _, _, wi, x, w, a = item
+        x, w, a = np_(x), np_(w), np_(a)
+        if full:
+            ref, s = oracle.conv_fwd(x, w, L[5], L[6], with_abs=True)
+            return check_contraction(name, a, np.maximum(ref, 0.0), s)
+        idx = sample(cfg, 1000 + i, a.size, n_samples)
+        ref, s = oracle.conv_fwd_at(x, w, idx, L[5], L[6])
+        return check_contraction(name, a.ravel()[idx], np.maximum(ref, 0.0), s)
+    if op == "conv_bwd_data_relu":
+        _, _, wi, dy, w, xact, dz = item
+        dy, w, xact, dz = np_(dy), np_(w), np_(xact), np_(dz)
+        H, W = dz.shape[2:]
+        assert np.all(dz[xact <= 0] == 0), name + ": gradient leaked through a closed ReLU"
+        if full:
+            ref, s = oracle.conv_bwd_data(dy, w, H, W, L[5], L[6], with_abs=True)
+            return check_contraction(name, dz, np.where(xact > 0, ref, 0.0), s)
+        idx = sample(cfg, 2000 + i, dz.size, n_samples)
+        ref, s = oracle.conv_bwd_data_at(dy, w, H, W, idx, L[5], L[6])
+        return check_contraction(name, dz.ravel()[idx], np.where(xact.ravel()[idx] > 0, ref, 0.0), s)
+    if op == "pool_relu_bwd":
+        _, _, dy, arg, y, dz = item
+        H, W = dz.shape[2:]
+        dy_, y_ = np_(dy), np_(y)
+        da = oracle.maxpool2_bwd(np.where(y_ > 0, dy_, np.float32(0)), np_(arg).astype(np.int32), H, W)
+        assert np.array_equal(np_(dz).astype(np.float64), da), name
+        return 0.0
     if op == "conv_bwd_data":
         _, _, wi, dy, w, dx = item
         dy, w, dx = np_(dy), np_(w), np_(dx)

@@ -193,11 +193,11 @@ def test_argument_validation_launches_nothing(cnn, ctx):
 
 
 # ------------------------------------------------------------------ the network workloads, per call, teacher-forced
-def _run_and_check(cnn, ctx, cfg, N, full, **kw):
+def _run_and_check(cnn, ctx, cfg, N, full, fuse=True, **kw):
     from paper_1602_06709_amd.net import Net
     wl = synth.workload(cfg, N)
-    say(f"workload cfg{cfg} N={wl.input_shape[0]} full={full}")
-    net = Net(ctx, wl, synth.make_weights(wl), record=True)
+    say(f"workload cfg{cfg} N={wl.input_shape[0]} full={full} fuse={fuse}")
+    net = Net(ctx, wl, synth.make_weights(wl), record=True, fuse=fuse)
     net.set_input(synth.make_input(wl), synth.make_labels(wl) if wl.loss else None)
     net.forward()
     if wl.loss:
@@ -223,8 +223,33 @@ def _run_and_check(cnn, ctx, cfg, N, full, **kw):
     return worst
 
 
-def test_config2_vgg_a_conv_stack_n4_full_tensors(cnn, ctx):
-    _run_and_check(cnn, ctx, 2, None, True)
+@pytest.mark.parametrize("fuse", [True, False])
+def test_config2_vgg_a_conv_stack_n4_full_tensors(cnn, ctx, fuse):
+    _run_and_check(cnn, ctx, 2, None, True, fuse=fuse)
+
+
+def test_fused_relu_entry_points_equal_the_unfused_sequence(cnn, ctx):
+    # conv_fwd_relu == relu(conv_fwd); conv_bwd_data_relu == relu_bwd(x, conv_bwd_data); pool_relu_bwd == relu_bwd(pool_bwd)
+    for (N, C, H, K, R, pad) in [(3, 16, 28, 72, 3, 1), (2, 3, 224, 64, 3, 1), (5, 32, 14, 48, 3, 1), (2, 8, 28, 40, 5, 0),
+                                 (2, 5, 9, 7, 3, 1)]:
+        say("fused case", (N, C, H, K, R, pad))
+        x = np.maximum(synth.randn(97, 1, (N, C, H, H)), 0).astype(np.float32)      # a ReLU output
+        w = synth.randn(97, 2, (K, C, R, R), 0.1)
+        P_ = H + 2 * pad - R + 1
+        dy = synth.randn(97, 3, (N, K, P_, P_))
+        a = cnn.cnn_conv_fwd_relu(ctx, dev(x), dev(w), 1, pad)
+        z = cnn.cnn_conv_fwd(ctx, dev(x), dev(w), 1, pad)
+        assert torch.equal(a, cnn.cnn_relu_fwd(ctx, z))
+        dz = cnn.cnn_conv_bwd_data_relu(ctx, dev(dy), dev(w), dev(x), 1, pad)
+        dx = cnn.cnn_conv_bwd_data(ctx, dev(dy), dev(w), H, H, 1, pad)
+        assert torch.equal(dz, cnn.cnn_relu_bwd(ctx, dev(x), dx))
+        ref, s = oracle.conv_bwd_data(dy, w, H, H, 1, pad, with_abs=True)
+        P.check_contraction("dz", P.np_(dz), np.where(x > 0, ref, 0.0), s)
+    zz = synth.randn(97, 4, (3, 5, 8, 12)); zz[0, 0, :2, :2] = -1.0
+    aa = cnn.cnn_relu_fwd(ctx, dev(zz)); y, arg = cnn.cnn_maxpool2_fwd(ctx, aa)
+    g = dev(synth.randn(97, 5, tuple(y.shape)))
+    fused = cnn.cnn_maxpool2_relu_bwd(ctx, g, arg, y, 8, 12)
+    assert torch.equal(fused, cnn.cnn_relu_bwd(ctx, dev(zz), cnn.cnn_maxpool2_bwd(ctx, g, arg, 8, 12)))
 
 
 def test_config5_dnn7_n1024_sampled(cnn, ctx):
