@@ -106,6 +106,15 @@ def main():
         flops += f * (2 if first else 3)
         first = False
 
+    # ---- HBM traffic per launch of each kernel, from the committed rocprofv3 --pmc summary of this same command
+    traffic = {}
+    tpath = os.path.join(ROOT, "profiles", "vgg_a_full_n64_hbm_traffic.txt")
+    if args.config == 3 and args.batch is None and os.path.exists(tpath):
+        for line in open(tpath):
+            if line.startswith("traffic_bytes_per_launch |"):
+                _, name, val = [t.strip() for t in line.split("|")]
+                traffic[name] = int(val)
+
     # ---- per-kernel table from the library's own events
     kern = {}
     if not args.no_profile:
@@ -129,8 +138,8 @@ def main():
         if fl > 0:
             ach = fl / (ms * 1e-3) / 1e12
             roofline = {"kernel": dom["kernel"], "bound": "mfma", "achieved": ach, "peak": PEAK_FP32_MFMA_TFLOPS,
-                        "unit": "TFLOP/s", "frac": ach / PEAK_FP32_MFMA_TFLOPS, "traffic": None,
-                        "launches": cnt, "avg_launch_ms": ms / cnt, "flops_per_launch": fl / cnt,
+                        "unit": "TFLOP/s", "frac": ach / PEAK_FP32_MFMA_TFLOPS,
+                        "traffic": traffic.get(dom["kernel"]), "launches": cnt, "avg_launch_ms": ms / cnt, "flops_per_launch": fl / cnt,
                         "share_of_step": dom["share"]}
         else:
             roofline = {"kernel": dom["kernel"], "bound": "hbm", "achieved": None, "peak": PEAK_HBM_GBS, "unit": "GB/s",
