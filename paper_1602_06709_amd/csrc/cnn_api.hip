@@ -153,6 +153,8 @@ static int conv_fwd_impl(cnn_ctx* ctx, int N, int C, int H, int W, int K, int R,
     if (!ctx->force_direct) {
         st = cnn::mfma_conv_fwd(ctx, s, x, w, y, relu);
         if (st != CNN_EUNSUPPORTED) return st;
+        st = cnn::c3_strided_conv_fwd(ctx, s, x, w, y, relu);
+        if (st != CNN_EUNSUPPORTED) return st;
     }
     return cnn::direct_conv_fwd(ctx, s, x, w, y, relu);
 }

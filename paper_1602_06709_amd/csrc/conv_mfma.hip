@@ -250,21 +250,23 @@ k_conv_s1(int N, int J, int M, int HI, int HO, int row_tiles, int chunks_per_spl
 }
 
 // wT[c][k][r][s] = w[k][c][R-1-r][S-1-s]: the "transpose-weights" of Section 2.3 with the taps mirrored, so that
-// backpropagation is a forward convolution of dy with wT.  One workgroup moves a 32(k) x 32(c) block through LDS;
-// both the reads (32*RS contiguous floats per k) and the writes (32*RS per c) are coalesced.
+// backpropagation is a forward convolution of dy with wT.  One workgroup moves an 8(k) x 32(c) block through LDS;
+// the reads (32*RS contiguous floats per k) are coalesced, the writes are runs of 8*RS floats per c.
+constexpr int kTfK = 8;
 __global__ void __launch_bounds__(256) k_transpose_flip(int K, int C, int RS, const float* __restrict__ w,
                                                        float* __restrict__ wT) {
-    extern __shared__ float tl[];               // [32 k][32*RS + 1]
-    const int k0 = blockIdx.x * 32, c0 = blockIdx.y * 32;
+    extern __shared__ float tl[];               // [kTfK][32*RS + 1]
+    const int k0 = blockIdx.x * kTfK, c0 = blockIdx.y * 32;
     const int row = 32 * RS, str = row + 1;
-    const int cn = min(32, C - c0), kn = min(32, K - k0);
-    for (int e = threadIdx.x; e < 32 * row; e += 256) {
+    const int cn = min(32, C - c0), kn = min(kTfK, K - k0);
+    for (int e = threadIdx.x; e < kTfK * row; e += 256) {
         const int k = e / row, o = e % row;
         if (k < kn && o < cn * RS) tl[k * str + o] = w[((size_t)(k0 + k) * C + c0) * RS + o];
     }
     __syncthreads();
-    for (int e = threadIdx.x; e < 32 * row; e += 256) {
-        const int c = e / row, o = e % row, k = o / RS, t = o % RS;
+    const int orow = kTfK * RS;
+    for (int e = threadIdx.x; e < 32 * orow; e += 256) {
+        const int c = e / orow, o = e % orow, k = o / RS, t = o % RS;
         if (c < cn && k < kn) wT[((size_t)(c0 + c) * K + k0) * RS + o] = tl[k * str + c * RS + (RS - 1 - t)];
     }
 }
@@ -441,8 +443,8 @@ int mfma_conv_bwd_data(cnn_ctx* ctx, const ConvShape& s, const float* dy, const 
     float* wT = reinterpret_cast<float*>(ctx->ws);
     float* partial = reinterpret_cast<float*>(reinterpret_cast<char*>(ctx->ws) + wt_bytes(s));
     const int RS = s.R * s.S;
-    dim3 grid((unsigned)((s.K + 31) / 32), (unsigned)((s.C + 31) / 32));
-    const size_t tl_bytes = (32 * (32 * RS + 1)) * sizeof(float);
+    dim3 grid((unsigned)((s.K + kTfK - 1) / kTfK), (unsigned)((s.C + 31) / 32));
+    const size_t tl_bytes = (kTfK * (32 * RS + 1)) * sizeof(float);
     static size_t tl_attr = 48 * 1024;
     if (tl_bytes > tl_attr) {
         hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(&k_transpose_flip),

@@ -234,14 +234,24 @@ Plan make_plan(const ConvShape& s) {
     const int groups = (s.N + G::NBI - 1) / G::NBI;
     p.total_rows = groups * s.P;
     const int tiles = p.ktiles * p.ctiles * p.col_tiles;
-    int want = (512 + tiles - 1) / tiles;                   // about two workgroups per compute unit
-    const int min_rows = 4 * (G::R - 1) > 8 ? 4 * (G::R - 1) : 8;   // keep ring warm-up rows a small fraction
-    int max_split = p.total_rows / min_rows;
-    if (max_split < 1) max_split = 1;
-    if (want > max_split) want = max_split;
-    if (want < 1) want = 1;
-    p.rows_per_split = (p.total_rows + want - 1) / want;
-    p.nsplit = (p.total_rows + p.rows_per_split - 1) / p.rows_per_split;
+    // Choose the number of row splits that minimises the time of the slowest compute unit, counted in steps (one
+    // output row each): a split of n rows costs n + R - 1 steps (ring warm-up), the workgroups run 256 at a time
+    // (one per compute unit, the LDS ring fills it), and every split adds one private copy of dw to write and read
+    // back (a step moves about as many bytes as 70 MB of that traffic takes).
+    const double copy_steps = (double)G::RS * s.K * s.C * 8.0 / 70e6;
+    double best = 1e30;
+    int best_split = 1;
+    for (int ns = 1; ns <= p.total_rows; ++ns) {
+        const int rps = (p.total_rows + ns - 1) / ns;
+        const int real = (p.total_rows + rps - 1) / rps;
+        if (real != ns) continue;
+        const long rounds = ((long)tiles * ns + 255) / 256;
+        const double cost = (double)rounds * (rps + G::R - 1) + copy_steps * ns;
+        if (cost < best) { best = cost; best_split = ns; }
+        if (rps == 1) break;
+    }
+    p.nsplit = best_split;
+    p.rows_per_split = (p.total_rows + best_split - 1) / best_split;
     p.ws_bytes = (size_t)p.nsplit * p.col_tiles * G::RS * s.K * s.C * sizeof(float);
     return p;
 }
