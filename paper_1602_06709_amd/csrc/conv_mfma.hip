@@ -1,22 +1,23 @@
-// Stride-1 convolution as an implicit contraction over (channel, kernel row, kernel col) on the fp32
-// matrix cores of gfx950 (v_mfma_f32_32x32x2_f32).  One kernel serves
-//   forward propagation  (Section 2.1, Algorithm 1):  out = y,  in = x,  contraction over ifm
-//   backpropagation      (Section 2.1):               out = dx, in = dy, contraction over ofm,
+// Convolution as an implicit contraction over (channel, kernel row, kernel col) on the fp32 matrix cores of gfx950
+// (v_mfma_f32_32x32x2_f32).  One kernel serves
+//   forward propagation  (Section 2.1, Algorithm 1):  out = y,  in = x,  contraction over ifm (any stride)
+//   backpropagation      (Section 2.1, stride 1):     out = dx, in = dy, contraction over ofm,
 //                                                      kernel taps mirrored, pad' = R-1-pad
 // which is the paper's remark that the passes share one loop nest and one blocking strategy.
 //
-// Tiling (per workgroup): MB = 32*WM output features x NPIX = NB*TH*WO output pixels
-// (NB images x TH full-width output rows).  Each wave owns 32 output features x NT blocks of
-// 32 pixels: NT accumulators of 16 VGPRs.  The contraction runs over chunks of CB channels:
-//   LDS  wl[MB][CB*R*S + 1]      filter tile, row stride odd  -> the 32 lanes of an A operand
-//                                (one output feature each) hit 32 different banks
-//   LDS  xl[CB][NB][TH+R-1][WI+2*PADE]   input tile with its halo, zeros where the image ends;
-//                                lanes of a B operand are consecutive pixels -> consecutive words
-// The two halves of the 64-lane wave feed k = 0 and k = 1 of the MFMA: the low half walks channels
-// [0, CB/2) of the chunk and the high half [CB/2, CB), so both halves use the same immediate offsets.
+// Tiling (per workgroup): MB = 32*WM output features x a pixel tile of NB images x TH full-width output rows
+// (at most 32*NT*WN pixels; NB, TH and all image sizes are run-time values).  Each wave owns 32 output features x NT
+// blocks of 32 pixels: NT accumulators of 16 VGPRs.  The contraction runs over chunks of CB channels:
+//   LDS  wl[MB][CB*R*S + 1]      filter tile, row stride odd  -> the 32 lanes of an A operand (one output feature
+//                                each) hit 32 different banks
+//   LDS  xl[CB][NB][rows][width] input tile with its halo, zeros where the image ends; lanes of a B operand are
+//                                consecutive pixels -> consecutive words.  Row and image strides are padded so that
+//                                this also holds across the end of a row / image (stride 1).
+// The two halves of the 64-lane wave feed k = 0 and k = 1 of the MFMA: the low half walks channels [0, CB/2) of the
+// chunk and the high half [CB/2, CB), so both halves use the same offsets.
 // Two LDS buffers: while chunk ch is multiplied, chunk ch+1 moves from registers into the other buffer and chunk
 // ch+2 from HBM into those registers, one staging item between every MFMA step (no staging phase, one barrier per
-// chunk).  LDS row / image strides are padded so that consecutive pixels stay in consecutive banks across row ends.
+// chunk).
 #include <stdio.h>
 
 #include "common.h"
@@ -28,47 +29,45 @@ typedef float f32x16 __attribute__((ext_vector_type(16)));
 // epilogues: plain store; ReLU of the result; result where aux > 0 else 0 (ReLU derivative, aux = the ReLU's output)
 enum { EPI_NONE = 0, EPI_RELU = 1, EPI_MASK = 2 };
 
+// Run-time geometry of one launch (uniform across the grid).
+struct ConvGeo {
+    int N, J, M;                   // images, contraction channels, output features
+    int HI, WI, HO, WO;            // input and output image sizes
+    int pad, stride;               // padding on the input side, stride
+    int NB, TH;                    // pixel tile: images x output rows (full width)
+    int THI, WLD;                  // staged input rows / columns per image: (TH-1)*stride + R, WI + 2*pad
+    int WLDP, IMGSTR, PLANEP;      // LDS row / image / channel strides
+    int PLANE;                     // staged elements per channel: NB * THI * WLD
+    int NPIX;                      // NB * TH * WO
+    int row_tiles, ptiles, mtiles, per_xcd;
+    int chunks_per_split, epi;
+    int lds_buf;                   // elements of one (filter tile, input tile) buffer
+};
+
 // VEC = 4: filter rows are fetched as float4 (needs J % CB == 0 and 16-byte aligned rows); VEC = 1: element-wise
-// fetch with the channels past J zero-filled (first layers: J = 3).
-template <int R_, int S_, int PADE_, int CB_, int WM_, int WN_, int NT_, int NB_, int TH_, int WI_, int VEC_ = 4>
+// fetch with the channels past J zero-filled (first layers: J = 3).  XP: input-tile positions per thread per channel.
+template <int R_, int S_, int CB_, int WM_, int WN_, int NT_, int VEC_, int XP_>
 struct ConvCfg {
-    static constexpr int R = R_, S = S_, PADE = PADE_, CB = CB_, WM = WM_, WN = WN_, NT = NT_, NB = NB_, TH = TH_, WI = WI_;
-    static constexpr int VEC = VEC_;
+    static constexpr int R = R_, S = S_, CB = CB_, WM = WM_, WN = WN_, NT = NT_, VEC = VEC_, XP = XP_;
     static constexpr int RS = R * S;
-    static constexpr int WO = WI + 2 * PADE - S + 1;
-    static constexpr int THI = TH + R - 1;
-    static constexpr int WLD = WI + 2 * PADE;
-    static constexpr int PLANE = NB * THI * WLD;            // staged elements per channel
-    // LDS strides.  Consecutive output pixels must fall into consecutive banks also across the end of a row and of
-    // an image, or every operand read that spans two rows pays a bank conflict: row stride = WO (mod 32), image
-    // stride = TH*WO (mod 32).
-    static constexpr int WLDP = WO + 32 * ((WLD - WO + 31) / 32);
-    static constexpr int IMG0 = THI * WLDP;
-    static constexpr int IMGSTR = IMG0 + ((((TH - 1) * WLDP + WO - IMG0) % 32) + 32) % 32;
-    static constexpr int PLANEP = NB * IMGSTR;               // LDS elements per channel
     static constexpr int MB = 32 * WM;
-    static constexpr int NPIX = NB * TH * WO;
-    static constexpr int NPIXB = WN * NT * 32;              // padded to whole MFMA column blocks
+    static constexpr int NPIXB = WN * NT * 32;               // pixel capacity of a tile
     static constexpr int T = WM * WN * 64;
     static constexpr int KCH = CB * RS;                      // contraction length of one chunk
     static constexpr int WSTR = (KCH % 2 == 0) ? KCH + 1 : KCH;
-    static constexpr int XTOT = CB * PLANEP;
-    static constexpr int XP = (PLANE + T - 1) / T;           // input-tile positions per thread (per channel)
     static constexpr int Q4 = KCH / VEC;                     // fetch units (float4 or float) per filter row
     static constexpr int RPP = T / Q4;                       // filter rows fetched per pass of the workgroup
     static constexpr int WSL = (MB + RPP - 1) / RPP;         // passes
-    static constexpr int LDS_BUF = MB * WSTR + XTOT;         // elements of one (filter tile, input tile) buffer
-    static constexpr int LDS_BYTES = LDS_BUF * 4 * 2;
+    static constexpr int MAXPLANE = XP * T;                  // staged elements per channel the threads can cover
     static_assert(CB % 2 == 0, "the two wave halves split the chunk's channels");
     static_assert(KCH % VEC == 0 && (VEC == 1 || VEC == 4), "filter tile is fetched as float4 or float");
-    static_assert(NPIXB >= NPIX && NPIXB - NPIX < 32 * WN, "pixel tile padded by less than one block per wave column");
+    static_assert(Q4 <= T, "one pass fetches at least one filter row");
 };
 
 template <class G>
 __global__ void __launch_bounds__(G::T, 2)
-k_conv_s1(int N, int J, int M, int HI, int HO, int row_tiles, int chunks_per_split, int epi,
-          const float* __restrict__ in, const float* __restrict__ wt, const float* __restrict__ aux,
-          float* __restrict__ out_base) {
+k_conv_tiled(ConvGeo g, const float* __restrict__ in, const float* __restrict__ wt, const float* __restrict__ aux,
+             float* __restrict__ out_base) {
     constexpr int R = G::R, S = G::S, RS = G::RS, CB = G::CB, NT = G::NT, T = G::T;
     extern __shared__ float lds[];
     float* wl = lds;
@@ -78,22 +77,21 @@ k_conv_s1(int N, int J, int M, int HI, int HO, int row_tiles, int chunks_per_spl
     const int lane = tid & 63, wave = tid >> 6;
     const int half = lane >> 5, l32 = lane & 31;
     const int wm = wave % G::WM, wn = wave / G::WM;
+    const int N = g.N, J = g.J, M = g.M;
 
     // Workgroups are handed to the 8 XCDs round-robin by linear id.  Give each XCD (its own L2) a contiguous range
     // of pixel tiles and run the output-feature tiles of one pixel tile back to back on it, so the input tile, and
     // the halo rows it shares with the next tile, come from HBM once instead of once per feature tile.
-    const int ptiles = row_tiles * ((N + G::NB - 1) / G::NB), mtiles = (M + G::MB - 1) / G::MB;
-    const int per_xcd = (ptiles + 7) / 8;
     const int xcd = blockIdx.x & 7, seq = blockIdx.x >> 3;
-    const int ptile = xcd * per_xcd + seq / mtiles;
-    if (seq / mtiles >= per_xcd || ptile >= ptiles) return;      // whole workgroup leaves: no barrier is left behind
-    const int m0 = (seq % mtiles) * G::MB;
-    const int n0 = (ptile / row_tiles) * G::NB;
-    const int p0 = (ptile % row_tiles) * G::TH;
+    const int ptile = xcd * g.per_xcd + seq / g.mtiles;
+    if (seq / g.mtiles >= g.per_xcd || ptile >= g.ptiles) return;   // whole workgroup leaves: no barrier is left behind
+    const int m0 = (seq % g.mtiles) * G::MB;
+    const int n0 = (ptile / g.row_tiles) * g.NB;
+    const int p0 = (ptile % g.row_tiles) * g.TH;
 
-    const size_t in_img = (size_t)J * HI * G::WI;      // elements per image of `in`
+    const int plane_g = g.HI * g.WI;
+    const size_t in_img = (size_t)J * plane_g;         // elements per image of `in`
     const float* in_base = in + (size_t)n0 * in_img;
-    const int plane_g = HI * G::WI;
 
     // ---- input tile staging: each thread owns XP positions of the (image, row, col) plane and fetches
     //      them for every channel of the chunk (-1 = outside the image: zero fill)
@@ -102,17 +100,18 @@ k_conv_s1(int N, int J, int M, int HI, int HO, int row_tiles, int chunks_per_spl
     for (int j = 0; j < G::XP; ++j) {
         const int e = tid + j * T;
         int off = -1, pos = 0;
-        if (e < G::PLANE) {
-            const int nb = e / (G::THI * G::WLD), rem = e % (G::THI * G::WLD);
-            const int row = rem / G::WLD, col = rem % G::WLD;
-            const int h = p0 - G::PADE + row, w = col - G::PADE;
-            pos = nb * G::IMGSTR + row * G::WLDP + col;
-            if (n0 + nb < N && h >= 0 && h < HI && w >= 0 && w < G::WI) off = nb * (int)in_img + h * G::WI + w;
+        if (e < g.PLANE) {
+            const int per_img = g.THI * g.WLD;
+            const int nb = e / per_img, rem = e % per_img;
+            const int row = rem / g.WLD, col = rem % g.WLD;
+            const int h = p0 * g.stride - g.pad + row, w = col - g.pad;
+            pos = nb * g.IMGSTR + row * g.WLDP + col;
+            if (n0 + nb < N && h >= 0 && h < g.HI && w >= 0 && w < g.WI) off = nb * (int)in_img + h * g.WI + w;
         }
         xoff[j] = off;
         xpos[j] = pos;
     }
-    // ---- filter tile staging: thread = (row m_sub, float4 kq) of a pass over RPP rows
+    // ---- filter tile staging: thread = (row m_sub, fetch unit kq) of a pass over RPP rows
     const int w_msub = tid / G::Q4, w_kq = tid % G::Q4;
     const bool w_thread = tid < G::RPP * G::Q4;
     const float* w_src = wt + ((size_t)(m0 + w_msub) * J) * RS + w_kq * G::VEC;
@@ -125,11 +124,12 @@ k_conv_s1(int N, int J, int M, int HI, int HO, int row_tiles, int chunks_per_spl
     for (int j = 0; j < NT; ++j) {
         const int i = (wn * NT + j) * 32 + l32;
         int o = 0;
-        if (i < G::NPIX) {
-            const int nb = i / (G::TH * G::WO), rem = i % (G::TH * G::WO);
-            o = nb * G::IMGSTR + (rem / G::WO) * G::WLDP + rem % G::WO;
+        if (i < g.NPIX) {
+            const int per_img = g.TH * g.WO;
+            const int nb = i / per_img, rem = i % per_img;
+            o = nb * g.IMGSTR + (rem / g.WO) * g.stride * g.WLDP + (rem % g.WO) * g.stride;
         }
-        b_base[j] = o + half * (CB / 2) * G::PLANEP;
+        b_base[j] = o + half * (CB / 2) * g.PLANEP;
     }
 
     f32x16 acc[NT];
@@ -141,8 +141,8 @@ k_conv_s1(int N, int J, int M, int HI, int HO, int row_tiles, int chunks_per_spl
     float xr[CB][G::XP];
     float4 wr[G::WSL];
 
-    // Staging is cut into items (one input-tile register or one filter-tile float4 each) so that it can be spread
-    // over the MFMA steps of a chunk instead of forming a phase of its own.
+    // Staging is cut into items (one input-tile register or one filter-tile fetch unit each) so that it can be
+    // spread over the MFMA steps of a chunk instead of forming a phase of its own.
     constexpr int NX = CB * G::XP, NITEMS = NX + G::WSL;
     auto fetch_item = [&](int it, int c0) {
         if (it < NX) {
@@ -163,11 +163,11 @@ k_conv_s1(int N, int J, int M, int HI, int HO, int row_tiles, int chunks_per_spl
     auto stage_item = [&](int it, int buf) {
         if (it < NX) {
             const int c = it / G::XP, j = it % G::XP;
-            if (tid + j * T < G::PLANE) xl[buf * G::LDS_BUF + c * G::PLANEP + xpos[j]] = xr[c][j];
+            if (tid + j * T < g.PLANE) xl[buf * g.lds_buf + c * g.PLANEP + xpos[j]] = xr[c][j];
         } else {
             const int i = it - NX;
             if (w_thread && w_msub + i * G::RPP < G::MB) {
-                float* d = w_dst + buf * G::LDS_BUF + i * G::RPP * G::WSTR;
+                float* d = w_dst + buf * g.lds_buf + i * G::RPP * G::WSTR;
                 d[0] = wr[i].x;
                 if (G::VEC == 4) { d[1] = wr[i].y; d[2] = wr[i].z; d[3] = wr[i].w; }
             }
@@ -181,9 +181,10 @@ k_conv_s1(int N, int J, int M, int HI, int HO, int row_tiles, int chunks_per_spl
     // never read), which keeps the chunk body one basic block.
     // blockIdx.z selects a slice of the contraction (used when the output alone gives too few workgroups);
     // each slice writes its own partial output, added up afterwards in slice order.
-    const int ch_begin = blockIdx.z * chunks_per_split;
-    const int ch_end = min(ch_begin + chunks_per_split, (J + CB - 1) / CB);
-    float* out = out_base + (size_t)blockIdx.z * N * M * HO * G::WO;
+    const int ch_begin = blockIdx.z * g.chunks_per_split;
+    const int ch_end = min(ch_begin + g.chunks_per_split, (J + CB - 1) / CB);
+    const size_t out_plane = (size_t)g.HO * g.WO;
+    float* out = out_base + (size_t)blockIdx.z * N * M * out_plane;
     constexpr int STEPS = (CB / 2) * RS, IPS = (NITEMS + STEPS - 1) / STEPS;
 #pragma unroll
     for (int it = 0; it < NITEMS; ++it) fetch_item(it, ch_begin * CB);
@@ -198,8 +199,8 @@ k_conv_s1(int N, int J, int M, int HI, int HO, int row_tiles, int chunks_per_spl
     for (int ch = ch_begin; ch < ch_end; ++ch) {
         const int buf = (ch - ch_begin) & 1;
         const int c2 = min(ch + 2, ch_end - 1) * CB;
-        const float* wb = wl + buf * G::LDS_BUF;
-        const float* xb = xl + buf * G::LDS_BUF;
+        const float* wb = wl + buf * g.lds_buf;
+        const float* xb = xl + buf * g.lds_buf;
 #pragma unroll
         for (int cc = 0; cc < CB / 2; ++cc)
 #pragma unroll
@@ -216,9 +217,10 @@ k_conv_s1(int N, int J, int M, int HI, int HO, int row_tiles, int chunks_per_spl
                         }
                     }
                     const float a = wb[a_base + cc * RS + r * S + s];
+                    const float* xs = xb + (cc * g.PLANEP + r * g.WLDP + s);
                     float b[NT];
 #pragma unroll
-                    for (int j = 0; j < NT; ++j) b[j] = xb[b_base[j] + cc * G::PLANEP + r * G::WLDP + s];
+                    for (int j = 0; j < NT; ++j) b[j] = xs[b_base[j]];
 #pragma unroll
                     for (int j = 0; j < NT; ++j) acc[j] = __builtin_amdgcn_mfma_f32_32x32x2f32(a, b[j], acc[j], 0, 0, 0);
                 }
@@ -226,23 +228,23 @@ k_conv_s1(int N, int J, int M, int HI, int HO, int row_tiles, int chunks_per_spl
     }
 
     // ---- epilogue: lane = pixel (coalesced along the row), register v = output feature
-    const size_t out_plane = (size_t)HO * G::WO;
 #pragma unroll
     for (int j = 0; j < NT; ++j) {
         const int i = (wn * NT + j) * 32 + l32;
-        if (i >= G::NPIX) continue;
-        const int nb = i / (G::TH * G::WO), rem = i % (G::TH * G::WO);
-        const int p = p0 + rem / G::WO, q = rem % G::WO;
-        if (n0 + nb >= N || p >= HO) continue;
-        const size_t o0 = ((size_t)(n0 + nb) * M) * out_plane + (size_t)p * G::WO + q;
+        if (i >= g.NPIX) continue;
+        const int per_img = g.TH * g.WO;
+        const int nb = i / per_img, rem = i % per_img;
+        const int p = p0 + rem / g.WO, q = rem % g.WO;
+        if (n0 + nb >= N || p >= g.HO) continue;
+        const size_t o0 = ((size_t)(n0 + nb) * M) * out_plane + (size_t)p * g.WO + q;
         float* o = out + o0;
 #pragma unroll
         for (int v = 0; v < 16; ++v) {
             const int m = m0 + wm * 32 + 8 * (v / 4) + 4 * half + (v % 4);
             if (m < M) {
                 float r = acc[j][v];
-                if (epi == EPI_RELU) r = r > 0.f ? r : 0.f;                                   // fused ReLU
-                else if (epi == EPI_MASK) r = aux[o0 + (size_t)m * out_plane] > 0.f ? r : 0.f;   // fused ReLU derivative
+                if (g.epi == EPI_RELU) r = r > 0.f ? r : 0.f;                                      // fused ReLU
+                else if (g.epi == EPI_MASK) r = aux[o0 + (size_t)m * out_plane] > 0.f ? r : 0.f;   // fused ReLU derivative
                 o[(size_t)m * out_plane] = r;
             }
         }
@@ -290,7 +292,9 @@ __global__ void __launch_bounds__(256) k_slice_reduce(int nslice, size_t n, int 
 }
 
 struct LaunchArgs {
-    int N, J, M, HI, HO, nsplit, chunks_per_split, epi;
+    ConvGeo g;
+    int nsplit;
+    size_t lds_bytes;
     const float *in, *wt, *aux;
     float* out;       // final output, or the partial buffer when nsplit > 1
 };
@@ -298,104 +302,135 @@ typedef int (*LaunchFn)(cnn_ctx*, const LaunchArgs&);
 
 template <class G>
 int launch(cnn_ctx* ctx, const LaunchArgs& a) {
-    static bool attr_done = false;
-    if (!attr_done && G::LDS_BYTES > 48 * 1024) {
-        hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(&k_conv_s1<G>),
-                                           hipFuncAttributeMaxDynamicSharedMemorySize, G::LDS_BYTES);
-        if (e != hipSuccess) return cnn::hip_check(ctx, e, "hipFuncSetAttribute(conv_s1)");
-        attr_done = true;
+    static size_t attr_bytes = 48 * 1024;
+    if (a.lds_bytes > attr_bytes) {
+        hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(&k_conv_tiled<G>),
+                                           hipFuncAttributeMaxDynamicSharedMemorySize, (int)a.lds_bytes);
+        if (e != hipSuccess) return cnn::hip_check(ctx, e, "hipFuncSetAttribute(conv_tiled)");
+        attr_bytes = a.lds_bytes;
     }
-    const int row_tiles = (a.HO + G::TH - 1) / G::TH;
-    const int img_tiles = (a.N + G::NB - 1) / G::NB;
-    dim3 grid((unsigned)(8 * ((row_tiles * img_tiles + 7) / 8) * ((a.M + G::MB - 1) / G::MB)), 1, (unsigned)a.nsplit);
+    dim3 grid((unsigned)(8 * a.g.per_xcd * a.g.mtiles), 1, (unsigned)a.nsplit);
     static char name[96] = "";
     if (!name[0])
-        snprintf(name, sizeof(name), "k_conv_s1<%dx%d pad%d CB%d WM%d WN%d NT%d NB%d TH%d W%d%s>", G::R, G::S, G::PADE, G::CB,
-                 G::WM, G::WN, G::NT, G::NB, G::TH, G::WI, G::VEC == 1 ? " v1" : "");
+        snprintf(name, sizeof(name), "k_conv_tiled<%dx%d CB%d WM%d WN%d NT%d%s>", G::R, G::S, G::CB, G::WM, G::WN, G::NT,
+                 G::VEC == 1 ? " v1" : "");
     {
-        cnn::ProfScope ps(ctx, name, 2.0 * a.N * a.J * a.M * G::RS * a.HO * G::WO);
-        hipLaunchKernelGGL(k_conv_s1<G>, grid, dim3(G::T), G::LDS_BYTES, ctx->stream, a.N, a.J, a.M, a.HI, a.HO, row_tiles,
-                           a.chunks_per_split, a.epi, a.in, a.wt, a.aux, a.out);
+        cnn::ProfScope ps(ctx, name, 2.0 * a.g.N * a.g.J * a.g.M * G::RS * a.g.HO * a.g.WO);
+        hipLaunchKernelGGL(k_conv_tiled<G>, grid, dim3(G::T), a.lds_bytes, ctx->stream, a.g, a.in, a.wt, a.aux, a.out);
     }
-    return cnn::launch_check(ctx, "conv_s1");
+    return cnn::launch_check(ctx, "conv_tiled");
 }
 
-// One table row per input geometry the tiled kernel is instantiated for.  Each row has a 128-feature tile
-// (4 waves) and a 64-feature tile (2 waves, same pixel tile); `big`/`small` may be null.
-struct Geo {
-    int R, S, pade, WI, CB, NB, TH, vec;
-    int mb_big;
-    LaunchFn big;
-    int mb_small;
-    LaunchFn small;
+// Instantiations: one per (kernel size, tile shape).  `mb`, `wn`, `nt`: features per tile, wave columns, pixel blocks
+// per wave; `maxplane`: staged input elements per channel the workgroup's threads can cover.
+struct Variant {
+    int R, S, CB, vec, mb, wn, nt, threads, maxplane, wstr;
+    LaunchFn fn;
 };
-#define CFG(R_, S_, P_, CB_, WM_, WN_, NT_, NB_, TH_, WI_, V_) launch<ConvCfg<R_, S_, P_, CB_, WM_, WN_, NT_, NB_, TH_, WI_, V_>>
-const Geo kGeo[] = {
-    // first layer: three input feature maps, element-wise filter fetch
-    {3, 3, 1, 224, 4, 1, 2, 1, 0, nullptr, 64, CFG(3, 3, 1, 4, 2, 2, 7, 1, 2, 224, 1)},
-    {3, 3, 1, 112, 4, 1, 2, 4, 128, CFG(3, 3, 1, 4, 4, 1, 7, 1, 2, 112, 4), 64, CFG(3, 3, 1, 4, 2, 1, 7, 1, 2, 112, 4)},
-    {3, 3, 1, 56, 4, 1, 4, 4, 128, CFG(3, 3, 1, 4, 4, 1, 7, 1, 4, 56, 4), 64, CFG(3, 3, 1, 4, 2, 1, 7, 1, 4, 56, 4)},
-    {3, 3, 1, 28, 4, 2, 4, 4, 128, CFG(3, 3, 1, 4, 4, 1, 7, 2, 4, 28, 4), 64, CFG(3, 3, 1, 4, 2, 1, 7, 2, 4, 28, 4)},
-    {3, 3, 1, 14, 4, 1, 14, 4, 128, CFG(3, 3, 1, 4, 4, 1, 7, 1, 14, 14, 4), 64, CFG(3, 3, 1, 4, 2, 1, 7, 1, 14, 14, 4)},
-    {3, 3, 1, 12, 4, 2, 12, 4, 128, CFG(3, 3, 1, 4, 4, 1, 9, 2, 12, 12, 4), 64, CFG(3, 3, 1, 4, 2, 1, 9, 2, 12, 12, 4)},
-    {5, 5, 0, 28, 4, 1, 8, 4, 0, nullptr, 64, CFG(5, 5, 0, 4, 2, 2, 3, 1, 8, 28, 4)},     // 28x28 -> 24x24 forward
-    {5, 5, 4, 24, 4, 2, 8, 4, 0, nullptr, 64, CFG(5, 5, 4, 4, 2, 2, 7, 2, 8, 24, 4)},     // its backpropagation
+#define V(R_, S_, CB_, WM_, WN_, NT_, VEC_, XP_)                                                                   \
+    {R_, S_, CB_, VEC_, 32 * WM_, WN_, NT_, 64 * WM_ * WN_, ConvCfg<R_, S_, CB_, WM_, WN_, NT_, VEC_, XP_>::MAXPLANE, \
+     ConvCfg<R_, S_, CB_, WM_, WN_, NT_, VEC_, XP_>::WSTR, launch<ConvCfg<R_, S_, CB_, WM_, WN_, NT_, VEC_, XP_>>}
+const Variant kVariants[] = {
+    // 3x3: 128-feature tiles (4 waves) and 64-feature tiles (2 waves), 7 / 8 / 9 pixel blocks per wave
+    V(3, 3, 4, 4, 1, 7, 4, 2), V(3, 3, 4, 4, 1, 8, 4, 2), V(3, 3, 4, 4, 1, 9, 4, 2),
+    V(3, 3, 4, 2, 1, 7, 4, 4), V(3, 3, 4, 2, 1, 8, 4, 4),
+    // 3x3 with fewer than 4 contraction channels (first layers)
+    V(3, 3, 4, 2, 2, 7, 1, 4),
+    // 5x5: 64-feature tiles, two wave columns
+    V(5, 5, 4, 2, 2, 3, 4, 4), V(5, 5, 4, 2, 2, 4, 4, 4), V(5, 5, 4, 2, 2, 7, 4, 4),
 };
-#undef CFG
+#undef V
 
 struct ConvPlan {
-    const Geo* g;
-    bool use_small;
-    int nsplit, chunks_per_split;
-    size_t partial_bytes;
+    const Variant* v;
+    ConvGeo g;
+    int nsplit;
+    size_t lds_bytes, partial_bytes;
 };
 
-// Picks the tile height (128 output features, or 64 for narrow layers) and slices the contraction when the output
-// alone gives fewer workgroups than the chip runs at once.
-bool make_plan(int R, int S, int pade, int N, int J, int M, int HI, int WI, ConvPlan* p) {
-    const int HO = HI + 2 * pade - R + 1;
-    if (HO <= 0) return false;
-    for (const Geo& g : kGeo) {
-        if (g.R != R || g.S != S || g.pade != pade || g.WI != WI) continue;
-        if (g.vec == 4 ? (J % g.CB != 0 || (J * R * S) % 4 != 0) : J >= 4) continue;
-        const long ptiles = (long)((N + g.NB - 1) / g.NB) * ((HO + g.TH - 1) / g.TH);
-        const int kCU = 256;
-        p->g = &g;
-        // the 64-feature tile re-stages the same input tile for half the MFMA work (measured ~30 % slower per
-        // FLOP), so it is used only when the layer has no more than 64 output features
-        p->use_small = !g.big || (g.small && M <= g.mb_small);
-        const int mb = p->use_small ? g.mb_small : g.mb_big;
-        const long wgs = ptiles * ((M + mb - 1) / mb);
-        const long concurrent = (long)kCU * 8 / ((p->use_small && g.big) ? 2 : 4);   // 8 waves per compute unit
-        const int nchunks = (J + g.CB - 1) / g.CB;
-        int want = 1;
-        if (wgs < concurrent) want = (int)((concurrent + wgs - 1) / wgs);
-        int max_split = nchunks / 8;                     // at least 8 chunks per slice
-        if (max_split < 1) max_split = 1;
-        if (want > max_split) want = max_split;
-        p->chunks_per_split = (nchunks + want - 1) / want;
-        p->nsplit = (nchunks + p->chunks_per_split - 1) / p->chunks_per_split;
-        const int WO = WI + 2 * pade - S + 1;
-        p->partial_bytes = p->nsplit > 1 ? (size_t)p->nsplit * N * M * HO * WO * sizeof(float) : 0;
-        return true;
+// Chooses, among the instantiations for this kernel size, the pixel tile (images x rows) that wastes the fewest MFMA
+// lanes, prefers the 128-feature tile unless the layer has at most 64 output features, and slices the contraction
+// when the output alone gives fewer workgroups than the chip runs at once.
+bool make_plan(int R, int S, int pad, int stride, int N, int J, int M, int HI, int WI, ConvPlan* p) {
+    if (HI + 2 * pad < R || WI + 2 * pad < S) return false;
+    const int HO = (HI + 2 * pad - R) / stride + 1, WO = (WI + 2 * pad - S) / stride + 1;
+    const int WLD = WI + 2 * pad;
+    double best = 0.0;
+    bool found = false;
+    for (const Variant& v : kVariants) {
+        if (v.R != R || v.S != S) continue;
+        if (v.vec == 4 ? (J % v.CB != 0 || (J * R * S) % 4 != 0) : J >= 4) continue;
+        if (v.vec == 4 && R != 5 && (M <= 64 ? v.mb != 64 : v.mb != 128)) continue;
+        const int cap = v.nt * v.wn * 32;
+        if (WO > cap) continue;
+        const int th_max = cap / WO < HO ? cap / WO : HO;
+        for (int TH = th_max; TH >= 1; --TH) {
+            int NB = cap / (TH * WO);
+            if (NB > N) NB = N;
+            const int THI = (TH - 1) * stride + R;
+            while (NB > 1 && NB * THI * WLD > v.maxplane) --NB;     // the threads must cover the staged plane
+            if (NB * THI * WLD > v.maxplane) continue;
+            const int row_tiles = (HO + TH - 1) / TH, img_tiles = (N + NB - 1) / NB;
+            const double eff = ((double)N * HO * WO) / ((double)row_tiles * img_tiles * cap);
+            for (int padded = (stride == 1 ? 1 : 0); padded >= 0; --padded) {
+                // LDS strides: padded so consecutive pixels stay in consecutive banks across row / image ends
+                const int WLDP = padded ? WO + 32 * ((WLD - WO + 31) / 32) : WLD;
+                const int IMG0 = THI * WLDP;
+                const int IMGSTR = padded ? IMG0 + ((((TH - 1) * WLDP + WO - IMG0) % 32) + 32) % 32 : IMG0;
+                const int PLANEP = NB * IMGSTR;
+                const int lds_buf = v.mb * v.wstr + v.CB * PLANEP;
+                const size_t lds_bytes = (size_t)lds_buf * 4 * 2;      // two buffers
+                if (lds_bytes > 156 * 1024) continue;
+                // score: MFMA lanes doing useful work, x 0.8 if only one workgroup fits a compute unit,
+                // x 0.97 for the conflicting LDS layout, slightly favouring taller tiles (less halo re-staging)
+                double score = eff * (lds_bytes <= 78 * 1024 ? 1.0 : 0.8) * (padded || stride != 1 ? 1.0 : 0.97);
+                score *= 1.0 - 0.01 * (double)(R - 1) / (TH * stride + R - 1);
+                if (found && score <= best + 1e-9) continue;
+                found = true;
+                best = score;
+                p->v = &v;
+                ConvGeo& g = p->g;
+                g.N = N; g.J = J; g.M = M; g.HI = HI; g.WI = WI; g.HO = HO; g.WO = WO; g.pad = pad; g.stride = stride;
+                g.NB = NB; g.TH = TH; g.THI = THI; g.WLD = WLD; g.WLDP = WLDP; g.IMGSTR = IMGSTR; g.PLANEP = PLANEP;
+                g.PLANE = NB * THI * WLD; g.NPIX = NB * TH * WO;
+                g.row_tiles = row_tiles; g.ptiles = row_tiles * img_tiles; g.mtiles = (M + v.mb - 1) / v.mb;
+                g.per_xcd = (g.ptiles + 7) / 8;
+                g.lds_buf = lds_buf;
+                p->lds_bytes = lds_bytes;
+            }
+        }
     }
-    return false;
+    if (!found) return false;
+    const Variant& v = *p->v;
+    ConvGeo& g = p->g;
+    const long wgs = (long)g.ptiles * g.mtiles;
+    const long concurrent = 256L * 8 / (v.threads / 64);           // 8 waves per compute unit
+    const int nchunks = (J + v.CB - 1) / v.CB;
+    int want = 1;
+    if (wgs < concurrent) want = (int)((concurrent + wgs - 1) / wgs);
+    int max_split = nchunks / 8;                                   // at least 8 chunks per slice
+    if (max_split < 1) max_split = 1;
+    if (want > max_split) want = max_split;
+    g.chunks_per_split = (nchunks + want - 1) / want;
+    p->nsplit = (nchunks + g.chunks_per_split - 1) / g.chunks_per_split;
+    p->partial_bytes = p->nsplit > 1 ? (size_t)p->nsplit * N * M * HO * WO * sizeof(float) : 0;
+    return true;
 }
 
 // ws: scratch for the partial outputs (only touched when the plan slices the contraction)
-int run_plan(cnn_ctx* ctx, const ConvPlan& p, int N, int J, int M, int HI, int HO, int WO, const float* in, const float* wt,
-             float* out, float* ws, int epi, const float* aux) {
+int run_plan(cnn_ctx* ctx, ConvPlan& p, const float* in, const float* wt, float* out, float* ws, int epi,
+             const float* aux) {
     // with a sliced contraction the epilogue belongs to the kernel that adds the slices
-    LaunchArgs a{N, J, M, HI, HO, p.nsplit, p.chunks_per_split, p.nsplit > 1 ? EPI_NONE : epi, in, wt, aux,
-                 p.nsplit > 1 ? ws : out};
-    int st = (p.use_small ? p.g->small : p.g->big)(ctx, a);
+    p.g.epi = p.nsplit > 1 ? EPI_NONE : epi;
+    LaunchArgs a{p.g, p.nsplit, p.lds_bytes, in, wt, aux, p.nsplit > 1 ? ws : out};
+    int st = p.v->fn(ctx, a);
     if (st != CNN_OK || p.nsplit == 1) return st;
-    const size_t n = (size_t)N * M * HO * WO;
-    size_t g = (n + 255) / 256;
-    if (g > 8192) g = 8192;
+    const size_t n = (size_t)p.g.N * p.g.M * p.g.HO * p.g.WO;
+    size_t gsz = (n + 255) / 256;
+    if (gsz > 8192) gsz = 8192;
     {
         cnn::ProfScope ps(ctx, "k_slice_reduce", 0.0);
-        hipLaunchKernelGGL(k_slice_reduce, dim3((unsigned)g), dim3(256), 0, ctx->stream, p.nsplit, n, epi, ws, aux, out);
+        hipLaunchKernelGGL(k_slice_reduce, dim3((unsigned)gsz), dim3(256), 0, ctx->stream, p.nsplit, n, epi, ws, aux, out);
     }
     return cnn::launch_check(ctx, "slice_reduce");
 }
@@ -406,22 +441,23 @@ namespace cnn {
 
 size_t mfma_conv_fwd_ws(const ConvShape& s) {
     ConvPlan p;
-    if (s.stride != 1 || s.H != s.W || !make_plan(s.R, s.S, s.pad, s.N, s.C, s.K, s.H, s.W, &p)) return 0;
+    if (!make_plan(s.R, s.S, s.pad, s.stride, s.N, s.C, s.K, s.H, s.W, &p)) return 0;
     return p.partial_bytes;
 }
 
 int mfma_conv_fwd(cnn_ctx* ctx, const ConvShape& s, const float* x, const float* w, float* y, int relu) {
     ConvPlan p;
-    if (s.stride != 1 || s.H != s.W || !make_plan(s.R, s.S, s.pad, s.N, s.C, s.K, s.H, s.W, &p)) return CNN_EUNSUPPORTED;
+    if (!make_plan(s.R, s.S, s.pad, s.stride, s.N, s.C, s.K, s.H, s.W, &p)) return CNN_EUNSUPPORTED;
     if (p.partial_bytes && (!ctx->ws || ctx->ws_bytes < p.partial_bytes)) return CNN_EWORKSPACE;
-    return run_plan(ctx, p, s.N, s.C, s.K, s.H, s.P, s.Q, x, w, y, reinterpret_cast<float*>(ctx->ws),
-                    relu ? EPI_RELU : EPI_NONE, nullptr);
+    return run_plan(ctx, p, x, w, y, reinterpret_cast<float*>(ctx->ws), relu ? EPI_RELU : EPI_NONE, nullptr);
 }
 
+// Backpropagation with stride 1 is a forward convolution of dy (P x Q, K channels) with the mirrored
+// transpose-weights and pad' = R-1-pad.
 static bool bwd_plan(const ConvShape& s, ConvPlan* p) {
-    if (s.stride != 1 || s.H != s.W || s.R != s.S || s.R - 1 - s.pad < 0) return false;
-    if (s.P + 2 * (s.R - 1 - s.pad) - s.R + 1 != s.H) return false;
-    return make_plan(s.R, s.S, s.R - 1 - s.pad, s.N, s.K, s.C, s.P, s.Q, p);
+    if (s.stride != 1 || s.R - 1 - s.pad < 0 || s.S - 1 - s.pad < 0 || s.R != s.S) return false;
+    if (!make_plan(s.R, s.S, s.R - 1 - s.pad, 1, s.N, s.K, s.C, s.P, s.Q, p)) return false;
+    return p->g.HO == s.H && p->g.WO == s.W;
 }
 
 static size_t wt_bytes(const ConvShape& s) {   // mirrored transpose of the weights, rounded up to 256 bytes
@@ -434,7 +470,6 @@ size_t mfma_conv_bwd_data_ws(const ConvShape& s) {
     return wt_bytes(s) + p.partial_bytes;
 }
 
-// dx = forward convolution of dy (P x Q, K channels) with the mirrored transpose-weights, pad' = R-1-pad.
 // act != NULL: dx is zeroed where act <= 0 (act = the ReLU output that was this layer's forward input).
 int mfma_conv_bwd_data(cnn_ctx* ctx, const ConvShape& s, const float* dy, const float* w, float* dx, const float* act) {
     ConvPlan p;
@@ -445,20 +480,13 @@ int mfma_conv_bwd_data(cnn_ctx* ctx, const ConvShape& s, const float* dy, const 
     const int RS = s.R * s.S;
     dim3 grid((unsigned)((s.K + kTfK - 1) / kTfK), (unsigned)((s.C + 31) / 32));
     const size_t tl_bytes = (kTfK * (32 * RS + 1)) * sizeof(float);
-    static size_t tl_attr = 48 * 1024;
-    if (tl_bytes > tl_attr) {
-        hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(&k_transpose_flip),
-                                           hipFuncAttributeMaxDynamicSharedMemorySize, (int)tl_bytes);
-        if (e != hipSuccess) return hip_check(ctx, e, "hipFuncSetAttribute(transpose_flip)");
-        tl_attr = tl_bytes;
-    }
     {
         ProfScope ps(ctx, "k_transpose_flip", 0.0);
         hipLaunchKernelGGL(k_transpose_flip, grid, dim3(256), tl_bytes, ctx->stream, s.K, s.C, RS, w, wT);
     }
     int st = launch_check(ctx, "transpose_flip");
     if (st != CNN_OK) return st;
-    return run_plan(ctx, p, s.N, s.K, s.C, s.P, s.H, s.W, dy, wT, dx, partial, act ? EPI_MASK : EPI_NONE, act);
+    return run_plan(ctx, p, dy, wT, dx, partial, act ? EPI_MASK : EPI_NONE, act);
 }
 
 }  // namespace cnn

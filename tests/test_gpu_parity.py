@@ -68,6 +68,11 @@ CONV_CASES = [  # N, C, H, K, R, pad       (square images, stride 1)
     (3, 8, 12, 136, 3, 1),      # pairs of 12x12 images
     (2, 8, 28, 40, 5, 0),       # 5x5, 28 -> 24
     (3, 64, 56, 128, 3, 1),
+    (2, 8, 32, 136, 3, 1),      # 32x32 images: 8-block tiles
+    (3, 12, 20, 40, 3, 1),      # 20x20: several images per tile, ragged
+    (2, 8, 40, 130, 3, 0),      # pad 0: 40 -> 38
+    (1, 16, 64, 24, 3, 2),      # pad 2: 64 -> 66
+    (2, 8, 17, 72, 5, 2),       # 5x5 'same' on an odd size
 ]
 
 
@@ -92,7 +97,9 @@ def test_conv_generic_shapes_fall_back_and_match(cnn, ctx):
     for (N, C, H, W, K, R, S, st, pad) in [(2, 3, 39, 39, 8, 11, 11, 4, 0), (1, 5, 9, 13, 7, 3, 2, 2, 1),
                                            (2, 4, 6, 6, 4, 1, 1, 1, 0), (1, 3, 224, 224, 8, 3, 3, 1, 1),
                                            (2, 3, 224, 224, 64, 3, 3, 1, 1), (3, 3, 231, 231, 96, 11, 11, 4, 0),
-                                           (2, 3, 30, 30, 40, 3, 3, 1, 1), (1, 3, 24, 36, 20, 3, 3, 1, 0)]:
+                                           (2, 3, 30, 30, 40, 3, 3, 1, 1), (1, 3, 24, 36, 20, 3, 3, 1, 0),
+                                           (2, 8, 24, 36, 40, 3, 3, 1, 1), (2, 16, 31, 45, 72, 3, 3, 2, 1),
+                                           (1, 8, 50, 30, 136, 5, 5, 2, 2), (2, 8, 13, 300, 16, 3, 3, 1, 1)]:
         say("generic conv", (N, C, H, W, K, R, S, st, pad))
         x = synth.randn(91, 1, (N, C, H, W)); w = synth.randn(91, 2, (K, C, R, S))
         y = cnn.cnn_conv_fwd(ctx, dev(x), dev(w), st, pad)
