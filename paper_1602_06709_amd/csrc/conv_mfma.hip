@@ -381,10 +381,11 @@ bool make_plan(int R, int S, int pad, int stride, int N, int J, int M, int HI, i
                 const int lds_buf = v.mb * v.wstr + v.CB * PLANEP;
                 const size_t lds_bytes = (size_t)lds_buf * 4 * 2;      // two buffers
                 if (lds_bytes > 156 * 1024) continue;
-                // score: MFMA lanes doing useful work, x 0.8 if only one workgroup fits a compute unit,
-                // x 0.97 for the conflicting LDS layout, slightly favouring taller tiles (less halo re-staging)
-                double score = eff * (lds_bytes <= 78 * 1024 ? 1.0 : 0.8) * (padded || stride != 1 ? 1.0 : 0.97);
-                score *= 1.0 - 0.01 * (double)(R - 1) / (TH * stride + R - 1);
+                // score: MFMA lanes doing useful work, x 0.9 if only one workgroup fits a compute unit, x 0.97 for
+                // the conflicting LDS layout, and a penalty for the share of staged rows that are halo (short tiles
+                // re-stage the same rows; measured on 14x14 and 24x24 layers)
+                double score = eff * (lds_bytes <= 78 * 1024 ? 1.0 : 0.9) * (padded || stride != 1 ? 1.0 : 0.97);
+                score *= 1.0 - 0.3 * (double)(R - 1) / (TH * stride + R - 1);
                 if (found && score <= best + 1e-9) continue;
                 found = true;
                 best = score;
