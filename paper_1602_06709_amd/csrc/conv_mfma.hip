@@ -68,7 +68,7 @@ template <class G>
 __global__ void __launch_bounds__(G::T, 2)
 k_conv_tiled(ConvGeo g, const float* __restrict__ in, const float* __restrict__ wt, const float* __restrict__ aux,
              float* __restrict__ out_base) {
-    constexpr int R = G::R, S = G::S, RS = G::RS, CB = G::CB, NT = G::NT, T = G::T;
+    constexpr int S = G::S, RS = G::RS, CB = G::CB, NT = G::NT, T = G::T;
     extern __shared__ float lds[];
     float* wl = lds;
     float* xl = lds + G::MB * G::WSTR;
@@ -93,29 +93,38 @@ k_conv_tiled(ConvGeo g, const float* __restrict__ in, const float* __restrict__ 
     const size_t in_img = (size_t)J * plane_g;         // elements per image of `in`
     const float* in_base = in + (size_t)n0 * in_img;
 
-    // ---- input tile staging: each thread owns XP positions of the (image, row, col) plane and fetches
-    //      them for every channel of the chunk (-1 = outside the image: zero fill)
+    // ---- input tile staging: each thread owns XP positions of the (image, row, col) plane and fetches them for
+    //      every channel of the chunk.  Everything in the chunk loop is branch-free: a position outside the image
+    //      loads a harmless in-range address and is replaced by zero when it is written to LDS, a position outside
+    //      the tile writes to a per-lane dummy word behind the two buffers.  (Branches around the loads made the
+    //      compiler wait for ALL outstanding loads at every staging item.)
+    float* const lds_dummy = lds + 2 * g.lds_buf + lane;
     int xoff[G::XP], xpos[G::XP];
+    bool xok[G::XP], xin[G::XP];
 #pragma unroll
     for (int j = 0; j < G::XP; ++j) {
         const int e = tid + j * T;
-        int off = -1, pos = 0;
+        int off = 0, pos = 0;
+        bool ok = false;
         if (e < g.PLANE) {
             const int per_img = g.THI * g.WLD;
             const int nb = e / per_img, rem = e % per_img;
             const int row = rem / g.WLD, col = rem % g.WLD;
             const int h = p0 * g.stride - g.pad + row, w = col - g.pad;
             pos = nb * g.IMGSTR + row * g.WLDP + col;
-            if (n0 + nb < N && h >= 0 && h < g.HI && w >= 0 && w < g.WI) off = nb * (int)in_img + h * g.WI + w;
+            if (n0 + nb < N && h >= 0 && h < g.HI && w >= 0 && w < g.WI) {
+                off = nb * (int)in_img + h * g.WI + w;
+                ok = true;
+            }
         }
         xoff[j] = off;
         xpos[j] = pos;
+        xok[j] = ok;
+        xin[j] = e < g.PLANE;
     }
     // ---- filter tile staging: thread = (row m_sub, fetch unit kq) of a pass over RPP rows
     const int w_msub = tid / G::Q4, w_kq = tid % G::Q4;
     const bool w_thread = tid < G::RPP * G::Q4;
-    const float* w_src = wt + ((size_t)(m0 + w_msub) * J) * RS + w_kq * G::VEC;
-    float* w_dst = wl + w_msub * G::WSTR + w_kq * G::VEC;
 
     // ---- per-lane LDS read bases
     const int a_base = (wm * 32 + l32) * G::WSTR + half * (CB / 2) * RS;
@@ -140,6 +149,19 @@ k_conv_tiled(ConvGeo g, const float* __restrict__ in, const float* __restrict__ 
 
     float xr[CB][G::XP];
     float4 wr[G::WSL];
+    // per-pass filter source row (clamped into the tensor), validity and LDS destination
+    const float* w_row[G::WSL];
+    bool w_ok[G::WSL];
+    int w_pos[G::WSL];
+#pragma unroll
+    for (int i = 0; i < G::WSL; ++i) {
+        const int m = w_msub + i * G::RPP;
+        const bool in_tile = w_thread && m < G::MB;
+        w_ok[i] = in_tile && m0 + m < M;
+        const int mrow = w_ok[i] ? m0 + m : 0;
+        w_row[i] = wt + ((size_t)mrow * J) * RS + (w_thread ? w_kq * G::VEC : 0);
+        w_pos[i] = in_tile ? m * G::WSTR + w_kq * G::VEC : -1;
+    }
 
     // Staging is cut into items (one input-tile register or one filter-tile fetch unit each) so that it can be
     // spread over the MFMA steps of a chunk instead of forming a phase of its own.
@@ -147,29 +169,33 @@ k_conv_tiled(ConvGeo g, const float* __restrict__ in, const float* __restrict__ 
     auto fetch_item = [&](int it, int c0) {
         if (it < NX) {
             const int c = it / G::XP, j = it % G::XP;
-            const float* src = in_base + (size_t)c0 * plane_g;
-            xr[c][j] = (xoff[j] >= 0 && (G::VEC == 4 || c0 + c < J)) ? src[xoff[j] + c * plane_g] : 0.f;
+            const int cc = (G::VEC == 4 || c0 + c < J) ? c0 + c : 0;          // channels past J: any valid plane
+            xr[c][j] = in_base[(size_t)cc * plane_g + xoff[j]];
         } else {
             // w[m][c0 .. c0+CB)[R][S]: CB*R*S contiguous floats per output feature
-            const int i = it - NX, m = w_msub + i * G::RPP;
-            float4 v = make_float4(0.f, 0.f, 0.f, 0.f);
-            if (w_thread && m < G::MB && m0 + m < M) {
-                if (G::VEC == 4) v = *reinterpret_cast<const float4*>(w_src + ((size_t)i * G::RPP * J + c0) * RS);
-                else if (c0 * RS + w_kq < J * RS) v.x = w_src[((size_t)i * G::RPP * J + c0) * RS];
+            const int i = it - NX;
+            if (G::VEC == 4) {
+                wr[i] = *reinterpret_cast<const float4*>(w_row[i] + (size_t)c0 * RS);
+            } else {
+                const int o = c0 * RS + w_kq < J * RS ? c0 * RS : 0;
+                wr[i].x = w_row[i][o];
             }
-            wr[i] = v;
         }
     };
-    auto stage_item = [&](int it, int buf) {
+    auto stage_item = [&](int it, int buf, int c0) {
         if (it < NX) {
             const int c = it / G::XP, j = it % G::XP;
-            if (tid + j * T < g.PLANE) xl[buf * g.lds_buf + c * g.PLANEP + xpos[j]] = xr[c][j];
+            const bool ok = xok[j] && (G::VEC == 4 || c0 + c < J);
+            float* d = xin[j] ? xl + (buf * g.lds_buf + c * g.PLANEP + xpos[j]) : lds_dummy;
+            *d = ok ? xr[c][j] : 0.f;
         } else {
             const int i = it - NX;
-            if (w_thread && w_msub + i * G::RPP < G::MB) {
-                float* d = w_dst + buf * g.lds_buf + i * G::RPP * G::WSTR;
-                d[0] = wr[i].x;
-                if (G::VEC == 4) { d[1] = wr[i].y; d[2] = wr[i].z; d[3] = wr[i].w; }
+            float* d = w_pos[i] >= 0 ? wl + (buf * g.lds_buf + w_pos[i]) : lds_dummy;
+            if (G::VEC == 4) {
+                d[0] = w_ok[i] ? wr[i].x : 0.f; d[1] = w_ok[i] ? wr[i].y : 0.f;
+                d[2] = w_ok[i] ? wr[i].z : 0.f; d[3] = w_ok[i] ? wr[i].w : 0.f;
+            } else {
+                d[0] = (w_ok[i] && c0 * RS + w_kq < J * RS) ? wr[i].x : 0.f;
             }
         }
     };
@@ -189,7 +215,7 @@ k_conv_tiled(ConvGeo g, const float* __restrict__ in, const float* __restrict__ 
 #pragma unroll
     for (int it = 0; it < NITEMS; ++it) fetch_item(it, ch_begin * CB);
 #pragma unroll
-    for (int it = 0; it < NITEMS; ++it) stage_item(it, 0);
+    for (int it = 0; it < NITEMS; ++it) stage_item(it, 0, ch_begin * CB);
     {
         const int c1 = min(ch_begin + 1, ch_end - 1) * CB;
 #pragma unroll
@@ -198,32 +224,50 @@ k_conv_tiled(ConvGeo g, const float* __restrict__ in, const float* __restrict__ 
     __syncthreads();
     for (int ch = ch_begin; ch < ch_end; ++ch) {
         const int buf = (ch - ch_begin) & 1;
+        const int c1 = min(ch + 1, ch_end - 1) * CB;      // chunk held in the staging registers
         const int c2 = min(ch + 2, ch_end - 1) * CB;
-        const float* wb = wl + buf * g.lds_buf;
+        const float* wb = wl + buf * g.lds_buf + a_base;
         const float* xb = xl + buf * g.lds_buf;
+        // operands of step t+1 are read from LDS before the MFMAs of step t are issued; the scheduling barrier
+        // after each step keeps the compiler from regrouping the staging loads (which would bunch them at the end
+        // of the chunk, right before they are needed)
+        float a_cur = wb[0], b_cur[NT];
 #pragma unroll
-        for (int cc = 0; cc < CB / 2; ++cc)
+        for (int j = 0; j < NT; ++j) b_cur[j] = xb[b_base[j]];
 #pragma unroll
-            for (int r = 0; r < R; ++r)
+        for (int step = 0; step < STEPS; ++step) {
 #pragma unroll
-                for (int s = 0; s < S; ++s) {
-                    const int step = (cc * R + r) * S + s;
-#pragma unroll
-                    for (int u = 0; u < IPS; ++u) {
-                        const int it = step * IPS + u;
-                        if (it < NITEMS) {
-                            stage_item(it, buf ^ 1);
-                            fetch_item(it, c2);
-                        }
-                    }
-                    const float a = wb[a_base + cc * RS + r * S + s];
-                    const float* xs = xb + (cc * g.PLANEP + r * g.WLDP + s);
-                    float b[NT];
-#pragma unroll
-                    for (int j = 0; j < NT; ++j) b[j] = xs[b_base[j]];
-#pragma unroll
-                    for (int j = 0; j < NT; ++j) acc[j] = __builtin_amdgcn_mfma_f32_32x32x2f32(a, b[j], acc[j], 0, 0, 0);
+            for (int u = 0; u < IPS; ++u) {
+                const int it = step * IPS + u;
+                if (it < NITEMS) {
+                    stage_item(it, buf ^ 1, c1);
+                    fetch_item(it, c2);
                 }
+            }
+            float a_nxt = 0.f, b_nxt[NT];
+            if (step + 1 < STEPS) {
+                const int n1 = step + 1, cc = n1 / RS, r = (n1 % RS) / S, s2 = n1 % S;
+                a_nxt = wb[n1];
+                const float* xs = xb + (cc * g.PLANEP + r * g.WLDP + s2);
+#pragma unroll
+                for (int j = 0; j < NT; ++j) b_nxt[j] = xs[b_base[j]];
+            }
+#pragma unroll
+            for (int j = 0; j < NT; ++j) acc[j] = __builtin_amdgcn_mfma_f32_32x32x2f32(a_cur, b_cur[j], acc[j], 0, 0, 0);
+            // issue order inside the step: one MFMA, then two of the next step's LDS reads, and so on, so the
+            // reads complete under the remaining MFMAs instead of being exposed at the start of the next step
+#pragma unroll
+            for (int j = 0; j < NT; ++j) {
+                __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);   // 1 MFMA
+                __builtin_amdgcn_sched_group_barrier(0x100, 2, 0);   // 2 DS reads
+            }
+            __builtin_amdgcn_sched_barrier(0);
+            if (step + 1 < STEPS) {
+                a_cur = a_nxt;
+#pragma unroll
+                for (int j = 0; j < NT; ++j) b_cur[j] = b_nxt[j];
+            }
+        }
         __syncthreads();
     }
 
@@ -379,7 +423,7 @@ bool make_plan(int R, int S, int pad, int stride, int N, int J, int M, int HI, i
                 const int IMGSTR = padded ? IMG0 + ((((TH - 1) * WLDP + WO - IMG0) % 32) + 32) % 32 : IMG0;
                 const int PLANEP = NB * IMGSTR;
                 const int lds_buf = v.mb * v.wstr + v.CB * PLANEP;
-                const size_t lds_bytes = (size_t)lds_buf * 4 * 2;      // two buffers
+                const size_t lds_bytes = ((size_t)lds_buf * 2 + 64) * 4;   // two buffers + 64 dummy words
                 if (lds_bytes > 156 * 1024) continue;
                 // score: MFMA lanes doing useful work, x 0.9 if only one workgroup fits a compute unit, x 0.97 for
                 // the conflicting LDS layout, and a penalty for the share of staged rows that are halo (short tiles
