@@ -19,6 +19,7 @@
 // ch+2 from HBM into those registers, one staging item between every MFMA step (no staging phase, one barrier per
 // chunk).
 #include <stdio.h>
+#include <stdlib.h>
 
 #include "common.h"
 
@@ -40,7 +41,11 @@ struct ConvGeo {
     int PLANE;                     // staged elements per channel: NB * THI * WLD
     int NPIX;                      // NB * TH * WO
     int row_tiles, ptiles, mtiles, per_xcd;
-    int chunks_per_split, epi;
+    // Per XCD, workgroups [0, full_per_xcd) run one (pixel tile, feature tile) unit over the whole contraction; the
+    // remaining tail_per_xcd units are each cut into nsl slices of chunks_per_slice channel chunks, one workgroup per
+    // slice, whose partial results go to a scratch buffer and are added up by k_tile_reduce.
+    int full_per_xcd, tail_per_xcd, nsl, chunks_per_slice;
+    int epi;
     int lds_buf;                   // elements of one (filter tile, input tile) buffer
 };
 
@@ -67,7 +72,7 @@ struct ConvCfg {
 template <class G>
 __global__ void __launch_bounds__(G::T, 2)
 k_conv_tiled(ConvGeo g, const float* __restrict__ in, const float* __restrict__ wt, const float* __restrict__ aux,
-             float* __restrict__ out_base) {
+             float* __restrict__ out_base, float* __restrict__ partial) {
     constexpr int S = G::S, RS = G::RS, CB = G::CB, NT = G::NT, T = G::T;
     extern __shared__ float lds[];
     float* wl = lds;
@@ -83,9 +88,15 @@ k_conv_tiled(ConvGeo g, const float* __restrict__ in, const float* __restrict__ 
     // of pixel tiles and run the output-feature tiles of one pixel tile back to back on it, so the input tile, and
     // the halo rows it shares with the next tile, come from HBM once instead of once per feature tile.
     const int xcd = blockIdx.x & 7, seq = blockIdx.x >> 3;
-    const int ptile = xcd * g.per_xcd + seq / g.mtiles;
-    if (seq / g.mtiles >= g.per_xcd || ptile >= g.ptiles) return;   // whole workgroup leaves: no barrier is left behind
-    const int m0 = (seq % g.mtiles) * G::MB;
+    int unit = seq, slice = -1;
+    if (seq >= g.full_per_xcd) {
+        const int t = seq - g.full_per_xcd;
+        unit = g.full_per_xcd + t / g.nsl;
+        slice = t % g.nsl;
+    }
+    const int ptile = xcd * g.per_xcd + unit / g.mtiles;
+    if (ptile >= g.ptiles) return;   // whole workgroup leaves: no barrier is left behind
+    const int m0 = (unit % g.mtiles) * G::MB;
     const int n0 = (ptile / g.row_tiles) * g.NB;
     const int p0 = (ptile % g.row_tiles) * g.TH;
 
@@ -205,12 +216,11 @@ k_conv_tiled(ConvGeo g, const float* __restrict__ in, const float* __restrict__ 
     // the LDS writes nor the global-load issue ever stall the matrix pipe for a whole phase.  One barrier per chunk.
     // The last iterations stage and fetch a clamped chunk again instead of branching (harmless: that buffer is
     // never read), which keeps the chunk body one basic block.
-    // blockIdx.z selects a slice of the contraction (used when the output alone gives too few workgroups);
-    // each slice writes its own partial output, added up afterwards in slice order.
-    const int ch_begin = blockIdx.z * g.chunks_per_split;
-    const int ch_end = min(ch_begin + g.chunks_per_split, (J + CB - 1) / CB);
+    // A tail workgroup (slice >= 0) covers only its slice of the contraction and writes a partial tile.
+    const int nchunks = (J + CB - 1) / CB;
+    const int ch_begin = slice < 0 ? 0 : slice * g.chunks_per_slice;
+    const int ch_end = slice < 0 ? nchunks : min(ch_begin + g.chunks_per_slice, nchunks);
     const size_t out_plane = (size_t)g.HO * g.WO;
-    float* out = out_base + (size_t)blockIdx.z * N * M * out_plane;
     constexpr int STEPS = (CB / 2) * RS, IPS = (NITEMS + STEPS - 1) / STEPS;
 #pragma unroll
     for (int it = 0; it < NITEMS; ++it) fetch_item(it, ch_begin * CB);
@@ -272,6 +282,23 @@ k_conv_tiled(ConvGeo g, const float* __restrict__ in, const float* __restrict__ 
     }
 
     // ---- epilogue: lane = pixel (coalesced along the row), register v = output feature
+    if (slice >= 0) {
+        // partial tile [MB][NPIXB] of tail unit (xcd, unit - full_per_xcd), slice `slice`; no guards: the scratch
+        // buffer holds whole tiles and the reduction skips what lies outside the tensor
+        const size_t tix = (size_t)xcd * g.tail_per_xcd + (unit - g.full_per_xcd);
+        float* po = partial + (tix * g.nsl + slice) * (size_t)(G::MB * G::NPIXB);
+#pragma unroll
+        for (int j = 0; j < NT; ++j) {
+            const int i = (wn * NT + j) * 32 + l32;
+#pragma unroll
+            for (int v = 0; v < 16; ++v) {
+                const int m = wm * 32 + 8 * (v / 4) + 4 * half + (v % 4);
+                po[(size_t)m * G::NPIXB + i] = acc[j][v];
+            }
+        }
+        return;
+    }
+    float* out = out_base;
 #pragma unroll
     for (int j = 0; j < NT; ++j) {
         const int i = (wn * NT + j) * 32 + l32;
@@ -317,30 +344,38 @@ __global__ void __launch_bounds__(256) k_transpose_flip(int K, int C, int RS, co
     }
 }
 
-// out[i] = sum over slices of partial[slice][i], in slice order.
-__global__ void __launch_bounds__(256) k_slice_reduce(int nslice, size_t n, int epi, const float* __restrict__ partial,
-                                                     const float* __restrict__ aux, float* __restrict__ out) {
-    for (size_t i = blockIdx.x * (size_t)256 + threadIdx.x; i < n; i += (size_t)gridDim.x * 256) {
-        float s0 = 0.f, s1 = 0.f;
-        int s = 0;
-        for (; s + 1 < nslice; s += 2) {
-            s0 += partial[(size_t)s * n + i];
-            s1 += partial[(size_t)(s + 1) * n + i];
-        }
-        if (s < nslice) s0 += partial[(size_t)s * n + i];
-        float r = s0 + s1;
-        if (epi == EPI_RELU) r = r > 0.f ? r : 0.f;
-        else if (epi == EPI_MASK) r = aux[i] > 0.f ? r : 0.f;
-        out[i] = r;
+// Adds up the slices of every tail unit in slice order and stores the tile with the epilogue applied.
+// grid = (tail units, MB / 8): one block owns 8 feature rows of one tile.
+__global__ void __launch_bounds__(256) k_tile_reduce(ConvGeo g, int MB, int cap, const float* __restrict__ partial,
+                                                    const float* __restrict__ aux, float* __restrict__ out) {
+    const int xcd = blockIdx.x / g.tail_per_xcd, unit = g.full_per_xcd + blockIdx.x % g.tail_per_xcd;
+    const int ptile = xcd * g.per_xcd + unit / g.mtiles;
+    if (ptile >= g.ptiles) return;
+    const int m0 = (unit % g.mtiles) * MB;
+    const int n0 = (ptile / g.row_tiles) * g.NB, p0 = (ptile % g.row_tiles) * g.TH;
+    const size_t out_plane = (size_t)g.HO * g.WO, tile = (size_t)MB * cap;
+    const float* pt = partial + (size_t)blockIdx.x * g.nsl * tile;
+    const int per_img = g.TH * g.WO;
+    for (int e = threadIdx.x; e < 8 * cap; e += 256) {
+        const int ml = blockIdx.y * 8 + e / cap, i = e % cap;
+        if (i >= g.NPIX || m0 + ml >= g.M) continue;
+        const int nb = i / per_img, rem = i % per_img;
+        const int p = p0 + rem / g.WO, q = rem % g.WO;
+        if (n0 + nb >= g.N || p >= g.HO) continue;
+        float r = 0.f;
+        for (int s = 0; s < g.nsl; ++s) r += pt[s * tile + (size_t)ml * cap + i];
+        const size_t o = ((size_t)(n0 + nb) * g.M + m0 + ml) * out_plane + (size_t)p * g.WO + q;
+        if (g.epi == EPI_RELU) r = r > 0.f ? r : 0.f;
+        else if (g.epi == EPI_MASK) r = aux[o] > 0.f ? r : 0.f;
+        out[o] = r;
     }
 }
 
 struct LaunchArgs {
     ConvGeo g;
-    int nsplit;
     size_t lds_bytes;
     const float *in, *wt, *aux;
-    float* out;       // final output, or the partial buffer when nsplit > 1
+    float *out, *partial;
 };
 typedef int (*LaunchFn)(cnn_ctx*, const LaunchArgs&);
 
@@ -353,14 +388,15 @@ int launch(cnn_ctx* ctx, const LaunchArgs& a) {
         if (e != hipSuccess) return cnn::hip_check(ctx, e, "hipFuncSetAttribute(conv_tiled)");
         attr_bytes = a.lds_bytes;
     }
-    dim3 grid((unsigned)(8 * a.g.per_xcd * a.g.mtiles), 1, (unsigned)a.nsplit);
+    dim3 grid((unsigned)(8 * (a.g.full_per_xcd + a.g.tail_per_xcd * a.g.nsl)));
     static char name[96] = "";
     if (!name[0])
         snprintf(name, sizeof(name), "k_conv_tiled<%dx%d CB%d WM%d WN%d NT%d%s>", G::R, G::S, G::CB, G::WM, G::WN, G::NT,
                  G::VEC == 1 ? " v1" : "");
     {
         cnn::ProfScope ps(ctx, name, 2.0 * a.g.N * a.g.J * a.g.M * G::RS * a.g.HO * a.g.WO);
-        hipLaunchKernelGGL(k_conv_tiled<G>, grid, dim3(G::T), a.lds_bytes, ctx->stream, a.g, a.in, a.wt, a.aux, a.out);
+        hipLaunchKernelGGL(k_conv_tiled<G>, grid, dim3(G::T), a.lds_bytes, ctx->stream, a.g, a.in, a.wt, a.aux, a.out,
+                           a.partial);
     }
     return cnn::launch_check(ctx, "conv_tiled");
 }
@@ -388,9 +424,9 @@ const Variant kVariants[] = {
 struct ConvPlan {
     const Variant* v;
     ConvGeo g;
-    int nsplit;
     size_t lds_bytes, partial_bytes;
 };
+
 
 // Chooses, among the instantiations for this kernel size, the pixel tile (images x rows) that wastes the fewest MFMA
 // lanes, prefers the 128-feature tile unless the layer has at most 64 output features, and slices the contraction
@@ -448,36 +484,60 @@ bool make_plan(int R, int S, int pad, int stride, int N, int J, int M, int HI, i
     if (!found) return false;
     const Variant& v = *p->v;
     ConvGeo& g = p->g;
-    const long wgs = (long)g.ptiles * g.mtiles;
-    const long concurrent = 256L * 8 / (v.threads / 64);           // 8 waves per compute unit
+    // Tail slicing.  Workgroups are handed to the 256 compute units as slots free up, so with `units` equal units
+    // the busiest compute unit works through ceil(units / 256) of them while the others idle at the end.  The
+    // units % 256 that overhang the last full round (all of them, when the grid is no larger than one round) are
+    // therefore cut along the contraction into nsl shorter workgroups each, so that the final round is even too.
+    // A workgroup that is alone on its compute unit reaches about 0.9 of the rate of two resident ones.
+    // The price is the partial tiles, written and read once (8 bytes per element at ~4 TB/s, relative to the
+    // tile's compute time).
+    const int upx = g.per_xcd * g.mtiles;                          // units per XCD
+    const long units = 8L * upx;
     const int nchunks = (J + v.CB - 1) / v.CB;
-    int want = 1;
-    if (wgs < concurrent) want = (int)((concurrent + wgs - 1) / wgs);
-    int max_split = nchunks / 8;                                   // at least 8 chunks per slice
-    if (max_split < 1) max_split = 1;
-    if (want > max_split) want = max_split;
-    g.chunks_per_split = (nchunks + want - 1) / want;
-    p->nsplit = (nchunks + g.chunks_per_split - 1) / g.chunks_per_split;
-    p->partial_bytes = p->nsplit > 1 ? (size_t)p->nsplit * N * M * HO * WO * sizeof(float) : 0;
+    const double ov_job = (8.0 / 4.0e12) / (2.0 * J * R * S / (0.85 * 157.3e12));
+    const long rounds = units > 256 ? units / 256 : 0, tail = units - rounds * 256;
+    int best_tail = 0, best_nsl = 1;
+    if (tail > 0) {
+        double best_t = 0.0;
+        for (int nsl = 1; nsl <= 16; ++nsl) {
+            if (nsl > 1 && nchunks / nsl < 8) break;               // at least 8 chunks per slice
+            const long k = (tail * nsl + 255) / 256;               // slices on the busiest compute unit
+            double t = (double)rounds + (double)k / nsl * (rounds == 0 && k == 1 ? 1.0 / 0.9 : 1.0);
+            if (nsl > 1) t += (double)(tail * nsl) / 256.0 * ov_job;
+            if (nsl == 1 || t < best_t * 0.98) { best_t = t; best_nsl = nsl; }
+        }
+        if (best_nsl > 1) best_tail = (int)tail;
+    }
+    if (const char* e = getenv("CNN_CONV_TAIL")) {                 // experiment override: "tail,nsl"
+        int a = 0, b = 1;
+        if (sscanf(e, "%d,%d", &a, &b) == 2 && a >= 0 && a % 8 == 0 && a <= units && b >= 1 && nchunks / b >= 1) {
+            best_tail = b > 1 ? a : 0; best_nsl = b;
+        }
+    }
+    if (getenv("CNN_PLAN_DEBUG"))
+        fprintf(stderr, "plan %dx%d N%d J%d M%d %dx%d: mb%d nt%d NB%d TH%d ptiles%d mtiles%d units%ld lds%zu tail%d nsl%d\n", R, S, N,
+                J, M, HI, WI, v.mb, v.nt, g.NB, g.TH, g.ptiles, g.mtiles, units, p->lds_bytes, best_tail, best_nsl);
+    g.tail_per_xcd = best_tail / 8;
+    g.full_per_xcd = upx - g.tail_per_xcd;
+    g.nsl = best_tail ? best_nsl : 1;
+    g.chunks_per_slice = (nchunks + g.nsl - 1) / g.nsl;
+    p->partial_bytes = (size_t)best_tail * g.nsl * v.mb * (v.nt * v.wn * 32) * sizeof(float);
     return true;
 }
 
-// ws: scratch for the partial outputs (only touched when the plan slices the contraction)
+// ws: scratch for the partial tiles (only touched when the plan has tail units)
 int run_plan(cnn_ctx* ctx, ConvPlan& p, const float* in, const float* wt, float* out, float* ws, int epi,
              const float* aux) {
-    // with a sliced contraction the epilogue belongs to the kernel that adds the slices
-    p.g.epi = p.nsplit > 1 ? EPI_NONE : epi;
-    LaunchArgs a{p.g, p.nsplit, p.lds_bytes, in, wt, aux, p.nsplit > 1 ? ws : out};
+    p.g.epi = epi;
+    LaunchArgs a{p.g, p.lds_bytes, in, wt, aux, out, ws};
     int st = p.v->fn(ctx, a);
-    if (st != CNN_OK || p.nsplit == 1) return st;
-    const size_t n = (size_t)p.g.N * p.g.M * p.g.HO * p.g.WO;
-    size_t gsz = (n + 255) / 256;
-    if (gsz > 8192) gsz = 8192;
+    if (st != CNN_OK || p.g.tail_per_xcd == 0) return st;
     {
-        cnn::ProfScope ps(ctx, "k_slice_reduce", 0.0);
-        hipLaunchKernelGGL(k_slice_reduce, dim3((unsigned)gsz), dim3(256), 0, ctx->stream, p.nsplit, n, epi, ws, aux, out);
+        cnn::ProfScope ps(ctx, "k_tile_reduce", 0.0);
+        hipLaunchKernelGGL(k_tile_reduce, dim3((unsigned)(8 * p.g.tail_per_xcd), (unsigned)(p.v->mb / 8)), dim3(256), 0,
+                           ctx->stream, p.g, p.v->mb, p.v->nt * p.v->wn * 32, ws, aux, out);
     }
-    return cnn::launch_check(ctx, "slice_reduce");
+    return cnn::launch_check(ctx, "tile_reduce");
 }
 
 }  // namespace

@@ -68,8 +68,10 @@ def test_validation_rejects_before_any_launch(L):
 
 def test_workspace_planning(L):
     ws = L.cnn_workspace_bytes
-    # forward never needs scratch; unknown shapes need none (they run on the plain kernels)
+    # a forward whose tiles fill whole rounds of the 256 compute units needs no scratch; one with an overhang keeps
+    # partial tiles of the sliced tail; unknown shapes need none (they run on the plain kernels)
     assert ws(binding.OP_CONV_FWD, 64, 256, 56, 56, 256, 3, 3, 1, 1) == 0
+    assert ws(binding.OP_CONV_FWD, 64, 512, 28, 28, 512, 3, 3, 1, 1) == 128 * 2 * 128 * 224 * 4
     assert ws(binding.OP_CONV_BWD_WEIGHT, 2, 5, 9, 13, 7, 3, 2, 2, 1) == 0
     # first-layer weight gradient: private copies of dw, one per split of the minibatch's rows
     b = ws(binding.OP_CONV_BWD_WEIGHT, 2, 3, 32, 32, 16, 3, 3, 1, 1)
