@@ -16,8 +16,16 @@
 // The two halves of the 64-lane wave feed k = 0 and k = 1 of the MFMA: the low half walks channels [0, CB/2) of the
 // chunk and the high half [CB/2, CB), so both halves use the same offsets.
 // Two LDS buffers: while chunk ch is multiplied, chunk ch+1 moves from registers into the other buffer and chunk
-// ch+2 from HBM into those registers, one staging item between every MFMA step (no staging phase, one barrier per
-// chunk).
+// ch+2 from HBM into those registers, a few staging items between the MFMA groups (no staging phase, one barrier
+// per chunk).  Every instruction that is not an MFMA costs matrix-pipe time here (measured: about 1 % per dozen
+// instructions in the chunk loop), so the loop is kept lean:
+//  * staging loads are raw buffer loads: the address is (descriptor base) + (scalar channel offset) + (per-thread
+//    byte offset computed once); positions outside the image carry an offset beyond the descriptor's range, for
+//    which the hardware returns 0 - no bounds selects, no 64-bit address arithmetic;
+//  * threads and filter rows beyond the tile repeat the last valid one's work (same value to the same LDS word);
+//  * operands are read per segment of TG taps of one kernel row: the TG consecutive words of a lane come from one
+//    base address (paired LDS reads), one segment ahead of the MFMAs that use them - also across the chunk barrier;
+//  * the hot layer shapes get instantiations with compile-time LDS strides, so all operand offsets are immediates.
 #include <stdio.h>
 #include <stdlib.h>
 
@@ -26,6 +34,7 @@
 namespace {
 
 typedef float f32x16 __attribute__((ext_vector_type(16)));
+typedef __attribute__((address_space(3))) float lds_float;      // LDS pointers are 32-bit: one VGPR each
 
 // epilogues: plain store; ReLU of the result; result where aux > 0 else 0 (ReLU derivative, aux = the ReLU's output)
 enum { EPI_NONE = 0, EPI_RELU = 1, EPI_MASK = 2 };
@@ -51,9 +60,11 @@ struct ConvGeo {
 
 // VEC = 4: filter rows are fetched as float4 (needs J % CB == 0 and 16-byte aligned rows); VEC = 1: element-wise
 // fetch with the channels past J zero-filled (first layers: J = 3).  XP: input-tile positions per thread per channel.
-template <int R_, int S_, int CB_, int WM_, int WN_, int NT_, int VEC_, int XP_>
+// TG: taps per operand segment.  WLDP / PLANEP: compile-time LDS row / channel strides (0 = run-time values).
+template <int R_, int S_, int CB_, int WM_, int WN_, int NT_, int VEC_, int XP_, int TG_, int WLDP_, int PLANEP_>
 struct ConvCfg {
-    static constexpr int R = R_, S = S_, CB = CB_, WM = WM_, WN = WN_, NT = NT_, VEC = VEC_, XP = XP_;
+    static constexpr int R = R_, S = S_, CB = CB_, WM = WM_, WN = WN_, NT = NT_, VEC = VEC_, XP = XP_, TG = TG_;
+    static constexpr int WLDP_CT = WLDP_, PLANEP_CT = PLANEP_;
     static constexpr int RS = R * S;
     static constexpr int MB = 32 * WM;
     static constexpr int NPIXB = WN * NT * 32;               // pixel capacity of a tile
@@ -64,16 +75,21 @@ struct ConvCfg {
     static constexpr int RPP = T / Q4;                       // filter rows fetched per pass of the workgroup
     static constexpr int WSL = (MB + RPP - 1) / RPP;         // passes
     static constexpr int MAXPLANE = XP * T;                  // staged elements per channel the threads can cover
+    static constexpr int SEG = (S + TG - 1) / TG;            // operand segments per kernel row
+    static constexpr int NSEG = (CB / 2) * R * SEG;          // ... per chunk (each wave half walks CB/2 channels)
     static_assert(CB % 2 == 0, "the two wave halves split the chunk's channels");
     static_assert(KCH % VEC == 0 && (VEC == 1 || VEC == 4), "filter tile is fetched as float4 or float");
     static_assert(Q4 <= T, "one pass fetches at least one filter row");
 };
 
+constexpr int kOutOfRange = (int)0x80000000;   // buffer-load byte offset beyond any descriptor used here -> reads 0
+constexpr int kRsrcWord3 = 0x00020000;         // raw buffer descriptor of 32-bit elements
+
 template <class G>
 __global__ void __launch_bounds__(G::T, 2)
 k_conv_tiled(ConvGeo g, const float* __restrict__ in, const float* __restrict__ wt, const float* __restrict__ aux,
              float* __restrict__ out_base, float* __restrict__ partial) {
-    constexpr int S = G::S, RS = G::RS, CB = G::CB, NT = G::NT, T = G::T;
+    constexpr int R = G::R, S = G::S, RS = G::RS, CB = G::CB, NT = G::NT, T = G::T, TG = G::TG;
     extern __shared__ float lds[];
     float* wl = lds;
     float* xl = lds + G::MB * G::WSTR;
@@ -83,6 +99,8 @@ k_conv_tiled(ConvGeo g, const float* __restrict__ in, const float* __restrict__ 
     const int half = lane >> 5, l32 = lane & 31;
     const int wm = wave % G::WM, wn = wave / G::WM;
     const int N = g.N, J = g.J, M = g.M;
+    const int WLDP = G::WLDP_CT ? G::WLDP_CT : g.WLDP;
+    const int PLANEP = G::PLANEP_CT ? G::PLANEP_CT : g.PLANEP;
 
     // Workgroups are handed to the 8 XCDs round-robin by linear id.  Give each XCD (its own L2) a contiguous range
     // of pixel tiles and run the output-feature tiles of one pixel tile back to back on it, so the input tile, and
@@ -102,40 +120,40 @@ k_conv_tiled(ConvGeo g, const float* __restrict__ in, const float* __restrict__ 
 
     const int plane_g = g.HI * g.WI;
     const size_t in_img = (size_t)J * plane_g;         // elements per image of `in`
-    const float* in_base = in + (size_t)n0 * in_img;
+    // descriptors: the input from the tile's first image to the end of the tensor, and the whole filter tensor
+    // (the planner keeps every offset used below 2^31 bytes)
+    const size_t in_left = (size_t)(N - n0) * in_img * sizeof(float);
+    const __amdgpu_buffer_rsrc_t rs_in = __builtin_amdgcn_make_buffer_rsrc(
+        const_cast<float*>(in + (size_t)n0 * in_img), 0, in_left > 0x7fffffffu ? 0x7fffffff : (int)in_left, kRsrcWord3);
+    const __amdgpu_buffer_rsrc_t rs_w = __builtin_amdgcn_make_buffer_rsrc(
+        const_cast<float*>(wt), 0, (int)((size_t)M * J * RS * sizeof(float)), kRsrcWord3);
 
     // ---- input tile staging: each thread owns XP positions of the (image, row, col) plane and fetches them for
-    //      every channel of the chunk.  Everything in the chunk loop is branch-free: a position outside the image
-    //      loads a harmless in-range address and is replaced by zero when it is written to LDS, a position outside
-    //      the tile writes to a per-lane dummy word behind the two buffers.  (Branches around the loads made the
-    //      compiler wait for ALL outstanding loads at every staging item.)
-    float* const lds_dummy = lds + 2 * g.lds_buf + lane;
-    int xoff[G::XP], xpos[G::XP];
-    bool xok[G::XP], xin[G::XP];
+    //      every channel of the chunk: byte offset within one channel (or kOutOfRange) and LDS position
+    int xvo[G::XP], xpos[G::XP];
 #pragma unroll
     for (int j = 0; j < G::XP; ++j) {
-        const int e = tid + j * T;
-        int off = 0, pos = 0;
-        bool ok = false;
-        if (e < g.PLANE) {
-            const int per_img = g.THI * g.WLD;
-            const int nb = e / per_img, rem = e % per_img;
-            const int row = rem / g.WLD, col = rem % g.WLD;
-            const int h = p0 * g.stride - g.pad + row, w = col - g.pad;
-            pos = nb * g.IMGSTR + row * g.WLDP + col;
-            if (n0 + nb < N && h >= 0 && h < g.HI && w >= 0 && w < g.WI) {
-                off = nb * (int)in_img + h * g.WI + w;
-                ok = true;
-            }
-        }
-        xoff[j] = off;
-        xpos[j] = pos;
-        xok[j] = ok;
-        xin[j] = e < g.PLANE;
+        const int e = min(tid + j * T, g.PLANE - 1);
+        const int per_img = g.THI * g.WLD;
+        const int nb = e / per_img, rem = e % per_img;
+        const int row = rem / g.WLD, col = rem % g.WLD;
+        const int h = p0 * g.stride - g.pad + row, w = col - g.pad;
+        xpos[j] = nb * g.IMGSTR + row * WLDP + col;
+        const bool ok = n0 + nb < N && h >= 0 && h < g.HI && w >= 0 && w < g.WI;
+        xvo[j] = ok ? (int)((nb * (int)in_img + h * g.WI + w) * sizeof(float)) : kOutOfRange;
     }
     // ---- filter tile staging: thread = (row m_sub, fetch unit kq) of a pass over RPP rows
-    const int w_msub = tid / G::Q4, w_kq = tid % G::Q4;
-    const bool w_thread = tid < G::RPP * G::Q4;
+    const int wtid = min(tid, G::RPP * G::Q4 - 1);
+    const int w_msub = wtid / G::Q4, w_kq = wtid % G::Q4;
+    int wvo[G::WSL], wpos[G::WSL];
+#pragma unroll
+    for (int i = 0; i < G::WSL; ++i) {
+        const int m = min(w_msub + i * G::RPP, G::MB - 1);
+        const int mrow = min(m0 + m, M - 1);          // rows past M repeat the last one (their results are not stored)
+        wvo[i] = (int)((mrow * J * RS + w_kq * G::VEC) * sizeof(float));
+        if (G::VEC == 1 && w_kq >= J * RS) wvo[i] = kOutOfRange;     // J < CB: one chunk, its missing channels are zero
+        wpos[i] = m * G::WSTR + w_kq * G::VEC;
+    }
 
     // ---- per-lane LDS read bases
     const int a_base = (wm * 32 + l32) * G::WSTR + half * (CB / 2) * RS;
@@ -147,9 +165,9 @@ k_conv_tiled(ConvGeo g, const float* __restrict__ in, const float* __restrict__ 
         if (i < g.NPIX) {
             const int per_img = g.TH * g.WO;
             const int nb = i / per_img, rem = i % per_img;
-            o = nb * g.IMGSTR + (rem / g.WO) * g.stride * g.WLDP + (rem % g.WO) * g.stride;
+            o = nb * g.IMGSTR + (rem / g.WO) * g.stride * WLDP + (rem % g.WO) * g.stride;
         }
-        b_base[j] = o + half * (CB / 2) * g.PLANEP;
+        b_base[j] = o + half * (CB / 2) * PLANEP;
     }
 
     f32x16 acc[NT];
@@ -160,125 +178,150 @@ k_conv_tiled(ConvGeo g, const float* __restrict__ in, const float* __restrict__ 
 
     float xr[CB][G::XP];
     float4 wr[G::WSL];
-    // per-pass filter source row (clamped into the tensor), validity and LDS destination
-    const float* w_row[G::WSL];
-    bool w_ok[G::WSL];
-    int w_pos[G::WSL];
-#pragma unroll
-    for (int i = 0; i < G::WSL; ++i) {
-        const int m = w_msub + i * G::RPP;
-        const bool in_tile = w_thread && m < G::MB;
-        w_ok[i] = in_tile && m0 + m < M;
-        const int mrow = w_ok[i] ? m0 + m : 0;
-        w_row[i] = wt + ((size_t)mrow * J) * RS + (w_thread ? w_kq * G::VEC : 0);
-        w_pos[i] = in_tile ? m * G::WSTR + w_kq * G::VEC : -1;
-    }
 
     // Staging is cut into items (one input-tile register or one filter-tile fetch unit each) so that it can be
-    // spread over the MFMA steps of a chunk instead of forming a phase of its own.
+    // spread over the MFMA groups of a chunk instead of forming a phase of its own.
     constexpr int NX = CB * G::XP, NITEMS = NX + G::WSL;
     auto fetch_item = [&](int it, int c0) {
         if (it < NX) {
             const int c = it / G::XP, j = it % G::XP;
-            const int cc = (G::VEC == 4 || c0 + c < J) ? c0 + c : 0;          // channels past J: any valid plane
-            xr[c][j] = in_base[(size_t)cc * plane_g + xoff[j]];
+            const int vo = (G::VEC == 4 || c0 + c < J) ? xvo[j] : kOutOfRange;     // channels past J are zero
+            xr[c][j] = __builtin_bit_cast(
+                float, __builtin_amdgcn_raw_buffer_load_b32(rs_in, vo, (c0 + c) * plane_g * (int)sizeof(float), 0));
         } else {
             // w[m][c0 .. c0+CB)[R][S]: CB*R*S contiguous floats per output feature
             const int i = it - NX;
-            if (G::VEC == 4) {
-                wr[i] = *reinterpret_cast<const float4*>(w_row[i] + (size_t)c0 * RS);
-            } else {
-                const int o = c0 * RS + w_kq < J * RS ? c0 * RS : 0;
-                wr[i].x = w_row[i][o];
-            }
+            if (G::VEC == 4)
+                wr[i] = __builtin_bit_cast(
+                    float4, __builtin_amdgcn_raw_buffer_load_b128(rs_w, wvo[i], c0 * RS * (int)sizeof(float), 0));
+            else
+                wr[i].x = __builtin_bit_cast(float, __builtin_amdgcn_raw_buffer_load_b32(rs_w, wvo[i], 0, 0));
         }
     };
-    auto stage_item = [&](int it, int buf, int c0) {
+    // LDS addresses are kept in registers as 32-bit pointers and moved to the other buffer once per chunk; everything
+    // else is an immediate offset.  (Left to itself the compiler recomputes them for every segment.)
+    lds_float* xw[G::XP];                       // staging destinations, channel 0 of the chunk
+    lds_float* ww[G::WSL];
+    const lds_float* bp[CB / 2][NT];            // B operand bases per channel of this wave half
+    const lds_float* ap;                        // A operand base
+#pragma unroll
+    for (int j = 0; j < G::XP; ++j) xw[j] = (lds_float*)(xl + xpos[j]);
+#pragma unroll
+    for (int i = 0; i < G::WSL; ++i) ww[i] = (lds_float*)(wl + wpos[i]);
+#pragma unroll
+    for (int cc = 0; cc < CB / 2; ++cc)
+#pragma unroll
+        for (int j = 0; j < NT; ++j) bp[cc][j] = (const lds_float*)(xl + b_base[j] + cc * PLANEP);
+    ap = (const lds_float*)(wl + a_base);
+    // wdelta = +-(elements of one buffer): the staging pointers move by it, the operand pointers the other way
+    auto flip = [&](int wdelta) {
+#pragma unroll
+        for (int j = 0; j < G::XP; ++j) { xw[j] += wdelta; asm volatile("" : "+v"(xw[j])); }
+#pragma unroll
+        for (int i = 0; i < G::WSL; ++i) { ww[i] += wdelta; asm volatile("" : "+v"(ww[i])); }
+#pragma unroll
+        for (int cc = 0; cc < CB / 2; ++cc)
+#pragma unroll
+            for (int j = 0; j < NT; ++j) { bp[cc][j] -= wdelta; asm volatile("" : "+v"(bp[cc][j])); }
+        ap -= wdelta;
+        asm volatile("" : "+v"(ap));
+    };
+
+    auto stage_item = [&](int it) {
         if (it < NX) {
             const int c = it / G::XP, j = it % G::XP;
-            const bool ok = xok[j] && (G::VEC == 4 || c0 + c < J);
-            float* d = xin[j] ? xl + (buf * g.lds_buf + c * g.PLANEP + xpos[j]) : lds_dummy;
-            *d = ok ? xr[c][j] : 0.f;
+            xw[j][c * PLANEP] = xr[c][j];
         } else {
             const int i = it - NX;
-            float* d = w_pos[i] >= 0 ? wl + (buf * g.lds_buf + w_pos[i]) : lds_dummy;
-            if (G::VEC == 4) {
-                d[0] = w_ok[i] ? wr[i].x : 0.f; d[1] = w_ok[i] ? wr[i].y : 0.f;
-                d[2] = w_ok[i] ? wr[i].z : 0.f; d[3] = w_ok[i] ? wr[i].w : 0.f;
-            } else {
-                d[0] = (w_ok[i] && c0 * RS + w_kq < J * RS) ? wr[i].x : 0.f;
-            }
+            ww[i][0] = wr[i].x;
+            if (G::VEC == 4) { ww[i][1] = wr[i].y; ww[i][2] = wr[i].z; ww[i][3] = wr[i].w; }
         }
     };
 
+    // Operands of segment `seg` of a chunk: TG (or fewer, at the end of a kernel row) taps of one (channel, kernel
+    // row): a[t] for this lane's output feature, b[j][t] for its pixel of block j.
+    auto read_seg = [&](int seg, float (&a)[TG], float (&b)[NT][TG]) {
+        const int cc = seg / (R * G::SEG), r = (seg / G::SEG) % R, s0 = (seg % G::SEG) * TG;
+        const int len = TG < S - s0 ? TG : S - s0;
+#pragma unroll
+        for (int t = 0; t < len; ++t) a[t] = ap[cc * RS + r * S + s0 + t];
+#pragma unroll
+        for (int j = 0; j < NT; ++j)
+#pragma unroll
+            for (int t = 0; t < len; ++t) b[j][t] = bp[cc][j][r * WLDP + s0 + t];
+    };
+
     // Two LDS buffers.  While chunk ch is multiplied out of buffer ch&1, chunk ch+1 goes from registers into the
-    // other buffer and chunk ch+2 from HBM into those registers, item by item between the MFMA steps, so neither
-    // the LDS writes nor the global-load issue ever stall the matrix pipe for a whole phase.  One barrier per chunk.
-    // The last iterations stage and fetch a clamped chunk again instead of branching (harmless: that buffer is
-    // never read), which keeps the chunk body one basic block.
+    // other buffer and chunk ch+2 from HBM into those registers, item by item between the MFMA groups.  One barrier
+    // per chunk, placed before the MFMAs of the chunk's last segment: the first operands of the next chunk are read
+    // behind it while those MFMAs run.  The last iterations stage and fetch a clamped chunk again instead of
+    // branching (harmless: that buffer is never read for results), which keeps the chunk body one basic block.
     // A tail workgroup (slice >= 0) covers only its slice of the contraction and writes a partial tile.
     const int nchunks = (J + CB - 1) / CB;
     const int ch_begin = slice < 0 ? 0 : slice * g.chunks_per_slice;
     const int ch_end = slice < 0 ? nchunks : min(ch_begin + g.chunks_per_slice, nchunks);
     const size_t out_plane = (size_t)g.HO * g.WO;
-    constexpr int STEPS = (CB / 2) * RS, IPS = (NITEMS + STEPS - 1) / STEPS;
+    constexpr int NSEG = G::NSEG, IPS = (NITEMS + NSEG - 1) / NSEG;
 #pragma unroll
     for (int it = 0; it < NITEMS; ++it) fetch_item(it, ch_begin * CB);
 #pragma unroll
-    for (int it = 0; it < NITEMS; ++it) stage_item(it, 0, ch_begin * CB);
+    for (int it = 0; it < NITEMS; ++it) stage_item(it);
     {
         const int c1 = min(ch_begin + 1, ch_end - 1) * CB;
 #pragma unroll
         for (int it = 0; it < NITEMS; ++it) fetch_item(it, c1);
     }
     __syncthreads();
+    float a_cur[TG] = {}, b_cur[NT][TG] = {};
+    read_seg(0, a_cur, b_cur);
+    // from here on: reads from buffer (ch - ch_begin) & 1, staging writes to the other one
+#pragma unroll
+    for (int j = 0; j < G::XP; ++j) xw[j] += g.lds_buf;
+#pragma unroll
+    for (int i = 0; i < G::WSL; ++i) ww[i] += g.lds_buf;
     for (int ch = ch_begin; ch < ch_end; ++ch) {
-        const int buf = (ch - ch_begin) & 1;
-        const int c1 = min(ch + 1, ch_end - 1) * CB;      // chunk held in the staging registers
-        const int c2 = min(ch + 2, ch_end - 1) * CB;
-        const float* wb = wl + buf * g.lds_buf + a_base;
-        const float* xb = xl + buf * g.lds_buf;
-        // operands of step t+1 are read from LDS before the MFMAs of step t are issued; the scheduling barrier
-        // after each step keeps the compiler from regrouping the staging loads (which would bunch them at the end
-        // of the chunk, right before they are needed)
-        float a_cur = wb[0], b_cur[NT];
+        const int c2 = min(ch + 2, ch_end - 1) * CB;      // the staging registers hold chunk min(ch + 1, ch_end - 1)
+        const int wdelta = ((ch - ch_begin) & 1) ? g.lds_buf : -g.lds_buf;   // where the write pointers go next
 #pragma unroll
-        for (int j = 0; j < NT; ++j) b_cur[j] = xb[b_base[j]];
-#pragma unroll
-        for (int step = 0; step < STEPS; ++step) {
+        for (int seg = 0; seg < NSEG; ++seg) {
 #pragma unroll
             for (int u = 0; u < IPS; ++u) {
-                const int it = step * IPS + u;
+                const int it = seg * IPS + u;
                 if (it < NITEMS) {
-                    stage_item(it, buf ^ 1, c1);
+                    stage_item(it);
                     fetch_item(it, c2);
                 }
             }
-            float a_nxt = 0.f, b_nxt[NT];
-            if (step + 1 < STEPS) {
-                const int n1 = step + 1, cc = n1 / RS, r = (n1 % RS) / S, s2 = n1 % S;
-                a_nxt = wb[n1];
-                const float* xs = xb + (cc * g.PLANEP + r * g.WLDP + s2);
-#pragma unroll
-                for (int j = 0; j < NT; ++j) b_nxt[j] = xs[b_base[j]];
+            float a_nxt[TG] = {}, b_nxt[NT][TG] = {};
+            if (seg + 1 < NSEG) {
+                read_seg(seg + 1, a_nxt, b_nxt);
+            } else {
+                __syncthreads();
+                flip(wdelta);
+                read_seg(0, a_nxt, b_nxt);
             }
+            const int s0 = (seg % G::SEG) * TG, len = TG < S - s0 ? TG : S - s0;
 #pragma unroll
-            for (int j = 0; j < NT; ++j) acc[j] = __builtin_amdgcn_mfma_f32_32x32x2f32(a_cur, b_cur[j], acc[j], 0, 0, 0);
-            // issue order inside the step: one MFMA, then two of the next step's LDS reads, and so on, so the
-            // reads complete under the remaining MFMAs instead of being exposed at the start of the next step
+            for (int t = 0; t < len; ++t)
 #pragma unroll
-            for (int j = 0; j < NT; ++j) {
+                for (int j = 0; j < NT; ++j)
+                    acc[j] = __builtin_amdgcn_mfma_f32_32x32x2f32(a_cur[t], b_cur[j][t], acc[j], 0, 0, 0);
+            // issue order inside the segment: one MFMA, then one of the next segment's LDS reads, and so on, so the
+            // reads complete under the remaining MFMAs instead of being exposed at the start of the next segment;
+            // the scheduling barrier keeps the staging items from being regrouped across segments
+#pragma unroll
+            for (int k = 0; k < NT * len; ++k) {
                 __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);   // 1 MFMA
-                __builtin_amdgcn_sched_group_barrier(0x100, 2, 0);   // 2 DS reads
+                __builtin_amdgcn_sched_group_barrier(0x100, 1, 0);   // 1 DS read
             }
             __builtin_amdgcn_sched_barrier(0);
-            if (step + 1 < STEPS) {
-                a_cur = a_nxt;
 #pragma unroll
-                for (int j = 0; j < NT; ++j) b_cur[j] = b_nxt[j];
+            for (int t = 0; t < TG; ++t) {
+                a_cur[t] = a_nxt[t];
+#pragma unroll
+                for (int j = 0; j < NT; ++j) b_cur[j][t] = b_nxt[j][t];
             }
         }
-        __syncthreads();
     }
 
     // ---- epilogue: lane = pixel (coalesced along the row), register v = output feature
@@ -391,8 +434,8 @@ int launch(cnn_ctx* ctx, const LaunchArgs& a) {
     dim3 grid((unsigned)(8 * (a.g.full_per_xcd + a.g.tail_per_xcd * a.g.nsl)));
     static char name[96] = "";
     if (!name[0])
-        snprintf(name, sizeof(name), "k_conv_tiled<%dx%d CB%d WM%d WN%d NT%d%s>", G::R, G::S, G::CB, G::WM, G::WN, G::NT,
-                 G::VEC == 1 ? " v1" : "");
+        snprintf(name, sizeof(name), "k_conv_tiled<%dx%d CB%d WM%d WN%d NT%d%s%s>", G::R, G::S, G::CB, G::WM, G::WN, G::NT,
+                 G::VEC == 1 ? " v1" : "", G::WLDP_CT ? " fixed" : "");
     {
         cnn::ProfScope ps(ctx, name, 2.0 * a.g.N * a.g.J * a.g.M * G::RS * a.g.HO * a.g.WO);
         hipLaunchKernelGGL(k_conv_tiled<G>, grid, dim3(G::T), a.lds_bytes, ctx->stream, a.g, a.in, a.wt, a.aux, a.out,
@@ -401,23 +444,30 @@ int launch(cnn_ctx* ctx, const LaunchArgs& a) {
     return cnn::launch_check(ctx, "conv_tiled");
 }
 
-// Instantiations: one per (kernel size, tile shape).  `mb`, `wn`, `nt`: features per tile, wave columns, pixel blocks
-// per wave; `maxplane`: staged input elements per channel the workgroup's threads can cover.
+// Instantiations: one per (kernel size, tile shape, LDS strides).  `mb`, `wn`, `nt`: features per tile, wave columns,
+// pixel blocks per wave; `maxplane`: staged input elements per channel the workgroup's threads can cover; `wldp`,
+// `planep`: the LDS strides the instantiation is compiled for (0: any, taken from the launch geometry).
 struct Variant {
-    int R, S, CB, vec, mb, wn, nt, threads, maxplane, wstr;
+    int R, S, CB, vec, mb, wn, nt, threads, maxplane, wstr, wldp, planep;
     LaunchFn fn;
 };
-#define V(R_, S_, CB_, WM_, WN_, NT_, VEC_, XP_)                                                                   \
-    {R_, S_, CB_, VEC_, 32 * WM_, WN_, NT_, 64 * WM_ * WN_, ConvCfg<R_, S_, CB_, WM_, WN_, NT_, VEC_, XP_>::MAXPLANE, \
-     ConvCfg<R_, S_, CB_, WM_, WN_, NT_, VEC_, XP_>::WSTR, launch<ConvCfg<R_, S_, CB_, WM_, WN_, NT_, VEC_, XP_>>}
+#define V(R_, S_, CB_, WM_, WN_, NT_, VEC_, XP_, TG_, WLDP_, PLANEP_)                                              \
+    {R_, S_, CB_, VEC_, 32 * WM_, WN_, NT_, 64 * WM_ * WN_,                                                        \
+     ConvCfg<R_, S_, CB_, WM_, WN_, NT_, VEC_, XP_, TG_, WLDP_, PLANEP_>::MAXPLANE,                                \
+     ConvCfg<R_, S_, CB_, WM_, WN_, NT_, VEC_, XP_, TG_, WLDP_, PLANEP_>::WSTR, WLDP_, PLANEP_,                    \
+     launch<ConvCfg<R_, S_, CB_, WM_, WN_, NT_, VEC_, XP_, TG_, WLDP_, PLANEP_>>}
 const Variant kVariants[] = {
-    // 3x3: 128-feature tiles (4 waves) and 64-feature tiles (2 waves), 7 / 8 / 9 pixel blocks per wave
-    V(3, 3, 4, 4, 1, 7, 4, 2), V(3, 3, 4, 4, 1, 8, 4, 2), V(3, 3, 4, 4, 1, 9, 4, 2),
-    V(3, 3, 4, 2, 1, 7, 4, 4), V(3, 3, 4, 2, 1, 8, 4, 4),
+    // 3x3, 128-feature tiles (4 waves), strides of the 3x3 / pad 1 layers of VGG-A at 112, 56, 28 and 14 pixels and
+    // of OverFeat-FAST at 12 pixels (both passes share them: backpropagation has pad' = 1 too)
+    V(3, 3, 4, 4, 1, 7, 4, 2, 3, 144, 576), V(3, 3, 4, 4, 1, 7, 4, 2, 3, 88, 544), V(3, 3, 4, 4, 1, 7, 4, 2, 3, 60, 736),
+    V(3, 3, 4, 4, 1, 7, 4, 2, 3, 46, 740), V(3, 3, 4, 4, 1, 9, 4, 2, 1, 44, 1248),
+    // 3x3, any strides: 128-feature tiles (4 waves) and 64-feature tiles (2 waves), 7 / 8 / 9 pixel blocks per wave
+    V(3, 3, 4, 4, 1, 7, 4, 2, 3, 0, 0), V(3, 3, 4, 4, 1, 8, 4, 2, 3, 0, 0), V(3, 3, 4, 4, 1, 9, 4, 2, 1, 0, 0),
+    V(3, 3, 4, 2, 1, 7, 4, 4, 3, 0, 0), V(3, 3, 4, 2, 1, 8, 4, 4, 1, 0, 0),
     // 3x3 with fewer than 4 contraction channels (first layers)
-    V(3, 3, 4, 2, 2, 7, 1, 4),
+    V(3, 3, 4, 2, 2, 7, 1, 4, 3, 0, 0),
     // 5x5: 64-feature tiles, two wave columns
-    V(5, 5, 4, 2, 2, 3, 4, 4), V(5, 5, 4, 2, 2, 4, 4, 4), V(5, 5, 4, 2, 2, 7, 4, 4),
+    V(5, 5, 4, 2, 2, 3, 4, 4, 2, 0, 0), V(5, 5, 4, 2, 2, 4, 4, 4, 2, 0, 0), V(5, 5, 4, 2, 2, 7, 4, 4, 2, 0, 0),
 };
 #undef V
 
@@ -433,6 +483,8 @@ struct ConvPlan {
 // when the output alone gives fewer workgroups than the chip runs at once.
 bool make_plan(int R, int S, int pad, int stride, int N, int J, int M, int HI, int WI, ConvPlan* p) {
     if (HI + 2 * pad < R || WI + 2 * pad < S) return false;
+    // byte offsets inside the kernel are 32-bit: the filter tensor, and (below) the images of one pixel tile
+    if ((size_t)M * J * R * S * sizeof(float) >= 0x7fffffffu) return false;
     const int HO = (HI + 2 * pad - R) / stride + 1, WO = (WI + 2 * pad - S) / stride + 1;
     const int WLD = WI + 2 * pad;
     double best = 0.0;
@@ -450,6 +502,7 @@ bool make_plan(int R, int S, int pad, int stride, int N, int J, int M, int HI, i
             const int THI = (TH - 1) * stride + R;
             while (NB > 1 && NB * THI * WLD > v.maxplane) --NB;     // the threads must cover the staged plane
             if (NB * THI * WLD > v.maxplane) continue;
+            if ((size_t)NB * J * HI * WI * sizeof(float) >= 0x7fffffffu) continue;
             const int row_tiles = (HO + TH - 1) / TH, img_tiles = (N + NB - 1) / NB;
             const double eff = ((double)N * HO * WO) / ((double)row_tiles * img_tiles * cap);
             for (int padded = (stride == 1 ? 1 : 0); padded >= 0; --padded) {
@@ -459,13 +512,16 @@ bool make_plan(int R, int S, int pad, int stride, int N, int J, int M, int HI, i
                 const int IMGSTR = padded ? IMG0 + ((((TH - 1) * WLDP + WO - IMG0) % 32) + 32) % 32 : IMG0;
                 const int PLANEP = NB * IMGSTR;
                 const int lds_buf = v.mb * v.wstr + v.CB * PLANEP;
-                const size_t lds_bytes = ((size_t)lds_buf * 2 + 64) * 4;   // two buffers + 64 dummy words
+                const size_t lds_bytes = (size_t)lds_buf * 2 * sizeof(float);   // two buffers
                 if (lds_bytes > 156 * 1024) continue;
+                // an instantiation compiled for fixed LDS strides serves exactly those
+                if (v.wldp && (v.wldp != WLDP || v.planep != PLANEP)) continue;
                 // score: MFMA lanes doing useful work, x 0.9 if only one workgroup fits a compute unit, x 0.97 for
                 // the conflicting LDS layout, and a penalty for the share of staged rows that are halo (short tiles
                 // re-stage the same rows; measured on 14x14 and 24x24 layers)
                 double score = eff * (lds_bytes <= 78 * 1024 ? 1.0 : 0.9) * (padded || stride != 1 ? 1.0 : 0.97);
                 score *= 1.0 - 0.3 * (double)(R - 1) / (TH * stride + R - 1);
+                if (v.wldp) score *= 1.03;                          // operand offsets are immediates
                 if (found && score <= best + 1e-9) continue;
                 found = true;
                 best = score;
