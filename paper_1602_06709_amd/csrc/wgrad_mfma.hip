@@ -22,6 +22,10 @@
 namespace {
 
 typedef float f32x16 __attribute__((ext_vector_type(16)));
+typedef __attribute__((address_space(3))) float lds_float;      // LDS pointers are 32-bit: one VGPR each
+
+constexpr int kOutOfRange = (int)0x80000000;   // buffer-load byte offset beyond any descriptor used here -> reads 0
+constexpr int kRsrcWord3 = 0x00020000;         // raw buffer descriptor of 32-bit elements
 
 struct WgGeo {
     int N, C, K, HI, WI, HO, WO, pad;
@@ -30,15 +34,27 @@ struct WgGeo {
     int col_tiles, rows_per_split, total_rows;
 };
 
-template <int R_, int S_, int KW_, int CW_, int RW_, int NSLOT_>
+// TW_ / NBI_ != 0: the step geometry (output columns per tile, images per step) is a compile-time constant, C and K
+// are multiples of the tile and every wave's feature rows lie inside it; the pixel-pair loop is then fully unrolled
+// with immediate LDS offsets.  TW_ = 0: everything is a run-time value.
+template <int R_, int S_, int KW_, int CW_, int RW_, int NSLOT_, int TW_ = 0, int NBI_ = 0>
 struct WgCfg {
     static constexpr int R = R_, S = S_, KW = KW_, CW = CW_, RW = RW_, NSLOT = NSLOT_;
+    static constexpr int TW_CT = TW_, NBI_CT = NBI_;
+    static constexpr bool FIXED = TW_ != 0;
     static constexpr int RS = R * S, RPW = R / RW;
     static constexpr int KB = 32 * KW, CBK = 32 * CW;
     static constexpr int T = 64 * KW * CW * RW;
     static constexpr int NWAVE = T / 64;
     static constexpr int XS = (CBK + NWAVE - 1) / NWAVE, DS = (KB + NWAVE - 1) / NWAVE;   // rows staged per wave per step
+    // LDS strides per input / output feature: odd, so the 32 features of an operand read 32 different banks
+    static constexpr int xstr(int tw, int nbi) { return (nbi * NSLOT * (tw + S - 1)) | 1; }
+    static constexpr int dstr(int tw, int nbi) { return (nbi * tw) | 1; }
+    static constexpr int QLOOP_CT = NBI_ == 1 ? TW_ / 2 : TW_;                 // columns per wave half and image
+    static constexpr int NPAIRS_CT = (NBI_ == 1 ? 1 : NBI_ / 2) * ((QLOOP_CT + 1) / 2);
     static_assert(R % RW == 0 && NSLOT >= R + 1 && (NSLOT & (NSLOT - 1)) == 0, "ring geometry");
+    static_assert(!FIXED || (CBK % NWAVE == 0 && KB % NWAVE == 0 && QLOOP_CT % 2 == 0 && NBI_ * (TW_ + S - 1) <= 64),
+                  "fixed geometry: whole feature rows per wave, even column share per wave half");
 };
 
 template <class G>
@@ -46,12 +62,13 @@ __global__ void __launch_bounds__(G::T)
 k_wgrad(WgGeo g, const float* __restrict__ x, const float* __restrict__ dy, float* __restrict__ partial) {
     constexpr int R = G::R, S = G::S, NSLOT = G::NSLOT, T = G::T;
     const int N = g.N, C = g.C, K = g.K, HI = g.HI, WI = g.WI, HO = g.HO, WO = g.WO, PAD = g.pad;
-    const int TW = g.TW, NBI = g.NBI, WLD = g.WLD;
+    const int TW = G::FIXED ? G::TW_CT : g.TW, NBI = G::FIXED ? G::NBI_CT : g.NBI, WLD = TW + S - 1;
+    const int XSTR = G::xstr(TW, NBI), DSTR = G::dstr(TW, NBI);
     extern __shared__ float lds[];
     float* xl = lds;                                  // [CBK][XSTR]
-    float* dyl = lds + G::CBK * g.XSTR;               // [2][KB][DSTR]
+    float* dyl = lds + G::CBK * XSTR;                 // [2][KB][DSTR]
 
-    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+    const int tid = threadIdx.x, lane = tid & 63, wave = __builtin_amdgcn_readfirstlane(tid >> 6);   // wave-uniform
     const int half = lane >> 5, l32 = lane & 31;
     const int kw = wave % G::KW, cw = (wave / G::KW) % G::CW, rw = wave / (G::KW * G::CW);
 
@@ -64,27 +81,32 @@ k_wgrad(WgGeo g, const float* __restrict__ x, const float* __restrict__ dy, floa
     const int V = HO + R - 1;                         // input rows of one image incl. the zero rows above/below
 
     // zero the whole ring once (slots never written are never read, but must not hold NaN patterns)
-    for (int e = tid; e < G::CBK * g.XSTR; e += T) xl[e] = 0.f;
+    for (int e = tid; e < G::CBK * XSTR; e += T) xl[e] = 0.f;
 
-    // staging: wave w fetches feature rows w, w+NWAVE, ...; lane = position in the row(s) of the NBI images
-    int xo = -1, xlds = 0;
-    const int xb = lane / WLD;
+    // ---- staging: wave w moves feature rows w, w+NWAVE, ... (those past the tile repeat the tile's last row);
+    //      lane = position in the row(s) of the NBI images (lanes past the row repeat its last position).
+    //      Loads are raw buffer loads: descriptor base + scalar offset (image group, feature, row) + per-lane byte
+    //      offset; a lane whose position is outside the image, or whose image or row does not exist, carries an
+    //      offset beyond the descriptor's range and the hardware returns 0.  Features past C / K read whatever
+    //      follows (or 0 past the end of the tensor): their results are never stored.
+    const int lx = min(lane, NBI * WLD - 1), ld = min(lane, NBI * TW - 1);
+    const int xb = lx / WLD, db = ld / TW;
+    int xvo, dvo;
     {
-        const int col = lane % WLD, w = q0 - PAD + col;
-        if (lane < NBI * WLD) {
-            xlds = wave * g.XSTR + xb * NSLOT * WLD + col;
-            if (w >= 0 && w < WI) xo = (xb * C + c0 + wave) * HI * WI + w;
-        }
+        const int w = q0 - PAD + lx % WLD;
+        xvo = (w >= 0 && w < WI) ? (int)((xb * C * HI * WI + w) * sizeof(float)) : kOutOfRange;
+        dvo = (int)((db * K * HO * WO + q0 + ld % TW) * sizeof(float));
     }
-    int dyo = -1, dlds = 0;
-    const int db = lane / TW;
-    {
-        const int q = lane % TW;
-        if (lane < NBI * TW) {
-            dlds = wave * g.DSTR + db * TW + q;
-            dyo = (db * K + k0 + wave) * HO * WO + q0 + q;
-        }
-    }
+    const __amdgpu_buffer_rsrc_t rs_x =
+        __builtin_amdgcn_make_buffer_rsrc(const_cast<float*>(x), 0, (int)((size_t)N * C * HI * WI * sizeof(float)), kRsrcWord3);
+    const __amdgpu_buffer_rsrc_t rs_dy =
+        __builtin_amdgcn_make_buffer_rsrc(const_cast<float*>(dy), 0, (int)((size_t)N * K * HO * WO * sizeof(float)), kRsrcWord3);
+    // feature rows this wave stages: wave, wave + NWAVE, ... clamped to the tile's (and the tensor's) last row, as
+    // scalar row indices relative to the tile's first row; the scalar part of a buffer address is not range-checked
+    const int x_rows = min(G::CBK, C - c0), d_rows = min(G::KB, K - k0);
+    // staging destinations of this wave's first feature row (fixed geometry) or of the tile's first row
+    lds_float* const xw = (lds_float*)(xl + (G::FIXED ? wave * XSTR : 0) + xb * NSLOT * WLD + lx % WLD);   // + ring slot
+    lds_float* const dw_ = (lds_float*)(dyl + (G::FIXED ? wave * DSTR : 0) + db * TW + ld % TW);           // + buffer
 
     f32x16 acc[G::RPW][S];
 #pragma unroll
@@ -100,33 +122,69 @@ k_wgrad(WgGeo g, const float* __restrict__ x, const float* __restrict__ dy, floa
     const int a_delta = NBI * TW / 2;                                          // in dyl: pixels are contiguous
     const int b_delta = NBI == 1 ? TW / 2 : (NBI / 2) * NSLOT * WLD;           // in xl
     const int nb_loop = NBI == 1 ? 1 : NBI / 2, q_loop = NBI == 1 ? TW / 2 : TW;
-    const int a_base = (kw * 32 + l32) * g.DSTR + half * a_delta;
-    const int b_base = (cw * 32 + l32) * g.XSTR + half * b_delta;
+    const lds_float* const a_lane = (const lds_float*)(dyl + (kw * 32 + l32) * DSTR + half * a_delta);
+    const lds_float* const b_lane = (const lds_float*)(xl + (cw * 32 + l32) * XSTR + half * b_delta);
+    const int qh = (q_loop + 1) / 2, npairs = nb_loop * qh;                    // the pixels are taken two at a time
 
     float xr[G::XS], dr[G::DS];
-    const size_t x_grp = (size_t)NBI * C * HI * WI, dy_grp = (size_t)NBI * K * HO * WO;
 
     // step u (virtual input row): image group = u / V, row within the zero-extended image = u % V
+    const int x_plane = HI * WI * (int)sizeof(float), d_plane = HO * WO * (int)sizeof(float);
     auto fetch = [&](int u) {
         const int grp = u / V, vr = u % V;
         const int h = vr - PAD, p = vr - (R - 1);
         const int nleft = N - grp * NBI;                 // images of this group that exist
-        const bool hv = h >= 0 && h < HI && xo >= 0 && xb < nleft;
-        const float* xs = x + grp * x_grp + (size_t)(h >= 0 && h < HI ? h : 0) * WI;
+        const int xo = (h >= 0 && h < HI && xb < nleft) ? xvo : kOutOfRange;
+        const int so = (((grp * NBI * C + c0) * HI + min(max(h, 0), HI - 1)) * WI) * (int)sizeof(float);
+        int sx = so + wave * x_plane;
 #pragma unroll
         for (int i = 0; i < G::XS; ++i) {
-            const int c = wave + i * G::NWAVE;
-            xr[i] = (hv && c < G::CBK && c0 + c < C) ? xs[xo + i * G::NWAVE * HI * WI] : 0.f;
+            const int off = G::FIXED ? sx : so + min(wave + i * G::NWAVE, x_rows - 1) * x_plane;
+            xr[i] = __builtin_bit_cast(float, __builtin_amdgcn_raw_buffer_load_b32(rs_x, xo, off, 0));
+            sx += G::NWAVE * x_plane;
         }
         const int gr = grp * HO + p;
         const bool rowv = p >= 0 && gr >= g_begin && gr < g_end;
-        const bool pv = rowv && dyo >= 0 && db < nleft;
-        const float* ds = dy + grp * dy_grp + (size_t)(rowv ? p : 0) * WO;
+        const int dyo = (rowv && db < nleft) ? dvo : kOutOfRange;
+        const int sd = (((grp * NBI * K + k0) * HO + min(max(p, 0), HO - 1)) * WO) * (int)sizeof(float);
+        int sy = sd + wave * d_plane;
 #pragma unroll
         for (int i = 0; i < G::DS; ++i) {
-            const int k = wave + i * G::NWAVE;
-            dr[i] = (pv && k < G::KB && k0 + k < K) ? ds[dyo + i * G::NWAVE * HO * WO] : 0.f;
+            const int off = G::FIXED ? sy : sd + min(wave + i * G::NWAVE, d_rows - 1) * d_plane;
+            dr[i] = __builtin_bit_cast(float, __builtin_amdgcn_raw_buffer_load_b32(rs_dy, dyo, off, 0));
+            sy += G::NWAVE * d_plane;
         }
+    };
+    // registers of step u -> ring slot u % NSLOT and dy buffer u % 2 (a wave past the tile's last feature row
+    // repeats that row: same value to the same word)
+    auto stage = [&](int u) {
+        lds_float* xd = xw + (u & (NSLOT - 1)) * WLD;
+#pragma unroll
+        for (int i = 0; i < G::XS; ++i) xd[(G::FIXED ? i * G::NWAVE : min(wave + i * G::NWAVE, G::CBK - 1)) * XSTR] = xr[i];
+        lds_float* dd = dw_ + (u & 1) * G::KB * DSTR;
+#pragma unroll
+        for (int i = 0; i < G::DS; ++i) dd[(G::FIXED ? i * G::NWAVE : min(wave + i * G::NWAVE, G::KB - 1)) * DSTR] = dr[i];
+    };
+
+    // operands of pixel pair (b, q) of step u: a[2], bv[r][S+1] (the two pixels' taps overlap in S-1 columns);
+    // `two` is false for the single last pixel of an odd row
+    auto load_pair = [&](const lds_float* ap, const lds_float* const (&bp)[G::RPW], bool two, float (&a)[2],
+                         float (&bv)[G::RPW][S + 1]) {
+        if (G::FIXED) two = true;
+        a[0] = ap[0];
+        a[1] = two ? ap[1] : 0.f;
+#pragma unroll
+        for (int r = 0; r < G::RPW; ++r) {
+#pragma unroll
+            for (int s2 = 0; s2 < S; ++s2) bv[r][s2] = bp[r][s2];
+            bv[r][S] = two ? bp[r][S] : 0.f;
+        }
+    };
+    // pointers to pair 0 of step u
+    auto step_ptrs = [&](int u, const lds_float*& ap, const lds_float* (&bp)[G::RPW]) {
+        ap = a_lane + (u & 1) * G::KB * DSTR;
+#pragma unroll
+        for (int r = 0; r < G::RPW; ++r) bp[r] = b_lane + ((u - (R - 1) + rw * G::RPW + r) & (NSLOT - 1)) * WLD;
     };
 
     if (g_begin < g_end) {
@@ -134,63 +192,101 @@ k_wgrad(WgGeo g, const float* __restrict__ x, const float* __restrict__ dy, floa
         const int u_last = ((g_end - 1) / HO) * V + ((g_end - 1) % HO) + R - 1;
         __syncthreads();   // ring zeroed
         fetch(u_begin);
+        stage(u_begin);
+        fetch(min(u_begin + 1, u_last));
+        __syncthreads();
+        // Step u first sends the registers holding step u+1 to the ring slot and dy buffer that step u does not read
+        // (last read before the previous barrier) and requests step u+2 from HBM.  Then it multiplies the output
+        // row that completes with input row u out of LDS, one pixel pair at a time, the next pair's operands being
+        // read while the current pair's MFMAs run.  One barrier per step, placed before the last pair's MFMAs: the
+        // first operands of step u+1 are read behind it while those MFMAs run.  Past the last step a clamped row
+        // is staged and fetched again instead of branching (same values to the same words).
+        const lds_float* ap;
+        const lds_float* bp[G::RPW];
+        float a_cur[2], b_cur[G::RPW][S + 1];
+        step_ptrs(u_begin, ap, bp);
+        load_pair(ap, bp, 1 < q_loop, a_cur, b_cur);
+        const int wrap_a = TW - 2 * (qh - 1), wrap_b = NSLOT * WLD - 2 * (qh - 1);   // last pair of an image -> next image
         for (int u = u_begin; u <= u_last; ++u) {
-            const int slot = u & (NSLOT - 1), buf = u & 1;
-            if (lane < NBI * WLD) {
-#pragma unroll
-                for (int i = 0; i < G::XS; ++i)
-                    if (wave + i * G::NWAVE < G::CBK) xl[xlds + i * G::NWAVE * g.XSTR + slot * WLD] = xr[i];
-            }
-            if (lane < NBI * TW) {
-#pragma unroll
-                for (int i = 0; i < G::DS; ++i)
-                    if (wave + i * G::NWAVE < G::KB) dyl[buf * G::KB * g.DSTR + dlds + i * G::NWAVE * g.DSTR] = dr[i];
-            }
-            __syncthreads();
-            if (u < u_last) fetch(u + 1);
             const int vr = u % V, p = vr - (R - 1);
             const int gr = (u / V) * HO + p;
-            if (p >= 0 && gr >= g_begin) {    // an output row completes at this step (gr < g_end by construction)
-                const float* ap = dyl + buf * G::KB * g.DSTR + a_base;
-                const float* bp = xl + b_base;
-                int so[G::RPW];
+            const int u1 = min(u + 1, u_last), u2 = min(u + 2, u_last);
+            stage(u1);
+            fetch(u2);
+            // pairs of this step: none unless an output row completes (gr < g_end by construction)
+            const int np = (p >= 0 && gr >= g_begin) ? npairs : 0;
+            auto mfmas = [&]() {
 #pragma unroll
-                for (int r = 0; r < G::RPW; ++r) so[r] = ((u - (R - 1) + rw * G::RPW + r) & (NSLOT - 1)) * WLD;
-                for (int b = 0; b < nb_loop; ++b) {
-                    const float* apb = ap + b * TW;
-                    const float* bpb = bp + b * NSLOT * WLD;
-                    // two pixels' operands are fetched before their 2 x RPW x S MFMAs are issued
-                    int q = 0;
-                    for (; q + 1 < q_loop; q += 2) {
-                        const float a0 = apb[q], a1 = apb[q + 1];
-                        float b0[G::RPW][S], b1[G::RPW][S];
+                for (int r = 0; r < G::RPW; ++r)
 #pragma unroll
-                        for (int r = 0; r < G::RPW; ++r)
+                    for (int s2 = 0; s2 < S; ++s2)
+                        acc[r][s2] = __builtin_amdgcn_mfma_f32_32x32x2f32(a_cur[0], b_cur[r][s2], acc[r][s2], 0, 0, 0);
 #pragma unroll
-                            for (int s = 0; s < S; ++s) {
-                                b0[r][s] = bpb[so[r] + q + s];
-                                b1[r][s] = bpb[so[r] + q + 1 + s];
-                            }
+                for (int r = 0; r < G::RPW; ++r)
 #pragma unroll
-                        for (int r = 0; r < G::RPW; ++r)
+                    for (int s2 = 0; s2 < S; ++s2)
+                        acc[r][s2] = __builtin_amdgcn_mfma_f32_32x32x2f32(a_cur[1], b_cur[r][s2 + 1], acc[r][s2], 0, 0, 0);
+            };
+            auto rotate = [&](const float (&an)[2], const float (&bn)[G::RPW][S + 1]) {
+                a_cur[0] = an[0]; a_cur[1] = an[1];
 #pragma unroll
-                            for (int s = 0; s < S; ++s)
-                                acc[r][s] = __builtin_amdgcn_mfma_f32_32x32x2f32(a0, b0[r][s], acc[r][s], 0, 0, 0);
+                for (int r = 0; r < G::RPW; ++r)
 #pragma unroll
-                        for (int r = 0; r < G::RPW; ++r)
+                    for (int s2 = 0; s2 <= S; ++s2) b_cur[r][s2] = bn[r][s2];
+            };
+            // one MFMA, then one of the next pair's LDS reads, and so on
+            auto interleave = [&]() {
 #pragma unroll
-                            for (int s = 0; s < S; ++s)
-                                acc[r][s] = __builtin_amdgcn_mfma_f32_32x32x2f32(a1, b1[r][s], acc[r][s], 0, 0, 0);
+                for (int k = 0; k < 2 * G::RPW * S; ++k) {
+                    __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);
+                    __builtin_amdgcn_sched_group_barrier(0x100, 1, 0);
+                }
+                __builtin_amdgcn_sched_barrier(0);
+            };
+            // all pairs but the last
+            if (np) {
+                if constexpr (G::FIXED) {
+                    // fully unrolled: pair i sits at compile-time offsets from the step's pointers
+                    constexpr int QH = (G::QLOOP_CT + 1) / 2;
+#pragma unroll
+                    for (int i = 1; i < G::NPAIRS_CT; ++i) {
+                        float a_nxt[2], b_nxt[G::RPW][S + 1];
+                        const int b = i / QH, q = 2 * (i % QH);
+                        const lds_float* bq[G::RPW];
+#pragma unroll
+                        for (int r = 0; r < G::RPW; ++r) bq[r] = bp[r] + (b * NSLOT * WLD + q);
+                        load_pair(ap + (b * TW + q), bq, true, a_nxt, b_nxt);
+                        mfmas();
+                        interleave();
+                        rotate(a_nxt, b_nxt);
                     }
-                    if (q < q_loop) {
-                        const float a = apb[q];
+                } else {
+                    int q = 0;
+                    for (int i = 1; i < np; ++i) {
+                        float a_nxt[2], b_nxt[G::RPW][S + 1];
+                        int qn = q + 2, da = 2, db2 = 2;
+                        if (qn >= q_loop) { qn = 0; da = wrap_a; db2 = wrap_b; }
+                        q = qn;
+                        ap += da;
 #pragma unroll
-                        for (int r = 0; r < G::RPW; ++r)
-#pragma unroll
-                            for (int s = 0; s < S; ++s)
-                                acc[r][s] = __builtin_amdgcn_mfma_f32_32x32x2f32(a, bpb[so[r] + q + s], acc[r][s], 0, 0, 0);
+                        for (int r = 0; r < G::RPW; ++r) bp[r] += db2;
+                        load_pair(ap, bp, qn + 1 < q_loop, a_nxt, b_nxt);
+                        mfmas();
+                        rotate(a_nxt, b_nxt);
                     }
                 }
+            }
+            // the last pair's MFMAs run behind the barrier, under the reads of the next step's first operands
+            {
+                float a_nxt[2], b_nxt[G::RPW][S + 1];
+                __syncthreads();
+                step_ptrs(u1, ap, bp);
+                load_pair(ap, bp, 1 < q_loop, a_nxt, b_nxt);
+                if (np) {
+                    mfmas();
+                    interleave();
+                }
+                rotate(a_nxt, b_nxt);
             }
         }
     }
@@ -243,6 +339,9 @@ template <class G>
 bool make_plan(const ConvShape& s, Plan* p) {
     if (s.stride != 1 || s.C < 16 || s.R != G::R || s.S != G::S) return false;
     if (s.P != s.H + 2 * s.pad - s.R + 1 || s.Q != s.W + 2 * s.pad - s.S + 1) return false;
+    // byte offsets inside the kernel are 32-bit
+    if ((size_t)s.N * s.C * s.H * s.W * sizeof(float) >= 0x7fffffffu) return false;
+    if ((size_t)s.N * s.K * s.P * s.Q * sizeof(float) >= 0x7fffffffu) return false;
     int best_tw = 0, best_nbi = 0;
     double best_score = 0.0;
     for (int tw = 1; tw <= s.Q && tw + G::S - 1 <= 64; ++tw) {
@@ -260,9 +359,8 @@ bool make_plan(const ConvShape& s, Plan* p) {
     WgGeo& g = p->g;
     g.N = s.N; g.C = s.C; g.K = s.K; g.HI = s.H; g.WI = s.W; g.HO = s.P; g.WO = s.Q; g.pad = s.pad;
     g.TW = best_tw; g.NBI = best_nbi; g.WLD = best_tw + G::S - 1;
-    const int xrow = g.NBI * G::NSLOT * g.WLD, drow = g.NBI * g.TW;
-    g.XSTR = (xrow & 1) ? xrow : xrow + 1;
-    g.DSTR = (drow & 1) ? drow : drow + 1;
+    g.XSTR = G::xstr(g.TW, g.NBI);
+    g.DSTR = G::dstr(g.TW, g.NBI);
     g.col_tiles = s.Q / g.TW;
     p->ktiles = (s.K + G::KB - 1) / G::KB;
     p->ctiles = (s.C + G::CBK - 1) / G::CBK;
@@ -304,7 +402,9 @@ int launch(cnn_ctx* ctx, const Plan& p, const ConvShape& s, const float* x, cons
     float* partial = reinterpret_cast<float*>(ctx->ws);
     dim3 grid((unsigned)(p.nsplit * p.g.col_tiles), (unsigned)p.ctiles, (unsigned)p.ktiles);
     static char name[96] = "";
-    if (!name[0]) snprintf(name, sizeof(name), "k_wgrad<%dx%d KW%d CW%d RW%d>", G::R, G::S, G::KW, G::CW, G::RW);
+    if (!name[0])
+        snprintf(name, sizeof(name), "k_wgrad<%dx%d KW%d CW%d RW%d%s>", G::R, G::S, G::KW, G::CW, G::RW,
+                 G::FIXED ? " fixed" : "");
     {
         cnn::ProfScope ps(ctx, name, cnn::conv_flops(s));
         hipLaunchKernelGGL(k_wgrad<G>, grid, dim3(G::T), p.lds_bytes, ctx->stream, p.g, x, dy, partial);
@@ -326,6 +426,12 @@ int launch(cnn_ctx* ctx, const Plan& p, const ConvShape& s, const float* x, cons
 // row per wave (10 waves)
 using Wg3 = WgCfg<3, 3, 4, 2, 1, 4>;
 using Wg5 = WgCfg<5, 5, 2, 1, 5, 8>;
+// 3x3 with whole tiles (C % 64 == 0, K % 128 == 0) and the step geometry (TW, NBI) of VGG-A's 112 / 56-pixel,
+// 28-pixel and 14-pixel layers and of OverFeat-FAST's 12-pixel layers
+using Wg3F56 = WgCfg<3, 3, 4, 2, 1, 4, 56, 1>;
+using Wg3F28 = WgCfg<3, 3, 4, 2, 1, 4, 28, 2>;
+using Wg3F14 = WgCfg<3, 3, 4, 2, 1, 4, 14, 4>;
+using Wg3F12 = WgCfg<3, 3, 4, 2, 1, 4, 12, 4>;
 
 }  // namespace
 
@@ -339,7 +445,16 @@ size_t mfma_conv_bwd_weight_ws(const ConvShape& s) {
 
 int mfma_conv_bwd_weight(cnn_ctx* ctx, const ConvShape& s, const float* x, const float* dy, float* dw) {
     Plan p;
-    if (make_plan<Wg3>(s, &p)) return launch<Wg3>(ctx, p, s, x, dy, dw);
+    if (make_plan<Wg3>(s, &p)) {
+        const int tw = p.g.TW, nbi = p.g.NBI;
+        if (s.C % Wg3::CBK == 0 && s.K % Wg3::KB == 0) {
+            if (tw == 56 && nbi == 1) return launch<Wg3F56>(ctx, p, s, x, dy, dw);
+            if (tw == 28 && nbi == 2) return launch<Wg3F28>(ctx, p, s, x, dy, dw);
+            if (tw == 14 && nbi == 4) return launch<Wg3F14>(ctx, p, s, x, dy, dw);
+            if (tw == 12 && nbi == 4) return launch<Wg3F12>(ctx, p, s, x, dy, dw);
+        }
+        return launch<Wg3>(ctx, p, s, x, dy, dw);
+    }
     if (make_plan<Wg5>(s, &p)) return launch<Wg5>(ctx, p, s, x, dy, dw);
     return CNN_EUNSUPPORTED;
 }
