@@ -22,7 +22,8 @@
 //  * staging loads are raw buffer loads: the address is (descriptor base) + (scalar channel offset) + (per-thread
 //    byte offset computed once); positions outside the image carry an offset beyond the descriptor's range, for
 //    which the hardware returns 0 - no bounds selects, no 64-bit address arithmetic;
-//  * threads and filter rows beyond the tile repeat the last valid one's work (same value to the same LDS word);
+//  * threads and filter rows beyond the tile wrap around and repeat another thread's work (same value to the same
+//    LDS word, but distinct words within a wave: lanes storing to one word would be serialised);
 //  * operands are read per segment of TG taps of one kernel row: the TG consecutive words of a lane come from one
 //    base address (paired LDS reads), one segment ahead of the MFMAs that use them - also across the chunk barrier;
 //  * the hot layer shapes get instantiations with compile-time LDS strides, so all operand offsets are immediates.
@@ -133,7 +134,7 @@ k_conv_tiled(ConvGeo g, const float* __restrict__ in, const float* __restrict__ 
     int xvo[G::XP], xpos[G::XP];
 #pragma unroll
     for (int j = 0; j < G::XP; ++j) {
-        const int e = min(tid + j * T, g.PLANE - 1);
+        const int e = (tid + j * T) % g.PLANE;     // positions past the plane wrap around: distinct words per lane
         const int per_img = g.THI * g.WLD;
         const int nb = e / per_img, rem = e % per_img;
         const int row = rem / g.WLD, col = rem % g.WLD;
@@ -143,12 +144,12 @@ k_conv_tiled(ConvGeo g, const float* __restrict__ in, const float* __restrict__ 
         xvo[j] = ok ? (int)((nb * (int)in_img + h * g.WI + w) * sizeof(float)) : kOutOfRange;
     }
     // ---- filter tile staging: thread = (row m_sub, fetch unit kq) of a pass over RPP rows
-    const int wtid = min(tid, G::RPP * G::Q4 - 1);
+    const int wtid = tid % (G::RPP * G::Q4);
     const int w_msub = wtid / G::Q4, w_kq = wtid % G::Q4;
     int wvo[G::WSL], wpos[G::WSL];
 #pragma unroll
     for (int i = 0; i < G::WSL; ++i) {
-        const int m = min(w_msub + i * G::RPP, G::MB - 1);
+        const int m = (w_msub + i * G::RPP) % G::MB;
         const int mrow = min(m0 + m, M - 1);          // rows past M repeat the last one (their results are not stored)
         wvo[i] = (int)((mrow * J * RS + w_kq * G::VEC) * sizeof(float));
         if (G::VEC == 1 && w_kq >= J * RS) wvo[i] = kOutOfRange;     // J < CB: one chunk, its missing channels are zero
@@ -433,9 +434,12 @@ int launch(cnn_ctx* ctx, const LaunchArgs& a) {
     }
     dim3 grid((unsigned)(8 * (a.g.full_per_xcd + a.g.tail_per_xcd * a.g.nsl)));
     static char name[96] = "";
+    if (!name[0] && G::WLDP_CT)
+        snprintf(name, sizeof(name), "k_conv_tiled<%dx%d CB%d WM%d WN%d NT%d ld%d/%d>", G::R, G::S, G::CB, G::WM, G::WN,
+                 G::NT, G::WLDP_CT, G::PLANEP_CT);
     if (!name[0])
-        snprintf(name, sizeof(name), "k_conv_tiled<%dx%d CB%d WM%d WN%d NT%d%s%s>", G::R, G::S, G::CB, G::WM, G::WN, G::NT,
-                 G::VEC == 1 ? " v1" : "", G::WLDP_CT ? " fixed" : "");
+        snprintf(name, sizeof(name), "k_conv_tiled<%dx%d CB%d WM%d WN%d NT%d%s>", G::R, G::S, G::CB, G::WM, G::WN, G::NT,
+                 G::VEC == 1 ? " v1" : "");
     {
         cnn::ProfScope ps(ctx, name, 2.0 * a.g.N * a.g.J * a.g.M * G::RS * a.g.HO * a.g.WO);
         hipLaunchKernelGGL(k_conv_tiled<G>, grid, dim3(G::T), a.lds_bytes, ctx->stream, a.g, a.in, a.wt, a.aux, a.out,
@@ -497,6 +501,7 @@ bool make_plan(int R, int S, int pad, int stride, int N, int J, int M, int HI, i
         if (WO > cap) continue;
         const int th_max = cap / WO < HO ? cap / WO : HO;
         for (int TH = th_max; TH >= 1; --TH) {
+            if (const char* e = getenv("CNN_CONV_TH")) { if (atoi(e) != TH) continue; }   // experiment override
             int NB = cap / (TH * WO);
             if (NB > N) NB = N;
             const int THI = (TH - 1) * stride + R;
@@ -516,6 +521,7 @@ bool make_plan(int R, int S, int pad, int stride, int N, int J, int M, int HI, i
                 if (lds_bytes > 156 * 1024) continue;
                 // an instantiation compiled for fixed LDS strides serves exactly those
                 if (v.wldp && (v.wldp != WLDP || v.planep != PLANEP)) continue;
+                if (v.wldp && getenv("CNN_CONV_NOFIXED")) continue;   // experiment override
                 // score: MFMA lanes doing useful work, x 0.9 if only one workgroup fits a compute unit, x 0.97 for
                 // the conflicting LDS layout, and a penalty for the share of staged rows that are halo (short tiles
                 // re-stage the same rows; measured on 14x14 and 24x24 layers)

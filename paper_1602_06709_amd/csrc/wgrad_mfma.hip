@@ -84,12 +84,13 @@ k_wgrad(WgGeo g, const float* __restrict__ x, const float* __restrict__ dy, floa
     for (int e = tid; e < G::CBK * XSTR; e += T) xl[e] = 0.f;
 
     // ---- staging: wave w moves feature rows w, w+NWAVE, ... (those past the tile repeat the tile's last row);
-    //      lane = position in the row(s) of the NBI images (lanes past the row repeat its last position).
+    //      lane = position in the row(s) of the NBI images (lanes past the row wrap around and repeat its first
+    //      positions: same value to the same word, at most two lanes per word; more would be serialised).
     //      Loads are raw buffer loads: descriptor base + scalar offset (image group, feature, row) + per-lane byte
     //      offset; a lane whose position is outside the image, or whose image or row does not exist, carries an
     //      offset beyond the descriptor's range and the hardware returns 0.  Features past C / K read whatever
     //      follows (or 0 past the end of the tensor): their results are never stored.
-    const int lx = min(lane, NBI * WLD - 1), ld = min(lane, NBI * TW - 1);
+    const int lx = lane % (NBI * WLD), ld = lane % (NBI * TW);
     const int xb = lx / WLD, db = ld / TW;
     int xvo, dvo;
     {
@@ -402,9 +403,10 @@ int launch(cnn_ctx* ctx, const Plan& p, const ConvShape& s, const float* x, cons
     float* partial = reinterpret_cast<float*>(ctx->ws);
     dim3 grid((unsigned)(p.nsplit * p.g.col_tiles), (unsigned)p.ctiles, (unsigned)p.ktiles);
     static char name[96] = "";
-    if (!name[0])
-        snprintf(name, sizeof(name), "k_wgrad<%dx%d KW%d CW%d RW%d%s>", G::R, G::S, G::KW, G::CW, G::RW,
-                 G::FIXED ? " fixed" : "");
+    if (!name[0] && G::FIXED)
+        snprintf(name, sizeof(name), "k_wgrad<%dx%d KW%d CW%d RW%d tw%dx%d>", G::R, G::S, G::KW, G::CW, G::RW, G::TW_CT,
+                 G::NBI_CT);
+    if (!name[0]) snprintf(name, sizeof(name), "k_wgrad<%dx%d KW%d CW%d RW%d>", G::R, G::S, G::KW, G::CW, G::RW);
     {
         cnn::ProfScope ps(ctx, name, cnn::conv_flops(s));
         hipLaunchKernelGGL(k_wgrad<G>, grid, dim3(G::T), p.lds_bytes, ctx->stream, p.g, x, dy, partial);
