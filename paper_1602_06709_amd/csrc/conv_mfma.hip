@@ -5,14 +5,18 @@
 //                                                      kernel taps mirrored, pad' = R-1-pad
 // which is the paper's remark that the passes share one loop nest and one blocking strategy.
 //
-// Tiling (per workgroup): MB = 32*WM output features x a pixel tile of NB images x TH full-width output rows
-// (at most 32*NT*WN pixels; NB, TH and all image sizes are run-time values).  Each wave owns 32 output features x NT
+// Tiling (per workgroup): MB = 32*WM output features x a pixel tile of TR full-width output rows (at most 32*NT*WN
+// pixels; TR and all image sizes are run-time values).  Output rows are numbered through the whole minibatch
+// (image n, row p -> n*HO + p) and a tile takes TR consecutive ones, so it continues into the next image instead of
+// ending with the image: every tile but the last is full whatever the image height.  Each wave owns 32 output features x NT
 // blocks of 32 pixels: NT accumulators of 16 VGPRs.  The contraction runs over chunks of CB channels:
 //   LDS  wl[MB][CB*R*S + 1]      filter tile, row stride odd  -> the 32 lanes of an A operand (one output feature
 //                                each) hit 32 different banks
-//   LDS  xl[CB][NB][rows][width] input tile with its halo, zeros where the image ends; lanes of a B operand are
-//                                consecutive pixels -> consecutive words.  Row and image strides are padded so that
-//                                this also holds across the end of a row / image (stride 1).
+//   LDS  xl[CB][rows][width]     input rows the tile needs, numbered through the zero-extended images (pad rows
+//                                above and below each image, so consecutive output rows need consecutive staged
+//                                rows also across an image boundary); zeros where the image ends; lanes of a B
+//                                operand are consecutive pixels -> consecutive words.  The row stride is padded so
+//                                that this also holds across the end of a row (stride 1).
 // The two halves of the 64-lane wave feed k = 0 and k = 1 of the MFMA: the low half walks channels [0, CB/2) of the
 // chunk and the high half [CB/2, CB), so both halves use the same offsets.
 // Two LDS buffers: while chunk ch is multiplied, chunk ch+1 moves from registers into the other buffer and chunk
@@ -45,12 +49,12 @@ struct ConvGeo {
     int N, J, M;                   // images, contraction channels, output features
     int HI, WI, HO, WO;            // input and output image sizes
     int pad, stride;               // padding on the input side, stride
-    int NB, TH;                    // pixel tile: images x output rows (full width)
-    int THI, WLD;                  // staged input rows / columns per image: (TH-1)*stride + R, WI + 2*pad
-    int WLDP, IMGSTR, PLANEP;      // LDS row / image / channel strides
-    int PLANE;                     // staged elements per channel: NB * THI * WLD
-    int NPIX;                      // NB * TH * WO
-    int row_tiles, ptiles, mtiles, per_xcd;
+    int TR, VH;                    // output rows per tile; rows of a zero-extended image: HI + 2*pad
+    int THI, WLD;                  // staged input rows (the widest tile's) / columns: WI + 2*pad
+    int WLDP, PLANEP;              // LDS row / channel strides
+    int PLANE;                     // staged elements per channel: THI * WLD
+    int NPIX;                      // TR * WO
+    int ptiles, mtiles, per_xcd;
     // Per XCD, workgroups [0, full_per_xcd) run one (pixel tile, feature tile) unit over the whole contraction; the
     // remaining tail_per_xcd units are each cut into nsl slices of chunks_per_slice channel chunks, one workgroup per
     // slice, whose partial results go to a scratch buffer and are added up by k_tile_reduce.
@@ -116,8 +120,9 @@ k_conv_tiled(ConvGeo g, const float* __restrict__ in, const float* __restrict__ 
     const int ptile = xcd * g.per_xcd + unit / g.mtiles;
     if (ptile >= g.ptiles) return;   // whole workgroup leaves: no barrier is left behind
     const int m0 = (unit % g.mtiles) * G::MB;
-    const int n0 = (ptile / g.row_tiles) * g.NB;
-    const int p0 = (ptile % g.row_tiles) * g.TH;
+    const int row0 = ptile * g.TR, nrows = N * g.HO;      // first output row of the tile, rows of the minibatch
+    const int n0 = row0 / g.HO;                           // image the tile starts in
+    const int v0 = n0 * g.VH + (row0 % g.HO) * g.stride;  // its first staged row, numbered through the extended images
 
     const int plane_g = g.HI * g.WI;
     const size_t in_img = (size_t)J * plane_g;         // elements per image of `in`
@@ -135,11 +140,10 @@ k_conv_tiled(ConvGeo g, const float* __restrict__ in, const float* __restrict__ 
 #pragma unroll
     for (int j = 0; j < G::XP; ++j) {
         const int e = (tid + j * T) % g.PLANE;     // positions past the plane wrap around: distinct words per lane
-        const int per_img = g.THI * g.WLD;
-        const int nb = e / per_img, rem = e % per_img;
-        const int row = rem / g.WLD, col = rem % g.WLD;
-        const int h = p0 * g.stride - g.pad + row, w = col - g.pad;
-        xpos[j] = nb * g.IMGSTR + row * WLDP + col;
+        const int row = e / g.WLD, col = e % g.WLD;
+        const int va = v0 + row, nb = va / g.VH - n0;         // image relative to the tile's first
+        const int h = va % g.VH - g.pad, w = col - g.pad;
+        xpos[j] = row * WLDP + col;
         const bool ok = n0 + nb < N && h >= 0 && h < g.HI && w >= 0 && w < g.WI;
         xvo[j] = ok ? (int)((nb * (int)in_img + h * g.WI + w) * sizeof(float)) : kOutOfRange;
     }
@@ -163,11 +167,9 @@ k_conv_tiled(ConvGeo g, const float* __restrict__ in, const float* __restrict__ 
     for (int j = 0; j < NT; ++j) {
         const int i = (wn * NT + j) * 32 + l32;
         int o = 0;
-        if (i < g.NPIX) {
-            const int per_img = g.TH * g.WO;
-            const int nb = i / per_img, rem = i % per_img;
-            o = nb * g.IMGSTR + (rem / g.WO) * g.stride * WLDP + (rem % g.WO) * g.stride;
-        }
+        const int orow = row0 + i / g.WO;
+        if (i < g.NPIX && orow < nrows)
+            o = ((orow / g.HO) * g.VH + (orow % g.HO) * g.stride - v0) * WLDP + (i % g.WO) * g.stride;
         b_base[j] = o + half * (CB / 2) * PLANEP;
     }
 
@@ -346,12 +348,9 @@ k_conv_tiled(ConvGeo g, const float* __restrict__ in, const float* __restrict__ 
 #pragma unroll
     for (int j = 0; j < NT; ++j) {
         const int i = (wn * NT + j) * 32 + l32;
-        if (i >= g.NPIX) continue;
-        const int per_img = g.TH * g.WO;
-        const int nb = i / per_img, rem = i % per_img;
-        const int p = p0 + rem / g.WO, q = rem % g.WO;
-        if (n0 + nb >= N || p >= g.HO) continue;
-        const size_t o0 = ((size_t)(n0 + nb) * M) * out_plane + (size_t)p * g.WO + q;
+        const int orow = row0 + i / g.WO;
+        if (i >= g.NPIX || orow >= nrows) continue;
+        const size_t o0 = ((size_t)(orow / g.HO) * M) * out_plane + (size_t)(orow % g.HO) * g.WO + i % g.WO;
         float* o = out + o0;
 #pragma unroll
         for (int v = 0; v < 16; ++v) {
@@ -396,19 +395,16 @@ __global__ void __launch_bounds__(256) k_tile_reduce(ConvGeo g, int MB, int cap,
     const int ptile = xcd * g.per_xcd + unit / g.mtiles;
     if (ptile >= g.ptiles) return;
     const int m0 = (unit % g.mtiles) * MB;
-    const int n0 = (ptile / g.row_tiles) * g.NB, p0 = (ptile % g.row_tiles) * g.TH;
+    const int row0 = ptile * g.TR, nrows = g.N * g.HO;
     const size_t out_plane = (size_t)g.HO * g.WO, tile = (size_t)MB * cap;
     const float* pt = partial + (size_t)blockIdx.x * g.nsl * tile;
-    const int per_img = g.TH * g.WO;
     for (int e = threadIdx.x; e < 8 * cap; e += 256) {
         const int ml = blockIdx.y * 8 + e / cap, i = e % cap;
-        if (i >= g.NPIX || m0 + ml >= g.M) continue;
-        const int nb = i / per_img, rem = i % per_img;
-        const int p = p0 + rem / g.WO, q = rem % g.WO;
-        if (n0 + nb >= g.N || p >= g.HO) continue;
+        const int orow = row0 + i / g.WO;
+        if (i >= g.NPIX || orow >= nrows || m0 + ml >= g.M) continue;
         float r = 0.f;
         for (int s = 0; s < g.nsl; ++s) r += pt[s * tile + (size_t)ml * cap + i];
-        const size_t o = ((size_t)(n0 + nb) * g.M + m0 + ml) * out_plane + (size_t)p * g.WO + q;
+        const size_t o = ((size_t)(orow / g.HO) * g.M + m0 + ml) * out_plane + (size_t)(orow % g.HO) * g.WO + i % g.WO;
         if (g.epi == EPI_RELU) r = r > 0.f ? r : 0.f;
         else if (g.epi == EPI_MASK) r = aux[o] > 0.f ? r : 0.f;
         out[o] = r;
@@ -463,8 +459,8 @@ struct Variant {
 const Variant kVariants[] = {
     // 3x3, 128-feature tiles (4 waves), strides of the 3x3 / pad 1 layers of VGG-A at 112, 56, 28 and 14 pixels and
     // of OverFeat-FAST at 12 pixels (both passes share them: backpropagation has pad' = 1 too)
-    V(3, 3, 4, 4, 1, 7, 4, 2, 3, 144, 576), V(3, 3, 4, 4, 1, 7, 4, 2, 3, 88, 544), V(3, 3, 4, 4, 1, 7, 4, 2, 3, 60, 736),
-    V(3, 3, 4, 4, 1, 7, 4, 2, 3, 46, 740), V(3, 3, 4, 4, 1, 9, 4, 2, 1, 44, 1248),
+    V(3, 3, 4, 4, 1, 7, 4, 2, 3, 144, 576), V(3, 3, 4, 4, 1, 7, 4, 2, 3, 88, 528), V(3, 3, 4, 4, 1, 7, 4, 2, 3, 60, 720),
+    V(3, 3, 4, 4, 1, 7, 4, 2, 3, 46, 920), V(3, 3, 4, 4, 1, 9, 4, 2, 1, 44, 1232),
     // 3x3, any strides: 128-feature tiles (4 waves) and 64-feature tiles (2 waves), 7 / 8 / 9 pixel blocks per wave
     V(3, 3, 4, 4, 1, 7, 4, 2, 3, 0, 0), V(3, 3, 4, 4, 1, 8, 4, 2, 3, 0, 0), V(3, 3, 4, 4, 1, 9, 4, 2, 1, 0, 0),
     V(3, 3, 4, 2, 1, 7, 4, 4, 3, 0, 0), V(3, 3, 4, 2, 1, 8, 4, 4, 1, 0, 0),
@@ -482,15 +478,16 @@ struct ConvPlan {
 };
 
 
-// Chooses, among the instantiations for this kernel size, the pixel tile (images x rows) that wastes the fewest MFMA
-// lanes, prefers the 128-feature tile unless the layer has at most 64 output features, and slices the contraction
-// when the output alone gives fewer workgroups than the chip runs at once.
+// Chooses, among the instantiations for this kernel size, the pixel tile (TR consecutive output rows of the whole
+// minibatch) that wastes the fewest MFMA lanes, prefers the 128-feature tile unless the layer has at most 64 output
+// features, and slices the contraction of the tail units (below).
 bool make_plan(int R, int S, int pad, int stride, int N, int J, int M, int HI, int WI, ConvPlan* p) {
     if (HI + 2 * pad < R || WI + 2 * pad < S) return false;
-    // byte offsets inside the kernel are 32-bit: the filter tensor, and (below) the images of one pixel tile
+    // byte offsets inside the kernel are 32-bit: the filter tensor, and (below) the images one pixel tile touches
     if ((size_t)M * J * R * S * sizeof(float) >= 0x7fffffffu) return false;
     const int HO = (HI + 2 * pad - R) / stride + 1, WO = (WI + 2 * pad - S) / stride + 1;
-    const int WLD = WI + 2 * pad;
+    const int WLD = WI + 2 * pad, VH = HI + 2 * pad;
+    const long nrows = (long)N * HO;
     double best = 0.0;
     bool found = false;
     for (const Variant& v : kVariants) {
@@ -499,23 +496,26 @@ bool make_plan(int R, int S, int pad, int stride, int N, int J, int M, int HI, i
         if (v.vec == 4 && R != 5 && (M <= 64 ? v.mb != 64 : v.mb != 128)) continue;
         const int cap = v.nt * v.wn * 32;
         if (WO > cap) continue;
-        const int th_max = cap / WO < HO ? cap / WO : HO;
-        for (int TH = th_max; TH >= 1; --TH) {
-            if (const char* e = getenv("CNN_CONV_TH")) { if (atoi(e) != TH) continue; }   // experiment override
-            int NB = cap / (TH * WO);
-            if (NB > N) NB = N;
-            const int THI = (TH - 1) * stride + R;
-            while (NB > 1 && NB * THI * WLD > v.maxplane) --NB;     // the threads must cover the staged plane
-            if (NB * THI * WLD > v.maxplane) continue;
-            if ((size_t)NB * J * HI * WI * sizeof(float) >= 0x7fffffffu) continue;
-            const int row_tiles = (HO + TH - 1) / TH, img_tiles = (N + NB - 1) / NB;
-            const double eff = ((double)N * HO * WO) / ((double)row_tiles * img_tiles * cap);
+        const int tr_max = (long)(cap / WO) < nrows ? cap / WO : (int)nrows;
+        for (int TR = tr_max; TR >= 1; --TR) {
+            if (const char* e = getenv("CNN_CONV_TH")) { if (atoi(e) != TR) continue; }   // experiment override
+            const int ptiles = (int)((nrows + TR - 1) / TR);
+            // staged rows of the widest tile: from the first output row's first input row to the last one's last,
+            // through the pad rows between images (the tile starts repeat with period HO)
+            int THI = 0;
+            for (int t = 0; t < ptiles && t <= HO; ++t) {
+                const long r0 = (long)t * TR, r1 = (r0 + TR - 1 < nrows ? r0 + TR - 1 : nrows - 1);
+                const long span = (r1 / HO) * VH + (r1 % HO) * stride + R - ((r0 / HO) * VH + (r0 % HO) * stride);
+                if (span > THI) THI = (int)span;
+            }
+            if (THI * WLD > v.maxplane) continue;                    // the threads must cover the staged plane
+            const int images = (THI + VH - 1) / VH + 1;              // images the staged rows of one tile can touch
+            if ((size_t)images * J * HI * WI * sizeof(float) >= 0x7fffffffu) continue;
+            const double eff = ((double)nrows * WO) / ((double)ptiles * cap);
             for (int padded = (stride == 1 ? 1 : 0); padded >= 0; --padded) {
-                // LDS strides: padded so consecutive pixels stay in consecutive banks across row / image ends
+                // LDS row stride: padded so consecutive pixels stay in consecutive banks across the end of a row
                 const int WLDP = padded ? WO + 32 * ((WLD - WO + 31) / 32) : WLD;
-                const int IMG0 = THI * WLDP;
-                const int IMGSTR = padded ? IMG0 + ((((TH - 1) * WLDP + WO - IMG0) % 32) + 32) % 32 : IMG0;
-                const int PLANEP = NB * IMGSTR;
+                const int PLANEP = THI * WLDP;
                 const int lds_buf = v.mb * v.wstr + v.CB * PLANEP;
                 const size_t lds_bytes = (size_t)lds_buf * 2 * sizeof(float);   // two buffers
                 if (lds_bytes > 156 * 1024) continue;
@@ -526,17 +526,24 @@ bool make_plan(int R, int S, int pad, int stride, int N, int J, int M, int HI, i
                 // the conflicting LDS layout, and a penalty for the share of staged rows that are halo (short tiles
                 // re-stage the same rows; measured on 14x14 and 24x24 layers)
                 double score = eff * (lds_bytes <= 78 * 1024 ? 1.0 : 0.9) * (padded || stride != 1 ? 1.0 : 0.97);
-                score *= 1.0 - 0.3 * (double)(R - 1) / (TH * stride + R - 1);
+                score *= 1.0 - 0.3 * (double)(THI - TR * stride) / THI;
                 if (v.wldp) score *= 1.03;                          // operand offsets are immediates
+                {
+                    // a grid that cannot fill the chip even with every unit sliced as far as allowed takes as long
+                    // as one of its workgroups: then the smaller pixel tile wins, not the better filled one
+                    const int nch = (J + v.CB - 1) / v.CB, max_nsl = nch / 8 < 1 ? 1 : (nch / 8 > 16 ? 16 : nch / 8);
+                    const long units = (long)ptiles * ((M + v.mb - 1) / v.mb);
+                    if (units * max_nsl <= 256) score *= 224.0 / cap / eff;
+                }
                 if (found && score <= best + 1e-9) continue;
                 found = true;
                 best = score;
                 p->v = &v;
                 ConvGeo& g = p->g;
                 g.N = N; g.J = J; g.M = M; g.HI = HI; g.WI = WI; g.HO = HO; g.WO = WO; g.pad = pad; g.stride = stride;
-                g.NB = NB; g.TH = TH; g.THI = THI; g.WLD = WLD; g.WLDP = WLDP; g.IMGSTR = IMGSTR; g.PLANEP = PLANEP;
-                g.PLANE = NB * THI * WLD; g.NPIX = NB * TH * WO;
-                g.row_tiles = row_tiles; g.ptiles = row_tiles * img_tiles; g.mtiles = (M + v.mb - 1) / v.mb;
+                g.TR = TR; g.VH = VH; g.THI = THI; g.WLD = WLD; g.WLDP = WLDP; g.PLANEP = PLANEP;
+                g.PLANE = THI * WLD; g.NPIX = TR * WO;
+                g.ptiles = ptiles; g.mtiles = (M + v.mb - 1) / v.mb;
                 g.per_xcd = (g.ptiles + 7) / 8;
                 g.lds_buf = lds_buf;
                 p->lds_bytes = lds_bytes;
@@ -550,7 +557,6 @@ bool make_plan(int R, int S, int pad, int stride, int N, int J, int M, int HI, i
     // the busiest compute unit works through ceil(units / 256) of them while the others idle at the end.  The
     // units % 256 that overhang the last full round (all of them, when the grid is no larger than one round) are
     // therefore cut along the contraction into nsl shorter workgroups each, so that the final round is even too.
-    // A workgroup that is alone on its compute unit reaches about 0.9 of the rate of two resident ones.
     // The price is the partial tiles, written and read once (8 bytes per element at ~4 TB/s, relative to the
     // tile's compute time).
     const int upx = g.per_xcd * g.mtiles;                          // units per XCD
@@ -559,12 +565,20 @@ bool make_plan(int R, int S, int pad, int stride, int N, int J, int M, int HI, i
     const double ov_job = (8.0 / 4.0e12) / (2.0 * J * R * S / (0.85 * 157.3e12));
     const long rounds = units > 256 ? units / 256 : 0, tail = units - rounds * 256;
     int best_tail = 0, best_nsl = 1;
-    if (tail > 0) {
+    if (rounds == 0) {
+        // a grid within one round: slice every unit just far enough that (almost) every compute unit gets a
+        // workgroup; finer slices only add partial-tile traffic (measured at minibatch 4)
+        const long live = (long)g.ptiles * g.mtiles;               // without the empty units that pad the last XCD's range
+        int nsl = 1;
+        while (live * nsl < 208 && nsl < 16 && nchunks / (nsl + 1) >= 8) ++nsl;
+        best_nsl = nsl;
+        if (nsl > 1) best_tail = (int)units;
+    } else if (tail > 0) {
         double best_t = 0.0;
         for (int nsl = 1; nsl <= 16; ++nsl) {
             if (nsl > 1 && nchunks / nsl < 8) break;               // at least 8 chunks per slice
             const long k = (tail * nsl + 255) / 256;               // slices on the busiest compute unit
-            double t = (double)rounds + (double)k / nsl * (rounds == 0 && k == 1 ? 1.0 / 0.9 : 1.0);
+            double t = (double)rounds + (double)k / nsl;
             if (nsl > 1) t += (double)(tail * nsl) / 256.0 * ov_job;
             if (nsl == 1 || t < best_t * 0.98) { best_t = t; best_nsl = nsl; }
         }
@@ -577,8 +591,9 @@ bool make_plan(int R, int S, int pad, int stride, int N, int J, int M, int HI, i
         }
     }
     if (getenv("CNN_PLAN_DEBUG"))
-        fprintf(stderr, "plan %dx%d N%d J%d M%d %dx%d: mb%d nt%d NB%d TH%d ptiles%d mtiles%d units%ld lds%zu tail%d nsl%d\n", R, S, N,
-                J, M, HI, WI, v.mb, v.nt, g.NB, g.TH, g.ptiles, g.mtiles, units, p->lds_bytes, best_tail, best_nsl);
+        fprintf(stderr, "plan %dx%d N%d J%d M%d %dx%d: mb%d nt%d TR%d THI%d WLDP%d PLANEP%d%s ptiles%d mtiles%d units%ld lds%zu tail%d nsl%d\n",
+                R, S, N, J, M, HI, WI, v.mb, v.nt, g.TR, g.THI, g.WLDP, g.PLANEP, v.wldp ? " fixed" : "", g.ptiles, g.mtiles, units,
+                p->lds_bytes, best_tail, best_nsl);
     g.tail_per_xcd = best_tail / 8;
     g.full_per_xcd = upx - g.tail_per_xcd;
     g.nsl = best_tail ? best_nsl : 1;
