@@ -461,8 +461,10 @@ const Variant kVariants[] = {
     // of OverFeat-FAST at 12 pixels (both passes share them: backpropagation has pad' = 1 too)
     V(3, 3, 4, 4, 1, 7, 4, 2, 3, 144, 576), V(3, 3, 4, 4, 1, 7, 4, 2, 3, 88, 528), V(3, 3, 4, 4, 1, 7, 4, 2, 3, 60, 720),
     V(3, 3, 4, 4, 1, 7, 4, 2, 3, 46, 920), V(3, 3, 4, 4, 1, 9, 4, 2, 1, 44, 1232),
+    // ... and the 64-feature tile at 112 pixels (backpropagation into a 64-channel layer)
+    V(3, 3, 4, 2, 1, 7, 4, 4, 3, 144, 576),
     // 3x3, any strides: 128-feature tiles (4 waves) and 64-feature tiles (2 waves), 7 / 8 / 9 pixel blocks per wave
-    V(3, 3, 4, 4, 1, 7, 4, 2, 3, 0, 0), V(3, 3, 4, 4, 1, 8, 4, 2, 3, 0, 0), V(3, 3, 4, 4, 1, 9, 4, 2, 1, 0, 0),
+    V(3, 3, 4, 4, 1, 7, 4, 2, 3, 0, 0), V(3, 3, 4, 4, 1, 8, 4, 2, 1, 0, 0), V(3, 3, 4, 4, 1, 9, 4, 2, 1, 0, 0),
     V(3, 3, 4, 2, 1, 7, 4, 4, 3, 0, 0), V(3, 3, 4, 2, 1, 8, 4, 4, 1, 0, 0),
     // 3x3 with fewer than 4 contraction channels (first layers)
     V(3, 3, 4, 2, 2, 7, 1, 4, 3, 0, 0),
@@ -498,7 +500,6 @@ bool make_plan(int R, int S, int pad, int stride, int N, int J, int M, int HI, i
         if (WO > cap) continue;
         const int tr_max = (long)(cap / WO) < nrows ? cap / WO : (int)nrows;
         for (int TR = tr_max; TR >= 1; --TR) {
-            if (const char* e = getenv("CNN_CONV_TH")) { if (atoi(e) != TR) continue; }   // experiment override
             const int ptiles = (int)((nrows + TR - 1) / TR);
             // staged rows of the widest tile: from the first output row's first input row to the last one's last,
             // through the pad rows between images (the tile starts repeat with period HO)
@@ -521,7 +522,6 @@ bool make_plan(int R, int S, int pad, int stride, int N, int J, int M, int HI, i
                 if (lds_bytes > 156 * 1024) continue;
                 // an instantiation compiled for fixed LDS strides serves exactly those
                 if (v.wldp && (v.wldp != WLDP || v.planep != PLANEP)) continue;
-                if (v.wldp && getenv("CNN_CONV_NOFIXED")) continue;   // experiment override
                 // score: MFMA lanes doing useful work, x 0.9 if only one workgroup fits a compute unit, x 0.97 for
                 // the conflicting LDS layout, and a penalty for the share of staged rows that are halo (short tiles
                 // re-stage the same rows; measured on 14x14 and 24x24 layers)
@@ -584,13 +584,7 @@ bool make_plan(int R, int S, int pad, int stride, int N, int J, int M, int HI, i
         }
         if (best_nsl > 1) best_tail = (int)tail;
     }
-    if (const char* e = getenv("CNN_CONV_TAIL")) {                 // experiment override: "tail,nsl"
-        int a = 0, b = 1;
-        if (sscanf(e, "%d,%d", &a, &b) == 2 && a >= 0 && a % 8 == 0 && a <= units && b >= 1 && nchunks / b >= 1) {
-            best_tail = b > 1 ? a : 0; best_nsl = b;
-        }
-    }
-    if (getenv("CNN_PLAN_DEBUG"))
+    if (getenv("CNN_PLAN_DEBUG"))     // diagnostic aid: the chosen plan, one line per planning call, on stderr
         fprintf(stderr, "plan %dx%d N%d J%d M%d %dx%d: mb%d nt%d TR%d THI%d WLDP%d PLANEP%d%s ptiles%d mtiles%d units%ld lds%zu tail%d nsl%d\n",
                 R, S, N, J, M, HI, WI, v.mb, v.nt, g.TR, g.THI, g.WLDP, g.PLANEP, v.wldp ? " fixed" : "", g.ptiles, g.mtiles, units,
                 p->lds_bytes, best_tail, best_nsl);

@@ -73,6 +73,11 @@ CONV_CASES = [  # N, C, H, K, R, pad       (square images, stride 1)
     (2, 8, 40, 130, 3, 0),      # pad 0: 40 -> 38
     (1, 16, 64, 24, 3, 2),      # pad 2: 64 -> 66
     (2, 8, 17, 72, 5, 2),       # 5x5 'same' on an odd size
+    (2, 64, 28, 128, 3, 1),     # whole tiles: fixed-geometry weight gradient (two images per step), sliced contraction
+    (5, 64, 14, 128, 3, 1),     # ... four images per step, odd N; pixel tiles cross image boundaries
+    (3, 64, 12, 128, 3, 1),     # ... 12x12
+    (7, 8, 7, 40, 3, 1),        # 7x7 images: one pixel tile spans several images
+    (3, 128, 10, 24, 3, 1),     # long contraction, few outputs: every unit sliced
 ]
 
 
@@ -237,8 +242,9 @@ def test_config2_vgg_a_conv_stack_n4_full_tensors(cnn, ctx, fuse):
 
 def test_fused_relu_entry_points_equal_the_unfused_sequence(cnn, ctx):
     # conv_fwd_relu == relu(conv_fwd); conv_bwd_data_relu == relu_bwd(x, conv_bwd_data); pool_relu_bwd == relu_bwd(pool_bwd)
+    # (the 64- and 128-channel cases slice the contraction, so the epilogue runs in the tile reduction)
     for (N, C, H, K, R, pad) in [(3, 16, 28, 72, 3, 1), (2, 3, 224, 64, 3, 1), (5, 32, 14, 48, 3, 1), (2, 8, 28, 40, 5, 0),
-                                 (2, 5, 9, 7, 3, 1)]:
+                                 (2, 5, 9, 7, 3, 1), (2, 64, 28, 128, 3, 1), (3, 128, 10, 64, 3, 1)]:
         say("fused case", (N, C, H, K, R, pad))
         x = np.maximum(synth.randn(97, 1, (N, C, H, H)), 0).astype(np.float32)      # a ReLU output
         w = synth.randn(97, 2, (K, C, R, R), 0.1)
