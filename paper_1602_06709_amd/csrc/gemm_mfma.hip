@@ -10,6 +10,12 @@
 // as [row][KC+1] (odd stride across the 32 lanes), row-contiguous tiles as [k][rows].  The output has
 // lane = column n (coalesced stores).  A small minibatch leaves few output tiles, so the contraction is
 // split across workgroups and the partial products are added by a second kernel in a fixed order.
+//
+// The chunk loop follows the convolution kernel's recipe (every non-MFMA instruction costs matrix-pipe time):
+// two LDS buffers with one barrier per chunk, placed before the chunk's last MFMA group so that the next chunk's
+// first operands are read behind it; staging by raw buffer loads whose per-thread byte offsets are computed once
+// (rows past the matrix carry an out-of-range offset and read 0), one staging item between MFMA groups; operands
+// read one group (two k-steps) ahead through persistent 32-bit LDS pointers with immediate offsets.
 #include <stdio.h>
 
 #include "common.h"
@@ -17,8 +23,13 @@
 namespace {
 
 typedef float f32x16 __attribute__((ext_vector_type(16)));
+typedef __attribute__((address_space(3))) float lds_float;      // LDS pointers are 32-bit: one VGPR each
+typedef float f32x4 __attribute__((ext_vector_type(4)));
+typedef __attribute__((address_space(3))) f32x4 lds_f32x4;
 
 constexpr int KC = 32;   // contraction elements per LDS chunk
+constexpr int kOutOfRange = (int)0x80000000;   // buffer-load byte offset beyond any descriptor used here -> reads 0
+constexpr int kRsrcWord3 = 0x00020000;         // raw buffer descriptor of 32-bit elements
 
 template <int MT_, int NT_, int WGM_, int WGN_, bool AKM_, bool BKM_>
 struct GemmCfg {
@@ -27,50 +38,56 @@ struct GemmCfg {
     static constexpr int TM = 32 * MT * WGM, TN = 32 * NT * WGN, T = 64 * WGM * WGN;
     static constexpr int A_LDS = AKM ? KC * TM : TM * (KC + 1);
     static constexpr int B_LDS = BKM ? KC * TN : TN * (KC + 1);
+    static constexpr int BUF = (A_LDS + B_LDS + 3) / 4 * 4;          // one (A tile, B tile) buffer, 16-byte multiple
     static constexpr int A4 = TM * KC / 4, B4 = TN * KC / 4;
     static constexpr int AS = (A4 + T - 1) / T, BS = (B4 + T - 1) / T;
+    static_assert(A4 % T == 0 && B4 % T == 0, "every thread stages whole float4 slots");
 };
 
-// One operand tile: fetch `rows` x KC elements starting at (row0, k0) into registers, then into LDS.
+// One operand tile of ROWS x KC elements: per-thread staging slots (float4 each).
+//   KM == false: src[row][Kd], float4 along k;  LDS [row][KC+1]
+//   KM == true:  src[Kd][rows_total], float4 along the row index;  LDS [k][ROWS]
 template <bool KM, int ROWS, int T, int SLOTS>
 struct Stager {
-    // KM == false: src[row][Kd], float4 along k.  KM == true: src[Kd][rows_total], float4 along the row index.
-    __device__ static void fetch(const float* __restrict__ src, int rows_total, int Kd, int row0, int k0, int k_end,
-                                 int tid, float4 (&reg)[SLOTS]) {
+    int vo[SLOTS];         // byte offset of the slot's float4 within chunk 0 of the split (or kOutOfRange)
+    int kofs[SLOTS];       // first contraction index of the slot within the chunk
+    lds_float* dst[SLOTS]; // where it goes in LDS buffer 0
+    f32x4 reg[SLOTS];
+
+    __device__ void init(int rows_total, int Kd, int row0, int tid, float* l) {
 #pragma unroll
         for (int i = 0; i < SLOTS; ++i) {
             const int f = tid + i * T;
-            float4 v = make_float4(0.f, 0.f, 0.f, 0.f);
-            if (f < ROWS * KC / 4) {
-                if (!KM) {
-                    const int r = f / (KC / 4), kq = f % (KC / 4);
-                    const int k = k0 + kq * 4;
-                    if (row0 + r < rows_total && k < k_end)
-                        v = *reinterpret_cast<const float4*>(src + (size_t)(row0 + r) * Kd + k);
-                } else {
-                    const int k = f / (ROWS / 4), rq = f % (ROWS / 4);
-                    const int r = row0 + rq * 4;
-                    if (r < rows_total && k0 + k < k_end)
-                        v = *reinterpret_cast<const float4*>(src + (size_t)(k0 + k) * rows_total + r);
-                }
+            if (!KM) {
+                const int r = f / (KC / 4), kq = f % (KC / 4);
+                vo[i] = row0 + r < rows_total ? (int)(((size_t)(row0 + r) * Kd + kq * 4) * sizeof(float)) : kOutOfRange;
+                kofs[i] = kq * 4;
+                dst[i] = (lds_float*)(l + r * (KC + 1) + kq * 4);
+            } else {
+                const int k = f / (ROWS / 4), rq = f % (ROWS / 4);
+                vo[i] = row0 + rq * 4 < rows_total ? (int)(((size_t)k * rows_total + row0 + rq * 4) * sizeof(float)) : kOutOfRange;
+                kofs[i] = k;
+                dst[i] = (lds_float*)(l + k * ROWS + rq * 4);
             }
-            reg[i] = v;
         }
     }
-    __device__ static void stage(float* __restrict__ l, int tid, const float4 (&reg)[SLOTS]) {
+    // chunk starting at contraction index k0; `whole`: the chunk lies entirely below k_end
+    __device__ void fetch(int i, __amdgpu_buffer_rsrc_t rs, int rows_total, int k0, int k_end, bool whole) {
+        const int so = (KM ? k0 * rows_total : k0) * (int)sizeof(float);
+        const int v = (whole || k0 + kofs[i] < k_end) ? vo[i] : kOutOfRange;
+        reg[i] = __builtin_bit_cast(f32x4, __builtin_amdgcn_raw_buffer_load_b128(rs, v, so, 0));
+    }
+    // dst moves between the two LDS buffers once per chunk (kept in registers; recomputing it costs more)
+    __device__ void flip(int delta) {
 #pragma unroll
-        for (int i = 0; i < SLOTS; ++i) {
-            const int f = tid + i * T;
-            if (f < ROWS * KC / 4) {
-                if (!KM) {
-                    const int r = f / (KC / 4), kq = f % (KC / 4);
-                    float* d = l + r * (KC + 1) + kq * 4;
-                    d[0] = reg[i].x; d[1] = reg[i].y; d[2] = reg[i].z; d[3] = reg[i].w;
-                } else {
-                    const int k = f / (ROWS / 4), rq = f % (ROWS / 4);
-                    *reinterpret_cast<float4*>(l + k * ROWS + rq * 4) = reg[i];
-                }
-            }
+        for (int i = 0; i < SLOTS; ++i) { dst[i] += delta; asm volatile("" : "+v"(dst[i])); }
+    }
+    __device__ void stage(int i) {
+        lds_float* d = dst[i];
+        if (!KM) {
+            d[0] = reg[i].x; d[1] = reg[i].y; d[2] = reg[i].z; d[3] = reg[i].w;
+        } else {
+            *(lds_f32x4*)d = reg[i];
         }
     }
 };
@@ -80,18 +97,14 @@ __global__ void __launch_bounds__(G::T, 2)
 k_gemm(int M, int Nn, int Kd, int k_per_split, const float* __restrict__ A, const float* __restrict__ B,
        float* __restrict__ Cout) {
     constexpr int MT = G::MT, NT = G::NT, T = G::T;
-    __shared__ __attribute__((aligned(16))) float al[G::A_LDS];
-    __shared__ __attribute__((aligned(16))) float bl[G::B_LDS];
+    extern __shared__ __attribute__((aligned(16))) float lds[];      // two (A tile, B tile) buffers
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
     const int half = lane >> 5, l32 = lane & 31;
     const int wm = wave % G::WGM, wn = wave / G::WGM;
     const int n0 = blockIdx.x * G::TN, m0 = blockIdx.y * G::TM;
     const int k_begin = blockIdx.z * k_per_split;
     const int k_end = min(k_begin + k_per_split, Kd);
-
-    using SA = Stager<G::AKM, G::TM, T, G::AS>;
-    using SB = Stager<G::BKM, G::TN, T, G::BS>;
-    float4 ar[G::AS], br[G::BS];
+    float* out = Cout + (size_t)blockIdx.z * M * Nn;
 
     f32x16 acc[MT][NT];
 #pragma unroll
@@ -101,44 +114,109 @@ k_gemm(int M, int Nn, int Kd, int k_per_split, const float* __restrict__ A, cons
 #pragma unroll
             for (int v = 0; v < 16; ++v) acc[i][j][v] = 0.f;
 
-    // LDS read addresses: element (row, k) at row*sr + k*sk; the high wave half starts KC/2 further along k
-    constexpr int a_sr = G::AKM ? 1 : KC + 1, a_sk = G::AKM ? G::TM : 1;
-    constexpr int b_sr = G::BKM ? 1 : KC + 1, b_sk = G::BKM ? G::TN : 1;
-    int a_base[MT], b_base[NT];
-#pragma unroll
-    for (int i = 0; i < MT; ++i) a_base[i] = ((wm * MT + i) * 32 + l32) * a_sr + half * (KC / 2) * a_sk;
-#pragma unroll
-    for (int j = 0; j < NT; ++j) b_base[j] = ((wn * NT + j) * 32 + l32) * b_sr + half * (KC / 2) * b_sk;
-
     if (k_begin < k_end) {
-        SA::fetch(A, M, Kd, m0, k_begin, k_end, tid, ar);
-        SB::fetch(B, Nn, Kd, n0, k_begin, k_end, tid, br);
-        for (int k0 = k_begin; k0 < k_end; k0 += KC) {
-            SA::stage(al, tid, ar);
-            SB::stage(bl, tid, br);
-            __syncthreads();
-            if (k0 + KC < k_end) {
-                SA::fetch(A, M, Kd, m0, k0 + KC, k_end, tid, ar);
-                SB::fetch(B, Nn, Kd, n0, k0 + KC, k_end, tid, br);
+        const __amdgpu_buffer_rsrc_t rs_a = __builtin_amdgcn_make_buffer_rsrc(
+            const_cast<float*>(A), 0, (int)((size_t)M * Kd * sizeof(float)), kRsrcWord3);
+        const __amdgpu_buffer_rsrc_t rs_b = __builtin_amdgcn_make_buffer_rsrc(
+            const_cast<float*>(B), 0, (int)((size_t)Nn * Kd * sizeof(float)), kRsrcWord3);
+        Stager<G::AKM, G::TM, T, G::AS> sa;
+        Stager<G::BKM, G::TN, T, G::BS> sb;
+        sa.init(M, Kd, m0, tid, lds);
+        sb.init(Nn, Kd, n0, tid, lds + G::A_LDS);
+        constexpr int NITEMS = G::AS + G::BS;
+        auto fetch_item = [&](int it, int k0, bool whole) {
+            if (it < G::AS) sa.fetch(it, rs_a, M, k0, k_end, whole);
+            else sb.fetch(it - G::AS, rs_b, Nn, k0, k_end, whole);
+        };
+        auto stage_item = [&](int it) {
+            if (it < G::AS) sa.stage(it);
+            else sb.stage(it - G::AS);
+        };
+
+        // LDS read pointers: element (row, k) at row*sr + k*sk; the high wave half starts KC/2 further along k
+        constexpr int a_sr = G::AKM ? 1 : KC + 1, a_sk = G::AKM ? G::TM : 1;
+        constexpr int b_sr = G::BKM ? 1 : KC + 1, b_sk = G::BKM ? G::TN : 1;
+        const lds_float* ap = (const lds_float*)(lds + (wm * MT * 32 + l32) * a_sr + half * (KC / 2) * a_sk);
+        const lds_float* bp = (const lds_float*)(lds + G::A_LDS + (wn * NT * 32 + l32) * b_sr + half * (KC / 2) * b_sk);
+        // operands of group g: two k-steps (kk = 2g, 2g+1) for every row / column block of the wave
+        constexpr int NG = KC / 4;
+        auto read_group = [&](int g, float (&a)[MT][2], float (&b)[NT][2]) {
+#pragma unroll
+            for (int i = 0; i < MT; ++i)
+#pragma unroll
+                for (int t = 0; t < 2; ++t) a[i][t] = ap[i * 32 * a_sr + (2 * g + t) * a_sk];
+#pragma unroll
+            for (int j = 0; j < NT; ++j)
+#pragma unroll
+                for (int t = 0; t < 2; ++t) b[j][t] = bp[j * 32 * b_sr + (2 * g + t) * b_sk];
+        };
+
+        const int nchunks = (k_end - k_begin + KC - 1) / KC;
+        auto chunk_k = [&](int c) { return k_begin + (c < nchunks - 1 ? c : nchunks - 1) * KC; };   // clamped
+        auto chunk_whole = [&](int c) { return c < nchunks - 1 || k_begin + nchunks * KC <= k_end; };
+#pragma unroll
+        for (int it = 0; it < NITEMS; ++it) fetch_item(it, chunk_k(0), chunk_whole(0));
+#pragma unroll
+        for (int it = 0; it < NITEMS; ++it) stage_item(it);
+#pragma unroll
+        for (int it = 0; it < NITEMS; ++it) fetch_item(it, chunk_k(1), chunk_whole(1));
+        __syncthreads();
+        float a_cur[MT][2], b_cur[NT][2];
+        read_group(0, a_cur, b_cur);
+        int wr_off = G::BUF;                      // staging writes go to the buffer that is not being read
+        sa.flip(wr_off);
+        sb.flip(wr_off);
+        for (int c = 0; c < nchunks; ++c) {
+            const int k2 = chunk_k(c + 2);
+            const bool whole2 = chunk_whole(c + 2);
+            constexpr int IPG = (NITEMS + NG - 1) / NG;
+#pragma unroll
+            for (int g = 0; g < NG; ++g) {
+#pragma unroll
+                for (int u = 0; u < IPG; ++u) {
+                    const int it = g * IPG + u;
+                    if (it < NITEMS) {
+                        stage_item(it);
+                        fetch_item(it, k2, whole2);
+                    }
+                }
+                float a_nxt[MT][2], b_nxt[NT][2];
+                if (g + 1 < NG) {
+                    read_group(g + 1, a_nxt, b_nxt);
+                } else {
+                    __syncthreads();
+                    // swap the roles of the two buffers
+                    ap += wr_off; bp += wr_off;
+                    asm volatile("" : "+v"(ap)); asm volatile("" : "+v"(bp));
+                    sa.flip(-wr_off);
+                    sb.flip(-wr_off);
+                    wr_off = -wr_off;
+                    read_group(0, a_nxt, b_nxt);
+                }
+#pragma unroll
+                for (int t = 0; t < 2; ++t)
+#pragma unroll
+                    for (int i = 0; i < MT; ++i)
+#pragma unroll
+                        for (int j = 0; j < NT; ++j)
+                            acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x2f32(a_cur[i][t], b_cur[j][t], acc[i][j], 0, 0, 0);
+#pragma unroll
+                for (int k = 0; k < 2 * MT * NT; ++k) {
+                    __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);   // 1 MFMA
+                    __builtin_amdgcn_sched_group_barrier(0x100, 1, 0);   // 1 DS read
+                }
+                __builtin_amdgcn_sched_barrier(0);
+#pragma unroll
+                for (int t = 0; t < 2; ++t) {
+#pragma unroll
+                    for (int i = 0; i < MT; ++i) a_cur[i][t] = a_nxt[i][t];
+#pragma unroll
+                    for (int j = 0; j < NT; ++j) b_cur[j][t] = b_nxt[j][t];
+                }
             }
-#pragma unroll
-            for (int kk = 0; kk < KC / 2; ++kk) {
-                float a[MT], b[NT];
-#pragma unroll
-                for (int i = 0; i < MT; ++i) a[i] = al[a_base[i] + kk * a_sk];
-#pragma unroll
-                for (int j = 0; j < NT; ++j) b[j] = bl[b_base[j] + kk * b_sk];
-#pragma unroll
-                for (int i = 0; i < MT; ++i)
-#pragma unroll
-                    for (int j = 0; j < NT; ++j)
-                        acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x2f32(a[i], b[j], acc[i][j], 0, 0, 0);
-            }
-            __syncthreads();
         }
     }
 
-    float* out = Cout + (size_t)blockIdx.z * M * Nn;
 #pragma unroll
     for (int i = 0; i < MT; ++i)
 #pragma unroll
@@ -193,13 +271,21 @@ GemmPlan plan_gemm(int M, int Nn, int Kd) {
 template <class G>
 int launch(cnn_ctx* ctx, const GemmPlan& p, int M, int Nn, int Kd, const float* A, const float* B, float* C) {
     float* dst = p.nsplit > 1 ? reinterpret_cast<float*>(ctx->ws) : C;
+    constexpr int lds_bytes = 2 * G::BUF * (int)sizeof(float);
+    static bool attr_done = false;
+    if (!attr_done && lds_bytes > 48 * 1024) {
+        hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(&k_gemm<G>),
+                                           hipFuncAttributeMaxDynamicSharedMemorySize, lds_bytes);
+        if (e != hipSuccess) return cnn::hip_check(ctx, e, "hipFuncSetAttribute(gemm)");
+        attr_done = true;
+    }
     dim3 grid((unsigned)((Nn + G::TN - 1) / G::TN), (unsigned)((M + G::TM - 1) / G::TM), (unsigned)p.nsplit);
     static char name[96] = "";
     if (!name[0])
         snprintf(name, sizeof(name), "k_gemm<%dx%d %s%s>", G::TM, G::TN, G::AKM ? "At" : "A", G::BKM ? "B" : "Bt");
     {
         cnn::ProfScope ps(ctx, name, 2.0 * M * Nn * Kd);
-        hipLaunchKernelGGL(k_gemm<G>, grid, dim3(G::T), 0, ctx->stream, M, Nn, Kd, p.k_per_split, A, B, dst);
+        hipLaunchKernelGGL(k_gemm<G>, grid, dim3(G::T), lds_bytes, ctx->stream, M, Nn, Kd, p.k_per_split, A, B, dst);
     }
     int st = cnn::launch_check(ctx, "gemm");
     if (st != CNN_OK || p.nsplit == 1) return st;
@@ -225,6 +311,8 @@ size_t mfma_gemm_ws(int M, int Nn, int Kd) {
 int mfma_gemm(cnn_ctx* ctx, int M, int Nn, int Kd, const float* A, int akm, const float* B, int bkm, float* C) {
     // float4 fetches along the contiguous index of each operand
     if ((akm ? M : Kd) % 4 != 0 || (bkm ? Nn : Kd) % 4 != 0) return CNN_EUNSUPPORTED;
+    // byte offsets inside the kernel are 32-bit
+    if ((size_t)M * Kd * sizeof(float) >= 0x7fffffffu || (size_t)Nn * Kd * sizeof(float) >= 0x7fffffffu) return CNN_EUNSUPPORTED;
     const GemmPlan p = plan_gemm(M, Nn, Kd);
     if (p.ws_bytes && (!ctx->ws || ctx->ws_bytes < p.ws_bytes)) return CNN_EWORKSPACE;
 #define GO(MT, NT, WGM, WGN)                                                                               \
