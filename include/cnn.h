@@ -54,7 +54,8 @@ enum {
     CNN_OP_CONV_BWD_DATA = 1,
     CNN_OP_CONV_BWD_WEIGHT = 2,
     CNN_OP_FC_FWD = 3,     /* N, I = C, O = K; H = W = R = S = 1 */
-    CNN_OP_FC_BWD = 4
+    CNN_OP_FC_BWD = 4,
+    CNN_OP_CONV_FWD_RELU_POOL = 5
 };
 
 /* options for cnn_set_option() */
@@ -108,6 +109,18 @@ int cnn_conv_fwd_relu(cnn_ctx* ctx, int N, int C, int H, int W, int K, int R, in
                       const float* x, const float* w, float* a);
 int cnn_conv_bwd_data_relu(cnn_ctx* ctx, int N, int C, int H, int W, int K, int R, int S, int stride, int pad,
                            const float* dy, const float* w, const float* x_act, float* dz);
+
+/* ---- Forward propagation with the following ReLU AND 2x2 / stride-2 max-pooling folded into the store:
+ *   a[n][k][i][j] = max over the window (2i + di, 2j + dj), di, dj in {0, 1}, of max(conv_fwd(x, w), 0)
+ *   arg[n][k][i][j] = 2*di + dj of that maximum (the first one in row-major window order on ties), as
+ *   cnn_maxpool2_fwd writes it.  a: N*K*(P/2)*(Q/2) floats out, arg: as many bytes out (both device memory).
+ *   The full-size activation is never written: in a conv -> ReLU -> pool chain nothing in the backward pass needs
+ *   it (cnn_maxpool2_relu_bwd works from a and arg).  Results equal cnn_maxpool2_fwd(cnn_conv_fwd_relu(x, w)) bit
+ *   for bit.  P and Q must be even.  Returns CNN_EUNSUPPORTED (nothing launched, outputs untouched) for shapes the
+ *   tiled kernel does not serve: call the two unfused entry points then.  Workspace: cnn_workspace_bytes with
+ *   CNN_OP_CONV_FWD_RELU_POOL. */
+int cnn_conv_fwd_relu_pool(cnn_ctx* ctx, int N, int C, int H, int W, int K, int R, int S, int stride, int pad,
+                           const float* x, const float* w, float* a, uint8_t* arg);
 
 /* ---- Section 2.1 "Weight-gradient Update", summed over the per-GPU minibatch (no 1/N):
  *   dw[k][c][r][s] = sum_{n,p,q} x[n][c][p*stride + r - pad][q*stride + s - pad] * dy[n][k][p][q]

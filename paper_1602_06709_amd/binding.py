@@ -13,7 +13,8 @@ from . import build as _build
 
 _LIB = None
 
-OP_CONV_FWD, OP_CONV_BWD_DATA, OP_CONV_BWD_WEIGHT, OP_FC_FWD, OP_FC_BWD = range(5)
+OP_CONV_FWD, OP_CONV_BWD_DATA, OP_CONV_BWD_WEIGHT, OP_FC_FWD, OP_FC_BWD, OP_CONV_FWD_RELU_POOL = range(6)
+EUNSUPPORTED = -2
 OPT_FORCE_DIRECT = 0
 OPT_PROFILE = 1
 
@@ -37,6 +38,7 @@ SIGNATURES = {
     "cnn_conv_bwd_weight": (_i, _CONV),
     "cnn_conv_fwd_relu": (_i, _CONV),
     "cnn_conv_bwd_data_relu": (_i, [_vp] + [_i] * 9 + [_vp] * 4),
+    "cnn_conv_fwd_relu_pool": (_i, [_vp] + [_i] * 9 + [_vp] * 4),
     "cnn_maxpool2_relu_bwd": (_i, [_vp, _sz, _i, _i, _vp, _vp, _vp, _vp]),
     "cnn_fc_fwd": (_i, [_vp, _i, _i, _i, _vp, _vp, _vp]),
     "cnn_fc_bwd": (_i, [_vp, _i, _i, _i, _vp, _vp, _vp, _vp, _vp]),
@@ -175,6 +177,24 @@ def cnn_conv_fwd(ctx, x, w, stride=1, pad=0, out=None, relu=False):
 
 def cnn_conv_fwd_relu(ctx, x, w, stride=1, pad=0, out=None):
     return cnn_conv_fwd(ctx, x, w, stride, pad, out, relu=True)
+
+
+def cnn_conv_fwd_relu_pool(ctx, x, w, stride=1, pad=0, out=None, arg_out=None):
+    """maxpool2(relu(conv_fwd(x, w))) and the argmax bytes in one kernel; returns None (nothing launched, outputs
+    untouched) when the library does not serve the shape this way."""
+    N, Cc, H, W = x.shape
+    K, C2, R, S = w.shape
+    assert Cc == C2
+    P, Q = out_dim(H, R, stride, pad), out_dim(W, S, stride, pad)
+    ctx.reserve_for(OP_CONV_FWD_RELU_POOL, N, Cc, H, W, K, R, S, stride, pad)
+    a = out if out is not None else torch.empty((N, K, P // 2, Q // 2), dtype=torch.float32, device=x.device)
+    arg = arg_out if arg_out is not None else torch.empty((N, K, P // 2, Q // 2), dtype=torch.uint8, device=x.device)
+    st = lib().cnn_conv_fwd_relu_pool(ctx.handle, N, Cc, H, W, K, R, S, stride, pad, _t(x), _t(w), _t(a),
+                                      _t(arg, torch.uint8))
+    if st == EUNSUPPORTED:
+        return None
+    _check(st, ctx.handle)
+    return a, arg
 
 
 def cnn_conv_bwd_data_relu(ctx, dy, w, x_act, stride=1, pad=0, out=None):

@@ -130,6 +130,7 @@ size_t cnn_workspace_bytes(int op, int N, int C, int H, int W, int K, int R, int
     if (make_shape(N, C, H, W, K, R, S, stride, pad, &s) != CNN_OK) return 0;
     switch (op) {
         case CNN_OP_CONV_FWD: return cnn::mfma_conv_fwd_ws(s);
+        case CNN_OP_CONV_FWD_RELU_POOL: return cnn::mfma_conv_fwd_pool_ws(s);
         case CNN_OP_CONV_BWD_DATA: return cnn::mfma_conv_bwd_data_ws(s);
         case CNN_OP_CONV_BWD_WEIGHT: {
             const size_t a = cnn::mfma_conv_bwd_weight_ws(s);
@@ -165,6 +166,17 @@ int cnn_conv_fwd(cnn_ctx* ctx, int N, int C, int H, int W, int K, int R, int S, 
 int cnn_conv_fwd_relu(cnn_ctx* ctx, int N, int C, int H, int W, int K, int R, int S, int stride, int pad,
                       const float* x, const float* w, float* a) {
     return conv_fwd_impl(ctx, N, C, H, W, K, R, S, stride, pad, x, w, a, 1);
+}
+
+int cnn_conv_fwd_relu_pool(cnn_ctx* ctx, int N, int C, int H, int W, int K, int R, int S, int stride, int pad,
+                           const float* x, const float* w, float* a, uint8_t* arg) {
+    if (!ctx || !x || !w || !a || !arg || !aligned16(x) || !aligned16(w) || !aligned16(a)) return CNN_EINVAL;
+    ConvShape s;
+    int st = make_shape(N, C, H, W, K, R, S, stride, pad, &s);
+    if (st != CNN_OK) return st;
+    if ((s.P | s.Q) & 1) return CNN_EINVAL;
+    if (ctx->force_direct) return CNN_EUNSUPPORTED;
+    return cnn::mfma_conv_fwd_pool(ctx, s, x, w, a, arg);
 }
 
 static int conv_bwd_data_impl(cnn_ctx* ctx, int N, int C, int H, int W, int K, int R, int S, int stride, int pad,

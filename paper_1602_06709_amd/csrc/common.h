@@ -63,6 +63,8 @@ int mfma_conv_bwd_weight(cnn_ctx*, const ConvShape&, const float* x, const float
 size_t mfma_conv_bwd_weight_ws(const ConvShape&);
 size_t mfma_conv_bwd_data_ws(const ConvShape&);
 size_t mfma_conv_fwd_ws(const ConvShape&);
+size_t mfma_conv_fwd_pool_ws(const ConvShape&);
+int mfma_conv_fwd_pool(cnn_ctx*, const ConvShape&, const float* x, const float* w, float* a, unsigned char* arg);
 // strided first layer (3 input feature maps, 11x11 / 4)
 int c3_strided_conv_fwd(cnn_ctx*, const ConvShape&, const float* x, const float* w, float* y, int relu);
 // few input feature maps (first layers), any kernel size / stride

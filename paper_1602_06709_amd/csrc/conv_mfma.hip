@@ -41,8 +41,10 @@ namespace {
 typedef float f32x16 __attribute__((ext_vector_type(16)));
 typedef __attribute__((address_space(3))) float lds_float;      // LDS pointers are 32-bit: one VGPR each
 
-// epilogues: plain store; ReLU of the result; result where aux > 0 else 0 (ReLU derivative, aux = the ReLU's output)
-enum { EPI_NONE = 0, EPI_RELU = 1, EPI_MASK = 2 };
+// epilogues: plain store; ReLU of the result; result where aux > 0 else 0 (ReLU derivative, aux = the ReLU's output);
+// ReLU followed by 2x2 / stride-2 max-pooling: only the pooled result and the window position of each maximum are
+// stored (the full-size activation is needed by nothing in the backward pass of conv -> ReLU -> pool)
+enum { EPI_NONE = 0, EPI_RELU = 1, EPI_MASK = 2, EPI_POOL = 3 };
 
 // Run-time geometry of one launch (uniform across the grid).
 struct ConvGeo {
@@ -93,7 +95,7 @@ constexpr int kRsrcWord3 = 0x00020000;         // raw buffer descriptor of 32-bi
 template <class G>
 __global__ void __launch_bounds__(G::T, 2)
 k_conv_tiled(ConvGeo g, const float* __restrict__ in, const float* __restrict__ wt, const float* __restrict__ aux,
-             float* __restrict__ out_base, float* __restrict__ partial) {
+             float* __restrict__ out_base, float* __restrict__ partial, unsigned char* __restrict__ arg_out) {
     constexpr int R = G::R, S = G::S, RS = G::RS, CB = G::CB, NT = G::NT, T = G::T, TG = G::TG;
     extern __shared__ float lds[];
     float* wl = lds;
@@ -344,6 +346,65 @@ k_conv_tiled(ConvGeo g, const float* __restrict__ in, const float* __restrict__ 
         }
         return;
     }
+    if (g.epi == EPI_POOL) {
+        // ReLU + 2x2 max-pool.  The tile holds whole row pairs (TR, HO, WO even).  Step 1, in registers: a lane and
+        // its neighbour (pixels q, q+1 of one row) exchange values; the even lane keeps the larger one and which it
+        // was, packed into the sign bit (the values are >= 0 after the ReLU).  Step 2: through LDS (free after the
+        // chunk loop; `hl[feature][pixel pair]`), the row pair is combined and the pooled value and the window
+        // position (row-major, first maximum wins) go to HBM.
+        float* hl = lds;
+        const int hw = g.NPIX / 2;
+        __syncthreads();                       // every wave is done with the operand buffers
+#pragma unroll
+        for (int j = 0; j < NT; ++j) {
+            const int i = (wn * NT + j) * 32 + l32;
+#pragma unroll
+            for (int v = 0; v < 16; ++v) {
+                const float val = acc[j][v] > 0.f ? acc[j][v] : 0.f;
+                const float other = __builtin_bit_cast(
+                    float, __builtin_amdgcn_update_dpp(0, __builtin_bit_cast(int, val), 0xB1, 0xF, 0xF, true));   // lane ^ 1
+                const bool right = other > val;                               // even lane: `other` is the pixel to the right
+                const float hmax = right ? other : val;
+                acc[j][v] = __builtin_bit_cast(float, __builtin_bit_cast(unsigned, hmax) | (right ? 0x80000000u : 0u));
+            }
+            if ((lane & 1) == 0 && i < g.NPIX) {
+#pragma unroll
+                for (int v = 0; v < 16; ++v) {
+                    const int m = wm * 32 + 8 * (v / 4) + 4 * half + (v % 4);
+                    hl[m * hw + i / 2] = acc[j][v];
+                }
+            }
+        }
+        __syncthreads();
+        // pooled pixels of the tile, the same for every feature: (TR/2) x (WO/2), one or two per lane
+        const int pw = g.WO / 2, per_m = (g.TR / 2) * pw, php = g.HO / 2;
+        constexpr int PPL = (G::NPIXB / 4 + 63) / 64;
+        int src[PPL];
+        size_t dst[PPL];
+        bool ok[PPL];
+#pragma unroll
+        for (int t = 0; t < PPL; ++t) {
+            const int e = lane + 64 * t, pr = e / pw, pq = e % pw;
+            const int orow = row0 + 2 * pr;
+            ok[t] = e < per_m && orow < nrows;
+            src[t] = 2 * pr * pw + pq;
+            dst[t] = ((size_t)(orow / g.HO) * M * php + (orow % g.HO) / 2) * pw + pq;
+        }
+        for (int m = wave; m < G::MB && m0 + m < M; m += T / 64) {
+#pragma unroll
+            for (int t = 0; t < PPL; ++t) {
+                if (!ok[t]) continue;
+                const float top = hl[m * hw + src[t]], bot = hl[m * hw + src[t] + pw];
+                const float vt = __builtin_fabsf(top), vb = __builtin_fabsf(bot);
+                const bool lower = vb > vt;
+                const unsigned bits = __builtin_bit_cast(unsigned, lower ? bot : top);
+                const size_t o = dst[t] + (size_t)(m0 + m) * php * pw;
+                out_base[o] = lower ? vb : vt;
+                arg_out[o] = (unsigned char)((lower ? 2u : 0u) + (bits >> 31));
+            }
+        }
+        return;
+    }
     float* out = out_base;
 #pragma unroll
     for (int j = 0; j < NT; ++j) {
@@ -390,7 +451,8 @@ __global__ void __launch_bounds__(256) k_transpose_flip(int K, int C, int RS, co
 // Adds up the slices of every tail unit in slice order and stores the tile with the epilogue applied.
 // grid = (tail units, MB / 8): one block owns 8 feature rows of one tile.
 __global__ void __launch_bounds__(256) k_tile_reduce(ConvGeo g, int MB, int cap, const float* __restrict__ partial,
-                                                    const float* __restrict__ aux, float* __restrict__ out) {
+                                                    const float* __restrict__ aux, float* __restrict__ out,
+                                                    unsigned char* __restrict__ arg_out) {
     const int xcd = blockIdx.x / g.tail_per_xcd, unit = g.full_per_xcd + blockIdx.x % g.tail_per_xcd;
     const int ptile = xcd * g.per_xcd + unit / g.mtiles;
     if (ptile >= g.ptiles) return;
@@ -398,6 +460,29 @@ __global__ void __launch_bounds__(256) k_tile_reduce(ConvGeo g, int MB, int cap,
     const int row0 = ptile * g.TR, nrows = g.N * g.HO;
     const size_t out_plane = (size_t)g.HO * g.WO, tile = (size_t)MB * cap;
     const float* pt = partial + (size_t)blockIdx.x * g.nsl * tile;
+    if (g.epi == EPI_POOL) {
+        // ReLU + 2x2 max-pool of the summed tile: one thread per pooled element (window order: row-major, first
+        // maximum wins, as in the stand-alone pooling kernel)
+        const int pw = g.WO / 2, per_m = (g.TR / 2) * pw, php = g.HO / 2;
+        for (int e = threadIdx.x; e < 8 * per_m; e += 256) {
+            const int ml = blockIdx.y * 8 + e / per_m, rem = e % per_m, pr = rem / pw, pq = rem % pw;
+            const int orow = row0 + 2 * pr;
+            if (orow >= nrows || m0 + ml >= g.M) continue;
+            float best = 0.f;
+            int idx = 0;
+            for (int w4 = 0; w4 < 4; ++w4) {
+                const int i = (2 * pr + w4 / 2) * g.WO + 2 * pq + (w4 & 1);
+                float r = 0.f;
+                for (int s = 0; s < g.nsl; ++s) r += pt[s * tile + (size_t)ml * cap + i];
+                r = r > 0.f ? r : 0.f;
+                if (w4 == 0 || r > best) { best = r; idx = w4; }
+            }
+            const size_t o = (((size_t)(orow / g.HO) * g.M + m0 + ml) * php + (orow % g.HO) / 2) * pw + pq;
+            out[o] = best;
+            arg_out[o] = (unsigned char)idx;
+        }
+        return;
+    }
     for (int e = threadIdx.x; e < 8 * cap; e += 256) {
         const int ml = blockIdx.y * 8 + e / cap, i = e % cap;
         const int orow = row0 + i / g.WO;
@@ -416,6 +501,7 @@ struct LaunchArgs {
     size_t lds_bytes;
     const float *in, *wt, *aux;
     float *out, *partial;
+    unsigned char* arg;
 };
 typedef int (*LaunchFn)(cnn_ctx*, const LaunchArgs&);
 
@@ -439,7 +525,7 @@ int launch(cnn_ctx* ctx, const LaunchArgs& a) {
     {
         cnn::ProfScope ps(ctx, name, 2.0 * a.g.N * a.g.J * a.g.M * G::RS * a.g.HO * a.g.WO);
         hipLaunchKernelGGL(k_conv_tiled<G>, grid, dim3(G::T), a.lds_bytes, ctx->stream, a.g, a.in, a.wt, a.aux, a.out,
-                           a.partial);
+                           a.partial, a.arg);
     }
     return cnn::launch_check(ctx, "conv_tiled");
 }
@@ -483,13 +569,15 @@ struct ConvPlan {
 // Chooses, among the instantiations for this kernel size, the pixel tile (TR consecutive output rows of the whole
 // minibatch) that wastes the fewest MFMA lanes, prefers the 128-feature tile unless the layer has at most 64 output
 // features, and slices the contraction of the tail units (below).
-bool make_plan(int R, int S, int pad, int stride, int N, int J, int M, int HI, int WI, ConvPlan* p) {
+// pool: the plan is for the ReLU + 2x2 max-pool epilogue (whole row pairs per tile, LDS room for the exchange).
+bool make_plan(int R, int S, int pad, int stride, int N, int J, int M, int HI, int WI, ConvPlan* p, bool pool = false) {
     if (HI + 2 * pad < R || WI + 2 * pad < S) return false;
     // byte offsets inside the kernel are 32-bit: the filter tensor, and (below) the images one pixel tile touches
     if ((size_t)M * J * R * S * sizeof(float) >= 0x7fffffffu) return false;
     const int HO = (HI + 2 * pad - R) / stride + 1, WO = (WI + 2 * pad - S) / stride + 1;
     const int WLD = WI + 2 * pad, VH = HI + 2 * pad;
     const long nrows = (long)N * HO;
+    if (pool && ((HO | WO) & 1)) return false;
     double best = 0.0;
     bool found = false;
     for (const Variant& v : kVariants) {
@@ -500,6 +588,7 @@ bool make_plan(int R, int S, int pad, int stride, int N, int J, int M, int HI, i
         if (WO > cap) continue;
         const int tr_max = (long)(cap / WO) < nrows ? cap / WO : (int)nrows;
         for (int TR = tr_max; TR >= 1; --TR) {
+            if (pool && (TR & 1)) continue;
             const int ptiles = (int)((nrows + TR - 1) / TR);
             // staged rows of the widest tile: from the first output row's first input row to the last one's last,
             // through the pad rows between images (the tile starts repeat with period HO)
@@ -518,7 +607,9 @@ bool make_plan(int R, int S, int pad, int stride, int N, int J, int M, int HI, i
                 const int WLDP = padded ? WO + 32 * ((WLD - WO + 31) / 32) : WLD;
                 const int PLANEP = THI * WLDP;
                 const int lds_buf = v.mb * v.wstr + v.CB * PLANEP;
-                const size_t lds_bytes = (size_t)lds_buf * 2 * sizeof(float);   // two buffers
+                size_t lds_bytes = (size_t)lds_buf * 2 * sizeof(float);   // two buffers
+                if (pool && lds_bytes < (size_t)v.mb * (TR * WO / 2) * sizeof(float))
+                    lds_bytes = (size_t)v.mb * (TR * WO / 2) * sizeof(float);   // the pooling exchange reuses them
                 if (lds_bytes > 156 * 1024) continue;
                 // an instantiation compiled for fixed LDS strides serves exactly those
                 if (v.wldp && (v.wldp != WLDP || v.planep != PLANEP)) continue;
@@ -598,15 +689,15 @@ bool make_plan(int R, int S, int pad, int stride, int N, int J, int M, int HI, i
 
 // ws: scratch for the partial tiles (only touched when the plan has tail units)
 int run_plan(cnn_ctx* ctx, ConvPlan& p, const float* in, const float* wt, float* out, float* ws, int epi,
-             const float* aux) {
+             const float* aux, unsigned char* arg = nullptr) {
     p.g.epi = epi;
-    LaunchArgs a{p.g, p.lds_bytes, in, wt, aux, out, ws};
+    LaunchArgs a{p.g, p.lds_bytes, in, wt, aux, out, ws, arg};
     int st = p.v->fn(ctx, a);
     if (st != CNN_OK || p.g.tail_per_xcd == 0) return st;
     {
         cnn::ProfScope ps(ctx, "k_tile_reduce", 0.0);
         hipLaunchKernelGGL(k_tile_reduce, dim3((unsigned)(8 * p.g.tail_per_xcd), (unsigned)(p.v->mb / 8)), dim3(256), 0,
-                           ctx->stream, p.g, p.v->mb, p.v->nt * p.v->wn * 32, ws, aux, out);
+                           ctx->stream, p.g, p.v->mb, p.v->nt * p.v->wn * 32, ws, aux, out, arg);
     }
     return cnn::launch_check(ctx, "tile_reduce");
 }
@@ -626,6 +717,20 @@ int mfma_conv_fwd(cnn_ctx* ctx, const ConvShape& s, const float* x, const float*
     if (!make_plan(s.R, s.S, s.pad, s.stride, s.N, s.C, s.K, s.H, s.W, &p)) return CNN_EUNSUPPORTED;
     if (p.partial_bytes && (!ctx->ws || ctx->ws_bytes < p.partial_bytes)) return CNN_EWORKSPACE;
     return run_plan(ctx, p, x, w, y, reinterpret_cast<float*>(ctx->ws), relu ? EPI_RELU : EPI_NONE, nullptr);
+}
+
+size_t mfma_conv_fwd_pool_ws(const ConvShape& s) {
+    ConvPlan p;
+    if (!make_plan(s.R, s.S, s.pad, s.stride, s.N, s.C, s.K, s.H, s.W, &p, true)) return 0;
+    return p.partial_bytes;
+}
+
+// a = maxpool2(max(conv_fwd(x, w), 0)) and the window position of each maximum; the full-size result is not stored.
+int mfma_conv_fwd_pool(cnn_ctx* ctx, const ConvShape& s, const float* x, const float* w, float* a, unsigned char* arg) {
+    ConvPlan p;
+    if (!make_plan(s.R, s.S, s.pad, s.stride, s.N, s.C, s.K, s.H, s.W, &p, true)) return CNN_EUNSUPPORTED;
+    if (p.partial_bytes && (!ctx->ws || ctx->ws_bytes < p.partial_bytes)) return CNN_EWORKSPACE;
+    return run_plan(ctx, p, x, w, a, reinterpret_cast<float*>(ctx->ws), EPI_POOL, nullptr, arg);
 }
 
 // Backpropagation with stride 1 is a forward convolution of dy (P x Q, K channels) with the mirrored

@@ -14,11 +14,14 @@ from . import synth
 
 
 class Net:
-    def __init__(self, ctx, wl: synth.Workload, weights=None, record=False, fuse=True):
+    def __init__(self, ctx, wl: synth.Workload, weights=None, record=False, fuse=True, fuse_pool=True):
         """fuse=True folds every ReLU that follows a convolution into the convolution's store, and its derivative
         into the store of whatever produces the gradient in front of it (the next convolution's backpropagation or
-        the max-pool backward); fuse=False calls one entry point per layer."""
+        the max-pool backward); fuse=False calls one entry point per layer.
+        fuse_pool (with fuse): a conv -> ReLU -> 2x2 max-pool chain becomes one call that stores only the pooled
+        activation and the window positions, where the library serves the shape that way."""
         self.ctx, self.wl, self.record, self.fuse = ctx, wl, record, fuse
+        self.fuse_pool = bool(fuse and fuse_pool)
         self.layers = list(wl.layers)
         dev = torch.device("cuda")
         wshapes = synth.weight_shapes(wl)
@@ -69,7 +72,7 @@ class Net:
             sin = shp[i]
             if L[0] == "conv":
                 _, c, k, r, s, st, pad = L
-                for op in (B.OP_CONV_FWD, B.OP_CONV_BWD_DATA, B.OP_CONV_BWD_WEIGHT):
+                for op in (B.OP_CONV_FWD, B.OP_CONV_FWD_RELU_POOL, B.OP_CONV_BWD_DATA, B.OP_CONV_BWD_WEIGHT):
                     need = max(need, L_.cnn_workspace_bytes(op, sin[0], c, sin[2], sin[3], k, r, s, st, pad))
             elif L[0] == "fc":
                 for op in (B.OP_FC_FWD, B.OP_FC_BWD):
@@ -98,7 +101,15 @@ class Net:
             if i in skip:
                 continue
             if kind == "conv":
-                if self._fused_relu_after(i):
+                pooled = None
+                if (self.fuse_pool and self._fused_relu_after(i) and i + 2 < len(self.layers)
+                        and self.layers[i + 2][0] == "pool" and self.act[i].shape[2] % 2 == 0 and self.act[i].shape[3] % 2 == 0):
+                    pooled = B.cnn_conv_fwd_relu_pool(ctx, xin, self.w[wi], L[5], L[6], out=self.act[i + 2],
+                                                      arg_out=self.arg[i + 2])
+                if pooled is not None:
+                    self._rec("conv_fwd_relu_pool", i, wi, xin, self.w[wi], self.act[i + 2], self.arg[i + 2])
+                    skip.update((i + 1, i + 2))
+                elif self._fused_relu_after(i):
                     B.cnn_conv_fwd_relu(ctx, xin, self.w[wi], L[5], L[6], out=self.act[i + 1])
                     self._rec("conv_fwd_relu", i, wi, xin, self.w[wi], self.act[i + 1])
                     skip.add(i + 1)

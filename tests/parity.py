@@ -71,6 +71,34 @@ def check_trace_item(item, cfg, layers, full, n_samples=20000, n_samples_wgrad=1
         idx = sample(cfg, 1000 + i, a.size, n_samples)
         ref, s = oracle.conv_fwd_at(x, w, idx, L[5], L[6])
         return check_contraction(name, a.ravel()[idx], np.maximum(ref, 0.0), s)
+    if op == "conv_fwd_relu_pool":
+        # fused conv -> ReLU -> 2x2 max-pool: the pooled value against the oracle's maximum; the recorded window
+        # position must hold a value within the contraction tolerance of that maximum, and must be the oracle's own
+        # position wherever the oracle's maximum is unique beyond that tolerance (fp32 decides near-ties)
+        _, _, wi, x, w, a, arg = item
+        x, w, a, arg = np_(x), np_(w), np_(a), np_(arg).astype(np.int64)
+        N_, K_, PH, PW = a.shape
+        P_, Q_ = 2 * PH, 2 * PW
+        idx = np.arange(a.size) if full else sample(cfg, 1000 + i, a.size, max(1, n_samples // 4))
+        pj = idx % PW; pi = (idx // PW) % PH; plane = idx // (PW * PH)
+        win = np.stack([(plane * P_ + 2 * pi + d // 2) * Q_ + 2 * pj + d % 2 for d in range(4)], axis=1)   # [n, 4]
+        if full:
+            ref, s_ = oracle.conv_fwd(x, w, L[5], L[6], with_abs=True)
+            r4, s4 = np.maximum(ref, 0.0).ravel()[win], s_.ravel()[win]
+        else:
+            ref, s_ = oracle.conv_fwd_at(x, w, win.ravel(), L[5], L[6])
+            r4, s4 = np.maximum(ref, 0.0).reshape(-1, 4), s_.reshape(-1, 4)
+        smax = s4.max(axis=1)
+        rel = check_contraction(name, a.ravel()[idx], r4.max(axis=1), smax)
+        got_arg = arg.ravel()[idx]
+        assert got_arg.min() >= 0 and got_arg.max() <= 3, name + ": window position out of range"
+        chosen = np.take_along_axis(r4, got_arg[:, None], axis=1)[:, 0]
+        tol = 2 * PER_ELEM * smax
+        assert np.all(r4.max(axis=1) - chosen <= tol), name + ": recorded window position does not hold the maximum"
+        srt = np.sort(r4, axis=1)
+        unique = srt[:, 3] - srt[:, 2] > tol
+        assert np.array_equal(got_arg[unique], np.argmax(r4, axis=1)[unique]), name + ": wrong window position"
+        return rel
     if op == "conv_bwd_data_relu":
         _, _, wi, dy, w, xact, dz = item
         dy, w, xact, dz = np_(dy), np_(w), np_(xact), np_(dz)

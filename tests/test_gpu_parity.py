@@ -205,11 +205,11 @@ def test_argument_validation_launches_nothing(cnn, ctx):
 
 
 # ------------------------------------------------------------------ the network workloads, per call, teacher-forced
-def _run_and_check(cnn, ctx, cfg, N, full, fuse=True, **kw):
+def _run_and_check(cnn, ctx, cfg, N, full, fuse=True, fuse_pool=True, **kw):
     from paper_1602_06709_amd.net import Net
     wl = synth.workload(cfg, N)
-    say(f"workload cfg{cfg} N={wl.input_shape[0]} full={full} fuse={fuse}")
-    net = Net(ctx, wl, synth.make_weights(wl), record=True, fuse=fuse)
+    say(f"workload cfg{cfg} N={wl.input_shape[0]} full={full} fuse={fuse} fuse_pool={fuse_pool}")
+    net = Net(ctx, wl, synth.make_weights(wl), record=True, fuse=fuse, fuse_pool=fuse_pool)
     net.set_input(synth.make_input(wl), synth.make_labels(wl) if wl.loss else None)
     net.forward()
     if wl.loss:
@@ -235,9 +235,9 @@ def _run_and_check(cnn, ctx, cfg, N, full, fuse=True, **kw):
     return worst
 
 
-@pytest.mark.parametrize("fuse", [True, False])
+@pytest.mark.parametrize("fuse", [True, "no-pool", False])
 def test_config2_vgg_a_conv_stack_n4_full_tensors(cnn, ctx, fuse):
-    _run_and_check(cnn, ctx, 2, None, True, fuse=fuse)
+    _run_and_check(cnn, ctx, 2, None, True, fuse=bool(fuse), fuse_pool=fuse is True)
 
 
 def test_fused_relu_entry_points_equal_the_unfused_sequence(cnn, ctx):
@@ -263,6 +263,28 @@ def test_fused_relu_entry_points_equal_the_unfused_sequence(cnn, ctx):
     g = dev(synth.randn(97, 5, tuple(y.shape)))
     fused = cnn.cnn_maxpool2_relu_bwd(ctx, g, arg, y, 8, 12)
     assert torch.equal(fused, cnn.cnn_relu_bwd(ctx, dev(zz), cnn.cnn_maxpool2_bwd(ctx, g, arg, 8, 12)))
+
+
+def test_fused_conv_relu_pool_equals_the_unfused_sequence(cnn, ctx):
+    # conv_fwd_relu_pool == maxpool2_fwd(conv_fwd_relu(x, w)), values and window positions bit for bit: the first
+    # layer shape (C = 3, two wave columns), whole / sliced / ragged tiles, tiles spanning images, 5x5, odd N;
+    # and against the oracle
+    for (N, C, H, K, R, pad) in [(2, 3, 224, 64, 3, 1), (3, 16, 28, 72, 3, 1), (2, 64, 28, 128, 3, 1), (5, 32, 14, 48, 3, 1),
+                                 (3, 128, 12, 64, 3, 1), (1, 8, 112, 136, 3, 1), (2, 8, 28, 40, 5, 0), (3, 64, 56, 128, 3, 1),
+                                 (7, 8, 8, 40, 3, 1)]:
+        say("fused pool case", (N, C, H, K, R, pad))
+        x = synth.randn(98, 1, (N, C, H, H)); w = synth.randn(98, 2, (K, C, R, R), 0.1)
+        r = cnn.cnn_conv_fwd_relu_pool(ctx, dev(x), dev(w), 1, pad)
+        assert r is not None, "the tiled kernel serves these shapes"
+        a, arg = r
+        a2, arg2 = cnn.cnn_maxpool2_fwd(ctx, cnn.cnn_conv_fwd_relu(ctx, dev(x), dev(w), 1, pad))
+        torch.cuda.synchronize()
+        assert torch.equal(a, a2)
+        assert torch.equal(arg, arg2)
+        P.check_trace_item(("conv_fwd_relu_pool", 0, 0, dev(x), dev(w), a, arg), 0, [("conv", C, K, R, R, 1, pad)], True)
+    # odd output sizes are refused before anything is launched
+    L = cnn.lib(); z = dev(np.zeros((1, 1, 5, 5), np.float32)); b = torch.zeros(4, dtype=torch.uint8, device="cuda")
+    assert L.cnn_conv_fwd_relu_pool(ctx.handle, 1, 1, 5, 5, 1, 3, 3, 1, 1, z.data_ptr(), z.data_ptr(), z.data_ptr(), b.data_ptr()) == -1
 
 
 def test_config5_dnn7_n1024_sampled(cnn, ctx):
