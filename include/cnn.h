@@ -122,6 +122,17 @@ int cnn_conv_bwd_data_relu(cnn_ctx* ctx, int N, int C, int H, int W, int K, int 
 int cnn_conv_fwd_relu_pool(cnn_ctx* ctx, int N, int C, int H, int W, int K, int R, int S, int stride, int pad,
                            const float* x, const float* w, float* a, uint8_t* arg);
 
+/* ---- Backpropagation through a layer whose forward input x (N*C*H*W) was the output of ReLU -> 2x2 max-pool of a
+ *   N*C*(2H)*(2W) tensor, with the max-pool backward and the ReLU derivative folded into the store:
+ *   dz[n][c][2i + di][2j + dj] = conv_bwd_data(dy, w)[n][c][i][j]  if arg[n][c][i][j] == 2*di + dj and
+ *                                                                   a_pool[n][c][i][j] > 0,   else 0
+ *   a_pool, arg: that pooled activation (this layer's forward input) and its window positions, N*C*H*W each, in.
+ *   dz: N*C*(2H)*(2W) out, every element written.  Equals cnn_maxpool2_relu_bwd(cnn_conv_bwd_data(dy, w), arg,
+ *   a_pool) bit for bit; the pooled-size gradient is never stored.  Workspace as cnn_conv_bwd_data.  Returns
+ *   CNN_EUNSUPPORTED (nothing launched) for shapes the tiled kernel does not serve. */
+int cnn_conv_bwd_data_unpool_relu(cnn_ctx* ctx, int N, int C, int H, int W, int K, int R, int S, int stride, int pad,
+                                  const float* dy, const float* w, const uint8_t* arg, const float* a_pool, float* dz);
+
 /* ---- Section 2.1 "Weight-gradient Update", summed over the per-GPU minibatch (no 1/N):
  *   dw[k][c][r][s] = sum_{n,p,q} x[n][c][p*stride + r - pad][q*stride + s - pad] * dy[n][k][p][q]
  *   x, dy in; dw: K*C*R*S out.  Needs workspace (partial sums of the split contraction,

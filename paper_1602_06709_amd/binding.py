@@ -39,6 +39,7 @@ SIGNATURES = {
     "cnn_conv_fwd_relu": (_i, _CONV),
     "cnn_conv_bwd_data_relu": (_i, [_vp] + [_i] * 9 + [_vp] * 4),
     "cnn_conv_fwd_relu_pool": (_i, [_vp] + [_i] * 9 + [_vp] * 4),
+    "cnn_conv_bwd_data_unpool_relu": (_i, [_vp] + [_i] * 9 + [_vp] * 5),
     "cnn_maxpool2_relu_bwd": (_i, [_vp, _sz, _i, _i, _vp, _vp, _vp, _vp]),
     "cnn_fc_fwd": (_i, [_vp, _i, _i, _i, _vp, _vp, _vp]),
     "cnn_fc_bwd": (_i, [_vp, _i, _i, _i, _vp, _vp, _vp, _vp, _vp]),
@@ -195,6 +196,22 @@ def cnn_conv_fwd_relu_pool(ctx, x, w, stride=1, pad=0, out=None, arg_out=None):
         return None
     _check(st, ctx.handle)
     return a, arg
+
+
+def cnn_conv_bwd_data_unpool_relu(ctx, dy, w, arg, a_pool, stride=1, pad=0, out=None):
+    """maxpool2_relu_bwd(conv_bwd_data(dy, w), arg, a_pool) in one kernel; returns None (nothing launched) when the
+    library does not serve the shape this way."""
+    K, Cc, R, S = w.shape
+    N, C2, H, W = a_pool.shape
+    assert Cc == C2
+    ctx.reserve_for(OP_CONV_BWD_DATA, N, Cc, H, W, K, R, S, stride, pad)
+    dz = out if out is not None else torch.empty((N, Cc, 2 * H, 2 * W), dtype=torch.float32, device=dy.device)
+    st = lib().cnn_conv_bwd_data_unpool_relu(ctx.handle, N, Cc, H, W, K, R, S, stride, pad, _t(dy), _t(w),
+                                             _t(arg, torch.uint8), _t(a_pool), _t(dz))
+    if st == EUNSUPPORTED:
+        return None
+    _check(st, ctx.handle)
+    return dz
 
 
 def cnn_conv_bwd_data_relu(ctx, dy, w, x_act, stride=1, pad=0, out=None):

@@ -201,6 +201,18 @@ int cnn_conv_bwd_data_relu(cnn_ctx* ctx, int N, int C, int H, int W, int K, int 
     return conv_bwd_data_impl(ctx, N, C, H, W, K, R, S, stride, pad, dy, w, x_act, dz);
 }
 
+int cnn_conv_bwd_data_unpool_relu(cnn_ctx* ctx, int N, int C, int H, int W, int K, int R, int S, int stride, int pad,
+                                  const float* dy, const float* w, const uint8_t* arg, const float* a_pool, float* dz) {
+    if (!ctx || !dy || !w || !arg || !a_pool || !dz || !aligned16(dy) || !aligned16(w) || !aligned16(a_pool) ||
+        !aligned16(dz))
+        return CNN_EINVAL;
+    ConvShape s;
+    int st = make_shape(N, C, H, W, K, R, S, stride, pad, &s);
+    if (st != CNN_OK) return st;
+    if (ctx->force_direct) return CNN_EUNSUPPORTED;
+    return cnn::mfma_conv_bwd_data(ctx, s, dy, w, dz, a_pool, arg);
+}
+
 int cnn_conv_bwd_weight(cnn_ctx* ctx, int N, int C, int H, int W, int K, int R, int S, int stride, int pad,
                         const float* x, const float* dy, float* dw) {
     if (!ctx || !x || !dy || !dw || !aligned16(x) || !aligned16(dy) || !aligned16(dw)) return CNN_EINVAL;

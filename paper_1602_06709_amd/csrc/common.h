@@ -58,7 +58,8 @@ int direct_conv_bwd_weight(cnn_ctx*, const ConvShape&, const float* x, const flo
 
 // ---- MFMA paths; each returns CNN_EUNSUPPORTED (without launching) for shapes it does not cover
 int mfma_conv_fwd(cnn_ctx*, const ConvShape&, const float* x, const float* w, float* y, int relu);
-int mfma_conv_bwd_data(cnn_ctx*, const ConvShape&, const float* dy, const float* w, float* dx, const float* act);
+int mfma_conv_bwd_data(cnn_ctx*, const ConvShape&, const float* dy, const float* w, float* dx, const float* act,
+                       const unsigned char* arg = nullptr);
 int mfma_conv_bwd_weight(cnn_ctx*, const ConvShape&, const float* x, const float* dy, float* dw);
 size_t mfma_conv_bwd_weight_ws(const ConvShape&);
 size_t mfma_conv_bwd_data_ws(const ConvShape&);

@@ -44,7 +44,10 @@ typedef __attribute__((address_space(3))) float lds_float;      // LDS pointers 
 // epilogues: plain store; ReLU of the result; result where aux > 0 else 0 (ReLU derivative, aux = the ReLU's output);
 // ReLU followed by 2x2 / stride-2 max-pooling: only the pooled result and the window position of each maximum are
 // stored (the full-size activation is needed by nothing in the backward pass of conv -> ReLU -> pool)
-enum { EPI_NONE = 0, EPI_RELU = 1, EPI_MASK = 2, EPI_POOL = 3 };
+// the reverse for backpropagation: the result is the gradient of a pooled activation (aux) whose window positions are
+// known (arg): each value goes to its window's position in the full-size gradient, if the activation was > 0, and
+// zeros to the window's other three positions (max-pool backward + ReLU derivative without the pooled-size round trip)
+enum { EPI_NONE = 0, EPI_RELU = 1, EPI_MASK = 2, EPI_POOL = 3, EPI_UNPOOL = 4 };
 
 // Run-time geometry of one launch (uniform across the grid).
 struct ConvGeo {
@@ -95,7 +98,7 @@ constexpr int kRsrcWord3 = 0x00020000;         // raw buffer descriptor of 32-bi
 template <class G>
 __global__ void __launch_bounds__(G::T, 2)
 k_conv_tiled(ConvGeo g, const float* __restrict__ in, const float* __restrict__ wt, const float* __restrict__ aux,
-             float* __restrict__ out_base, float* __restrict__ partial, unsigned char* __restrict__ arg_out) {
+             float* __restrict__ out_base, float* __restrict__ partial, unsigned char* arg_out) {
     constexpr int R = G::R, S = G::S, RS = G::RS, CB = G::CB, NT = G::NT, T = G::T, TG = G::TG;
     extern __shared__ float lds[];
     float* wl = lds;
@@ -405,6 +408,36 @@ k_conv_tiled(ConvGeo g, const float* __restrict__ in, const float* __restrict__ 
         }
         return;
     }
+    if (g.epi == EPI_UNPOOL) {
+        // lane = pixel (p, q) of the pooled map: its 2x2 window of the full-size gradient is written as two float2,
+        // consecutive lanes writing consecutive 8-byte pairs of rows 2p and 2p+1
+        typedef float f32x2 __attribute__((ext_vector_type(2)));
+#pragma unroll
+        for (int j = 0; j < NT; ++j) {
+            const int i = (wn * NT + j) * 32 + l32;
+            const int orow = row0 + i / g.WO;
+            if (i >= g.NPIX || orow >= nrows) continue;
+            const int n = orow / g.HO, p = orow % g.HO, q = i % g.WO;
+            const size_t o0 = ((size_t)n * M) * out_plane + (size_t)p * g.WO + q;
+            const size_t f0 = ((size_t)n * M) * 4 * out_plane + (size_t)(2 * p) * (2 * g.WO) + 2 * q;
+#pragma unroll
+            for (int v = 0; v < 16; ++v) {
+                const int m = m0 + wm * 32 + 8 * (v / 4) + 4 * half + (v % 4);
+                if (m < M) {
+                    const size_t o = o0 + (size_t)m * out_plane;
+                    const float r = aux[o] > 0.f ? acc[j][v] : 0.f;
+                    const int pos = arg_out[o];
+                    f32x2* d = reinterpret_cast<f32x2*>(out_base + f0 + (size_t)m * 4 * out_plane);
+                    f32x2 top, bot;
+                    top.x = pos == 0 ? r : 0.f; top.y = pos == 1 ? r : 0.f;
+                    bot.x = pos == 2 ? r : 0.f; bot.y = pos == 3 ? r : 0.f;
+                    d[0] = top;
+                    d[g.WO] = bot;        // next row of the full-size map: 2*WO floats = WO pairs further
+                }
+            }
+        }
+        return;
+    }
     float* out = out_base;
 #pragma unroll
     for (int j = 0; j < NT; ++j) {
@@ -452,7 +485,7 @@ __global__ void __launch_bounds__(256) k_transpose_flip(int K, int C, int RS, co
 // grid = (tail units, MB / 8): one block owns 8 feature rows of one tile.
 __global__ void __launch_bounds__(256) k_tile_reduce(ConvGeo g, int MB, int cap, const float* __restrict__ partial,
                                                     const float* __restrict__ aux, float* __restrict__ out,
-                                                    unsigned char* __restrict__ arg_out) {
+                                                    unsigned char* arg_out) {
     const int xcd = blockIdx.x / g.tail_per_xcd, unit = g.full_per_xcd + blockIdx.x % g.tail_per_xcd;
     const int ptile = xcd * g.per_xcd + unit / g.mtiles;
     if (ptile >= g.ptiles) return;
@@ -489,6 +522,16 @@ __global__ void __launch_bounds__(256) k_tile_reduce(ConvGeo g, int MB, int cap,
         if (i >= g.NPIX || orow >= nrows || m0 + ml >= g.M) continue;
         float r = 0.f;
         for (int s = 0; s < g.nsl; ++s) r += pt[s * tile + (size_t)ml * cap + i];
+        if (g.epi == EPI_UNPOOL) {
+            const size_t plane = (size_t)(orow / g.HO) * g.M + m0 + ml;
+            const size_t o = plane * out_plane + (size_t)(orow % g.HO) * g.WO + i % g.WO;
+            r = aux[o] > 0.f ? r : 0.f;
+            const int pos = arg_out[o];
+            float* d = out + plane * 4 * out_plane + (size_t)(2 * (orow % g.HO)) * (2 * g.WO) + 2 * (i % g.WO);
+            d[0] = pos == 0 ? r : 0.f; d[1] = pos == 1 ? r : 0.f;
+            d[2 * g.WO] = pos == 2 ? r : 0.f; d[2 * g.WO + 1] = pos == 3 ? r : 0.f;
+            continue;
+        }
         const size_t o = ((size_t)(orow / g.HO) * g.M + m0 + ml) * out_plane + (size_t)(orow % g.HO) * g.WO + i % g.WO;
         if (g.epi == EPI_RELU) r = r > 0.f ? r : 0.f;
         else if (g.epi == EPI_MASK) r = aux[o] > 0.f ? r : 0.f;
@@ -752,7 +795,10 @@ size_t mfma_conv_bwd_data_ws(const ConvShape& s) {
 }
 
 // act != NULL: dx is zeroed where act <= 0 (act = the ReLU output that was this layer's forward input).
-int mfma_conv_bwd_data(cnn_ctx* ctx, const ConvShape& s, const float* dy, const float* w, float* dx, const float* act) {
+// arg != NULL as well: act is a pooled ReLU output with window positions arg, and dx is the full-size (2H x 2W)
+// gradient in front of that ReLU + pool.
+int mfma_conv_bwd_data(cnn_ctx* ctx, const ConvShape& s, const float* dy, const float* w, float* dx, const float* act,
+                       const unsigned char* arg) {
     ConvPlan p;
     if (!bwd_plan(s, &p)) return CNN_EUNSUPPORTED;      // decided before the workspace is touched
     if (!ctx->ws || ctx->ws_bytes < wt_bytes(s) + p.partial_bytes) return CNN_EWORKSPACE;
@@ -767,7 +813,8 @@ int mfma_conv_bwd_data(cnn_ctx* ctx, const ConvShape& s, const float* dy, const 
     }
     int st = launch_check(ctx, "transpose_flip");
     if (st != CNN_OK) return st;
-    return run_plan(ctx, p, dy, wT, dx, partial, act ? EPI_MASK : EPI_NONE, act);
+    return run_plan(ctx, p, dy, wT, dx, partial, arg ? EPI_UNPOOL : (act ? EPI_MASK : EPI_NONE), act,
+                    const_cast<unsigned char*>(arg));
 }
 
 }  // namespace cnn

@@ -157,7 +157,18 @@ class Net:
             if kind == "conv":
                 B.cnn_conv_bwd_weight(ctx, xin, dy, L[3], L[4], L[5], L[6], out=self.dw[wi])
                 self._rec("conv_bwd_weight", i, wi, xin, dy, self.dw[wi])
-                if not first:
+                # is the input of layer i the output of ReLU -> pool behind a convolution (all folded in the forward pass)?
+                pool_in = (self.fuse_pool and i >= 3 and self.layers[i - 1][0] == "pool" and self.layers[i - 2][0] == "relu"
+                           and self._fused_relu_after(i - 3))
+                unpooled = None
+                if not first and pool_in:
+                    # gradient in front of that ReLU + pool, straight into the earlier convolution's slot
+                    unpooled = B.cnn_conv_bwd_data_unpool_relu(ctx, dy, self.w[wi], self.arg[i - 1], xin, L[5], L[6],
+                                                               out=self.gact[i - 3])
+                if unpooled is not None:
+                    self._rec("conv_bwd_data_unpool_relu", i, wi, dy, self.w[wi], self.arg[i - 1], xin, self.gact[i - 3])
+                    skip.update((i - 1, i - 2))
+                elif not first:
                     if relu_in:      # gradient in front of that ReLU, straight into the earlier convolution's slot
                         B.cnn_conv_bwd_data_relu(ctx, dy, self.w[wi], xin, L[5], L[6], out=self.gact[i - 2])
                         self._rec("conv_bwd_data_relu", i, wi, dy, self.w[wi], xin, self.gact[i - 2])

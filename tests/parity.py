@@ -110,6 +110,25 @@ def check_trace_item(item, cfg, layers, full, n_samples=20000, n_samples_wgrad=1
         idx = sample(cfg, 2000 + i, dz.size, n_samples)
         ref, s = oracle.conv_bwd_data_at(dy, w, H, W, idx, L[5], L[6])
         return check_contraction(name, dz.ravel()[idx], np.where(xact.ravel()[idx] > 0, ref, 0.0), s)
+    if op == "conv_bwd_data_unpool_relu":
+        # fused backpropagation -> max-pool backward -> ReLU derivative: the pooled-size gradient goes to its window
+        # position where the pooled activation is > 0; every other element of the full-size gradient is exactly 0
+        _, _, wi, dy, w, arg, apool, dz = item
+        dy, w, arg, apool, dz = np_(dy), np_(w), np_(arg).astype(np.int64), np_(apool), np_(dz)
+        H, W = apool.shape[2:]
+        di = np.arange(2 * H)[:, None]; dj = np.arange(2 * W)[None, :]
+        pos_full = ((di % 2) * 2 + dj % 2)[None, None]                               # window position of each element
+        up = lambda t: np.repeat(np.repeat(t, 2, axis=2), 2, axis=3)                 # pooled -> full size
+        open_ = (up(arg) == pos_full) & (up(apool) > 0)
+        assert np.all(dz[~open_] == 0), name + ": gradient outside the maximum's position or through a closed ReLU"
+        if full:
+            ref, s_ = oracle.conv_bwd_data(dy, w, H, W, L[5], L[6], with_abs=True)
+            return check_contraction(name, dz, np.where(open_, up(ref), 0.0), up(s_))
+        idx = sample(cfg, 2000 + i, dz.size, n_samples)
+        fj = idx % (2 * W); fi = (idx // (2 * W)) % (2 * H); plane = idx // (4 * H * W)
+        pidx = (plane * H + fi // 2) * W + fj // 2
+        ref, s_ = oracle.conv_bwd_data_at(dy, w, H, W, pidx, L[5], L[6])
+        return check_contraction(name, dz.ravel()[idx], np.where(open_.ravel()[idx], ref, 0.0), s_)
     if op == "pool_relu_bwd":
         _, _, dy, arg, y, dz = item
         H, W = dz.shape[2:]

@@ -282,6 +282,19 @@ def test_fused_conv_relu_pool_equals_the_unfused_sequence(cnn, ctx):
         assert torch.equal(a, a2)
         assert torch.equal(arg, arg2)
         P.check_trace_item(("conv_fwd_relu_pool", 0, 0, dev(x), dev(w), a, arg), 0, [("conv", C, K, R, R, 1, pad)], True)
+        # the way back: conv_bwd_data_unpool_relu == maxpool2_relu_bwd(conv_bwd_data(dy, w), arg, a) for a layer whose
+        # input is that pooled activation
+        K2 = 40
+        w2 = synth.randn(98, 3, (K2, K, 3, 3), 0.1)
+        Hp = a.shape[2]
+        dy2 = synth.randn(98, 4, (N, K2, Hp, Hp))
+        dz = cnn.cnn_conv_bwd_data_unpool_relu(ctx, dev(dy2), dev(w2), arg, a, 1, 1)
+        assert dz is not None
+        dz2 = cnn.cnn_maxpool2_relu_bwd(ctx, cnn.cnn_conv_bwd_data(ctx, dev(dy2), dev(w2), Hp, Hp, 1, 1), arg, a, 2 * Hp, 2 * Hp)
+        torch.cuda.synchronize()
+        assert torch.equal(dz, dz2)
+        P.check_trace_item(("conv_bwd_data_unpool_relu", 0, 0, dev(dy2), dev(w2), arg, a, dz), 0,
+                           [("conv", K, K2, 3, 3, 1, 1)], True)
     # odd output sizes are refused before anything is launched
     L = cnn.lib(); z = dev(np.zeros((1, 1, 5, 5), np.float32)); b = torch.zeros(4, dtype=torch.uint8, device="cuda")
     assert L.cnn_conv_fwd_relu_pool(ctx.handle, 1, 1, 5, 5, 1, 3, 3, 1, 1, z.data_ptr(), z.data_ptr(), z.data_ptr(), b.data_ptr()) == -1
