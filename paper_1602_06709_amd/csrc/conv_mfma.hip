@@ -96,7 +96,7 @@ constexpr int kOutOfRange = (int)0x80000000;   // buffer-load byte offset beyond
 constexpr int kRsrcWord3 = 0x00020000;         // raw buffer descriptor of 32-bit elements
 
 template <class G>
-__global__ void __launch_bounds__(G::T, 2)
+__global__ void __launch_bounds__(G::T, G::VEC == 1 ? 3 : 2)   // first layers are memory-phase bound: a third workgroup per CU helps
 k_conv_tiled(ConvGeo g, const float* __restrict__ in, const float* __restrict__ wt, const float* __restrict__ aux,
              float* __restrict__ out_base, float* __restrict__ partial, unsigned char* arg_out) {
     constexpr int R = G::R, S = G::S, RS = G::RS, CB = G::CB, NT = G::NT, T = G::T, TG = G::TG;
@@ -270,11 +270,14 @@ k_conv_tiled(ConvGeo g, const float* __restrict__ in, const float* __restrict__ 
     const int ch_end = slice < 0 ? nchunks : min(ch_begin + g.chunks_per_slice, nchunks);
     const size_t out_plane = (size_t)g.HO * g.WO;
     constexpr int NSEG = G::NSEG, IPS = (NITEMS + NSEG - 1) / NSEG;
+    // fewer channels than one chunk (VEC == 1: first layers): the whole contraction is this one chunk, nothing is
+    // staged ahead
+    constexpr bool SINGLE = G::VEC == 1;
 #pragma unroll
     for (int it = 0; it < NITEMS; ++it) fetch_item(it, ch_begin * CB);
 #pragma unroll
     for (int it = 0; it < NITEMS; ++it) stage_item(it);
-    {
+    if (!SINGLE) {
         const int c1 = min(ch_begin + 1, ch_end - 1) * CB;
 #pragma unroll
         for (int it = 0; it < NITEMS; ++it) fetch_item(it, c1);
@@ -295,7 +298,7 @@ k_conv_tiled(ConvGeo g, const float* __restrict__ in, const float* __restrict__ 
 #pragma unroll
             for (int u = 0; u < IPS; ++u) {
                 const int it = seg * IPS + u;
-                if (it < NITEMS) {
+                if (it < NITEMS && !SINGLE) {
                     stage_item(it);
                     fetch_item(it, c2);
                 }
@@ -303,7 +306,7 @@ k_conv_tiled(ConvGeo g, const float* __restrict__ in, const float* __restrict__ 
             float a_nxt[TG] = {}, b_nxt[NT][TG] = {};
             if (seg + 1 < NSEG) {
                 read_seg(seg + 1, a_nxt, b_nxt);
-            } else {
+            } else if (!SINGLE) {
                 __syncthreads();
                 flip(wdelta);
                 read_seg(0, a_nxt, b_nxt);
@@ -596,7 +599,7 @@ const Variant kVariants[] = {
     V(3, 3, 4, 4, 1, 7, 4, 2, 3, 0, 0), V(3, 3, 4, 4, 1, 8, 4, 2, 1, 0, 0), V(3, 3, 4, 4, 1, 9, 4, 2, 1, 0, 0),
     V(3, 3, 4, 2, 1, 7, 4, 4, 3, 0, 0), V(3, 3, 4, 2, 1, 8, 4, 4, 1, 0, 0),
     // 3x3 with fewer than 4 contraction channels (first layers)
-    V(3, 3, 4, 2, 2, 7, 1, 4, 3, 0, 0),
+    V(3, 3, 4, 2, 2, 7, 1, 4, 1, 0, 0),
     // 5x5: 64-feature tiles, two wave columns
     V(5, 5, 4, 2, 2, 3, 4, 4, 2, 0, 0), V(5, 5, 4, 2, 2, 4, 4, 4, 2, 0, 0), V(5, 5, 4, 2, 2, 7, 4, 4, 2, 0, 0),
 };
