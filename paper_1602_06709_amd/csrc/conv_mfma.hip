@@ -290,7 +290,26 @@ k_conv_tiled(ConvGeo g, const float* __restrict__ in, const float* __restrict__ 
     for (int j = 0; j < G::XP; ++j) xw[j] += g.lds_buf;
 #pragma unroll
     for (int i = 0; i < G::WSL; ++i) ww[i] += g.lds_buf;
-    for (int ch = ch_begin; ch < ch_end; ++ch) {
+    // A wave whose 32 output features all lie past M (the last feature tile of a ragged M) only takes part in the
+    // staging and the barriers: its MFMAs would be discarded, and skipping them leaves the matrix pipe to the waves
+    // that share its SIMD.
+    const bool wave_live = __builtin_amdgcn_readfirstlane(m0 + wm * 32) < M;
+    if (!wave_live) {
+        for (int ch = ch_begin; ch < ch_end; ++ch) {
+            const int c2 = min(ch + 2, ch_end - 1) * CB;
+            const int wdelta = ((ch - ch_begin) & 1) ? g.lds_buf : -g.lds_buf;
+            if (!SINGLE) {
+#pragma unroll
+                for (int it = 0; it < NITEMS; ++it) {
+                    stage_item(it);
+                    fetch_item(it, c2);
+                }
+                __syncthreads();
+                flip(wdelta);
+            }
+        }
+    }
+    for (int ch = ch_begin; wave_live && ch < ch_end; ++ch) {
         const int c2 = min(ch + 2, ch_end - 1) * CB;      // the staging registers hold chunk min(ch + 1, ch_end - 1)
         const int wdelta = ((ch - ch_begin) & 1) ? g.lds_buf : -g.lds_buf;   // where the write pointers go next
 #pragma unroll
