@@ -72,6 +72,9 @@ def test_workspace_planning(L):
     # partial tiles of the sliced tail; unknown shapes need none (they run on the plain kernels)
     assert ws(binding.OP_CONV_FWD, 64, 256, 56, 56, 256, 3, 3, 1, 1) == 0
     assert ws(binding.OP_CONV_FWD, 64, 512, 28, 28, 512, 3, 3, 1, 1) == 128 * 2 * 128 * 224 * 4
+    # the fused conv -> ReLU -> pool call plans whole row pairs; here that is the same tiling
+    assert ws(binding.OP_CONV_FWD_RELU_POOL, 64, 512, 28, 28, 512, 3, 3, 1, 1) == 128 * 2 * 128 * 224 * 4
+    assert ws(binding.OP_CONV_FWD_RELU_POOL, 2, 8, 7, 7, 16, 3, 3, 1, 1) == 0      # odd output: not served, no scratch
     assert ws(binding.OP_CONV_BWD_WEIGHT, 2, 5, 9, 13, 7, 3, 2, 2, 1) == 0
     # first-layer weight gradient: private copies of dw, one per split of the minibatch's rows
     b = ws(binding.OP_CONV_BWD_WEIGHT, 2, 3, 32, 32, 16, 3, 3, 1, 1)
