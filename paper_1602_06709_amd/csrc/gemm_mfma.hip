@@ -254,6 +254,9 @@ struct GemmPlan {
 GemmPlan plan_gemm(int M, int Nn, int Kd) {
     GemmPlan p;
     p.tm = M <= 64 ? 64 : 128;
+    // too few 128-row tiles to fill the chip and a short contraction: 64-row tiles (twice as many workgroups) beat
+    // splitting the contraction, which needs the partial products written, read back and added
+    if (p.tm == 128 && (long)((M + 127) / 128) * ((Nn + 127) / 128) < 256 && Kd <= 4096) p.tm = 64;
     p.tn = 128;
     const long tiles = (long)((M + p.tm - 1) / p.tm) * ((Nn + p.tn - 1) / p.tn);
     int want = tiles >= 256 ? 1 : (int)((512 + tiles - 1) / tiles);
