@@ -106,13 +106,27 @@ k_wgrad_smallc(SmallcArgs a, const float* __restrict__ x, const float* __restric
                 // start of the range or of an image: all R rows straight into the ring (no prefetch)
                 __syncthreads();                  // nobody still reads the previous image's rows
                 const float* xs = x + (size_t)n * CC * a.H * a.W;
-                if (tid < a.WLD)
-                    for (int rr = 0; rr < a.R; ++rr) {
-                        const int h = p * ST - a.pad + rr;
-                        const bool ok = xcol_ok && h >= 0 && h < a.H;
-                        for (int c = 0; c < CC; ++c)
-                            xl[c * a.cpl + ((h + a.pad) & mask) * a.WLD + tid] = ok ? xs[((size_t)c * a.H + h) * a.W + xcol_w] : 0.f;
+                if (tid < a.WLD) {
+                    // rows in batches of 4: all loads of a batch are issued before its first LDS write (one trip to
+                    // HBM per batch instead of one per element)
+                    for (int r0 = 0; r0 < a.R; r0 += 4) {
+                        float t[4][CC];
+#pragma unroll
+                        for (int i = 0; i < 4; ++i) {
+                            const int h = p * ST - a.pad + r0 + i;
+                            const bool ok = xcol_ok && r0 + i < a.R && h >= 0 && h < a.H;
+#pragma unroll
+                            for (int c = 0; c < CC; ++c) t[i][c] = ok ? xs[((size_t)c * a.H + h) * a.W + xcol_w] : 0.f;
+                        }
+#pragma unroll
+                        for (int i = 0; i < 4; ++i) {
+                            const int h = p * ST - a.pad + r0 + i;
+                            if (r0 + i < a.R)
+#pragma unroll
+                                for (int c = 0; c < CC; ++c) xl[c * a.cpl + ((h + a.pad) & mask) * a.WLD + tid] = t[i][c];
+                        }
                     }
+                }
             } else if (tid < a.WLD) {
                 const int hb = p * ST - a.pad + a.R - ST;
 #pragma unroll
@@ -263,7 +277,10 @@ SmallcPlan plan(const ConvShape& s) {
     a.cpl = ns * a.WLD;
     a.dstr = (tw & 1) ? tw : tw + 1;
     a.total_rows = s.N * s.P;
-    int want = (512 + a.col_tiles - 1) / a.col_tiles;
+    p.lds_bytes = ((size_t)s.C * a.cpl + 2 * 32 * kbk * a.dstr) * sizeof(float);
+    // one round of workgroups: as many as the chip holds at once (one or two per compute unit, by LDS size)
+    const int resident = p.lds_bytes <= 78 * 1024 ? 512 : 256;
+    int want = (resident + a.col_tiles - 1) / a.col_tiles;
     const int warm = (s.R + s.stride - 1) / s.stride;      // steps' worth of rows a fresh window costs
     int min_rows = 4 * warm > 8 ? 4 * warm : 8;
     int max_split = a.total_rows / min_rows;
@@ -271,7 +288,6 @@ SmallcPlan plan(const ConvShape& s) {
     if (want > max_split) want = max_split;
     a.rows_per_split = (a.total_rows + want - 1) / want;
     p.nsplit = (a.total_rows + a.rows_per_split - 1) / a.rows_per_split;
-    p.lds_bytes = ((size_t)s.C * a.cpl + 2 * 32 * kbk * a.dstr) * sizeof(float);
     const size_t red_bytes = p.pw > 1 ? (size_t)p.pw * kbk * 16 * 64 * sizeof(float) : 0;   // cross-wave reduction scratch
     if (p.lds_bytes < red_bytes) p.lds_bytes = red_bytes;
     if (p.lds_bytes > 150 * 1024) return p;
