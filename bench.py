@@ -40,6 +40,8 @@ def main():
     ap.add_argument("--profile-every", type=int, default=5,
                     help="record the per-kernel HIP events on every P-th step of the timed region (the two event "
                          "records around each launch cost about 0.5 ms per VGG-A step; default: steps 0, 5, ...)")
+    ap.add_argument("--separate-sgd", action="store_true",
+                    help="store the weight gradients and update in one pass at the end instead of inside their reductions")
     ap.add_argument("--per-kernel", action="store_true", help="print the per-kernel table to stderr")
     ap.add_argument("--calibrate-copy", action="store_true",
                     help="instead of the benchmark: three plain 1 GiB device-to-device copies (libcnn's identity "
@@ -73,7 +75,7 @@ def main():
     wl = synth.workload(args.config, args.batch)
     N = wl.input_shape[0]
     ctx = cnn.Context()
-    net = Net(ctx, wl, synth.make_weights(wl))
+    net = Net(ctx, wl, synth.make_weights(wl), fuse_sgd=not args.separate_sgd)
     net.set_input(synth.make_input(wl), synth.make_labels(wl) if wl.loss else None)
     upstream = None if wl.loss else torch.from_numpy(synth.make_upstream(wl)).cuda()
 

@@ -153,6 +153,22 @@ int cnn_fc_bwd(cnn_ctx* ctx, int N, int I, int O, const float* x, const float* w
  *   n elements; w and v updated in place.  One launch over the whole (flat) parameter arena. */
 int cnn_sgd_update(cnn_ctx* ctx, size_t n, float* w, const float* dw, float* v, float lr, float momentum);
 
+/* ---- Weight gradient with the SGD step folded into its last stage.  The weight gradient is a two-stage sum: partial
+ *   sums over parts of the minibatch, then their reduction (Section 3.1); the update needs each reduced element
+ *   exactly once (Section 3.4), so the reduction hands it to the update and dw never reaches memory:
+ *     g = the element cnn_conv_bwd_weight / cnn_fc_bwd would store;  v <- momentum * v + g;  w <- w - lr * v
+ *     (v == NULL: w <- w - lr * g).  Same arithmetic as cnn_sgd_update on a stored g: identical bits.
+ *   w [K][C][R][S] (or [O][I]) and v are updated in place.  The layer's backpropagation needs the weights of this
+ *   iteration: issue cnn_conv_bwd_data BEFORE cnn_conv_bwd_weight_sgd; cnn_fc_bwd_sgd computes dx (may be NULL:
+ *   first layer) from the old w itself before it updates.  (The paper computes the weight gradient first so that its
+ *   exchange between nodes overlaps backpropagation; the update there also lands after backpropagation.)
+ *   Workspace: as CNN_OP_CONV_BWD_WEIGHT / CNN_OP_FC_BWD.  Returns CNN_EUNSUPPORTED, with nothing launched and
+ *   nothing modified, for shapes only the plain fallback kernels serve: call the unfused pair there. */
+int cnn_conv_bwd_weight_sgd(cnn_ctx* ctx, int N, int C, int H, int W, int K, int R, int S, int stride, int pad,
+                            const float* x, const float* dy, float* w, float* v, float lr, float momentum);
+int cnn_fc_bwd_sgd(cnn_ctx* ctx, int N, int I, int O, const float* x, float* w, const float* dy, float* dx, float* v,
+                   float lr, float momentum);
+
 /* ---- Section 2.3 data layouts; pure permutations (bit-exact), lanes past C (or K) are written as 0.
  *   activations:        [N][C][H][W]  <->  [N][ceil(C/SW)][H][W][SW]
  *   weights (transpose == 0): [K][C][R][S] <-> [C][ceil(K/SW)][R][S][SW]   (paper: IFM x OFM/SW x KH x KW x SW)

@@ -44,6 +44,8 @@ SIGNATURES = {
     "cnn_fc_fwd": (_i, [_vp, _i, _i, _i, _vp, _vp, _vp]),
     "cnn_fc_bwd": (_i, [_vp, _i, _i, _i, _vp, _vp, _vp, _vp, _vp]),
     "cnn_sgd_update": (_i, [_vp, _sz, _vp, _vp, _vp, _f, _f]),
+    "cnn_conv_bwd_weight_sgd": (_i, [_vp] + [_i] * 9 + [_vp] * 4 + [_f, _f]),
+    "cnn_fc_bwd_sgd": (_i, [_vp, _i, _i, _i, _vp, _vp, _vp, _vp, _vp, _f, _f]),
     "cnn_packed_act_elems": (_sz, [_i] * 5),
     "cnn_packed_wt_elems": (_sz, [_i] * 6),
     "cnn_pack_act": (_i, [_vp] + [_i] * 5 + [_vp] * 2),
@@ -275,6 +277,40 @@ def cnn_sgd_update(ctx, w, dw, v=None, lr=0.01, momentum=0.0):
     _check(lib().cnn_sgd_update(ctx.handle, n, _t(w), _t(dw), _t(v) if v is not None else None, lr, momentum),
            ctx.handle)
     return w
+
+
+def cnn_conv_bwd_weight_sgd(ctx, x, dy, w, v=None, stride=1, pad=0, lr=0.01, momentum=0.0):
+    """The weight gradient of (x, dy) applied to w (and v) in place, without storing it; returns None (nothing
+    launched, w untouched) when the library does not serve the shape this way."""
+    N, Cc, H, W = x.shape
+    K, C2, R, S = w.shape
+    assert Cc == C2 and (v is None or tuple(v.shape) == tuple(w.shape))
+    assert tuple(dy.shape) == (N, K, out_dim(H, R, stride, pad), out_dim(W, S, stride, pad))
+    ctx.reserve_for(OP_CONV_BWD_WEIGHT, N, Cc, H, W, K, R, S, stride, pad)
+    st = lib().cnn_conv_bwd_weight_sgd(ctx.handle, N, Cc, H, W, K, R, S, stride, pad, _t(x), _t(dy), _t(w),
+                                       _t(v) if v is not None else None, lr, momentum)
+    if st == EUNSUPPORTED:
+        return None
+    _check(st, ctx.handle)
+    return w
+
+
+def cnn_fc_bwd_sgd(ctx, x, w, dy, v=None, need_dx=True, dx_out=None, lr=0.01, momentum=0.0):
+    """dx from the old w (when asked for), then the weight gradient applied to w (and v) in place; returns None
+    (nothing launched) when the library does not serve the shape this way, else (dx, w)."""
+    N, O = dy.shape
+    I = w.shape[1]
+    assert tuple(x.shape) == (N, I) and w.shape[0] == O and (v is None or tuple(v.shape) == tuple(w.shape))
+    ctx.reserve_for(OP_FC_BWD, N, I, 1, 1, O, 1, 1, 1, 0)
+    dx = None
+    if need_dx:
+        dx = dx_out if dx_out is not None else torch.empty((N, I), dtype=torch.float32, device=dy.device)
+    st = lib().cnn_fc_bwd_sgd(ctx.handle, N, I, O, _t(x), _t(w), _t(dy), _t(dx) if dx is not None else None,
+                              _t(v) if v is not None else None, lr, momentum)
+    if st == EUNSUPPORTED:
+        return None
+    _check(st, ctx.handle)
+    return dx, w
 
 
 # ---------------------------------------------------------------- layouts (Section 2.3)

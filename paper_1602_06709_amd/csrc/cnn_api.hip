@@ -220,12 +220,28 @@ int cnn_conv_bwd_weight(cnn_ctx* ctx, int N, int C, int H, int W, int K, int R, 
     int st = make_shape(N, C, H, W, K, R, S, stride, pad, &s);
     if (st != CNN_OK) return st;
     if (!ctx->force_direct) {
-        st = cnn::mfma_conv_bwd_weight(ctx, s, x, dy, dw);
+        st = cnn::mfma_conv_bwd_weight(ctx, s, x, dy, sink_dw(dw));
         if (st != CNN_EUNSUPPORTED) return st;
-        st = cnn::smallc_conv_bwd_weight(ctx, s, x, dy, dw);
+        st = cnn::smallc_conv_bwd_weight(ctx, s, x, dy, sink_dw(dw));
         if (st != CNN_EUNSUPPORTED) return st;
     }
     return cnn::direct_conv_bwd_weight(ctx, s, x, dy, dw);
+}
+
+// The second stage of the weight gradient (the sum over the minibatch splits, Section 3.1) hands each finished
+// element to the SGD step of Section 3.4 instead of storing it.
+int cnn_conv_bwd_weight_sgd(cnn_ctx* ctx, int N, int C, int H, int W, int K, int R, int S, int stride, int pad,
+                            const float* x, const float* dy, float* w, float* v, float lr, float momentum) {
+    if (!ctx || !x || !dy || !w || !aligned16(x) || !aligned16(dy) || !aligned16(w) || (v && !aligned16(v)))
+        return CNN_EINVAL;
+    ConvShape s;
+    int st = make_shape(N, C, H, W, K, R, S, stride, pad, &s);
+    if (st != CNN_OK) return st;
+    if (ctx->force_direct) return CNN_EUNSUPPORTED;
+    const GradSink sink{nullptr, w, v, lr, momentum};
+    st = cnn::mfma_conv_bwd_weight(ctx, s, x, dy, sink);
+    if (st != CNN_EUNSUPPORTED) return st;
+    return cnn::smallc_conv_bwd_weight(ctx, s, x, dy, sink);
 }
 
 // Fully-connected layers: the conv loop nest with k_h = k_w = out_h = out_w = 1 (Section 2.1), i.e. GEMMs.
@@ -262,6 +278,24 @@ int cnn_fc_bwd(cnn_ctx* ctx, int N, int I, int O, const float* x, const float* w
         if (st != CNN_OK) return st;
     }
     return CNN_OK;
+}
+
+int cnn_fc_bwd_sgd(cnn_ctx* ctx, int N, int I, int O, const float* x, float* w, const float* dy, float* dx, float* v,
+                   float lr, float momentum) {
+    if (!ctx || !dy || !x || !w || !aligned16(dy) || !aligned16(x) || !aligned16(w) || (v && !aligned16(v)) ||
+        (dx && !aligned16(dx)))
+        return CNN_EINVAL;
+    ConvShape s;
+    int st = make_shape(N, I, 1, 1, O, 1, 1, 1, 0, &s);
+    if (st != CNN_OK) return st;
+    if (ctx->force_direct || !cnn::mfma_gemm_serves(O, I, N, 1, 1)) return CNN_EUNSUPPORTED;
+    if (dx) {   // backpropagation reads the weights of this iteration: before they are updated
+        st = cnn::mfma_gemm(ctx, N, I, O, dy, 0, w, 1, dx);
+        if (st == CNN_EUNSUPPORTED) st = cnn::direct_conv_bwd_data(ctx, s, dy, w, dx, nullptr);
+        if (st != CNN_OK) return st;
+    }
+    const GradSink sink{nullptr, w, v, lr, momentum};
+    return cnn::mfma_gemm(ctx, O, I, N, dy, 1, x, 1, nullptr, &sink);
 }
 
 }  // extern "C"

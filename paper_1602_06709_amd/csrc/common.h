@@ -29,6 +29,31 @@ struct ConvShape {
     int N, C, H, W, K, R, S, stride, pad, P, Q;
 };
 
+// Where the last stage of a weight gradient puts each element g (flat index i of the [K][C][R][S] / [O][I] tensor):
+// into dw[i], or, when w is set, straight into the SGD step of Section 3.4 without dw ever reaching memory:
+//   v[i] <- mu * v[i] + g (when v is set);  w[i] <- w[i] - lr * v[i]   (v == nullptr: w[i] <- w[i] - lr * g)
+// The arithmetic is the one k_sgd applies to a stored gradient, so both routes give the same bits.
+struct GradSink {
+    float* dw;
+    float* w;
+    float* v;
+    float lr, mu;
+};
+inline GradSink sink_dw(float* dw) { return GradSink{dw, nullptr, nullptr, 0.f, 0.f}; }
+
+__device__ __forceinline__ void sink_store(const GradSink& k, size_t i, float g) {
+    if (k.w) {
+        float vel = g;
+        if (k.v) {
+            vel = fmaf(k.mu, k.v[i], g);
+            k.v[i] = vel;
+        }
+        k.w[i] = fmaf(-k.lr, vel, k.w[i]);
+    } else {
+        k.dw[i] = g;
+    }
+}
+
 namespace cnn {
 
 inline int out_dim(int in, int k, int stride, int pad) {
@@ -60,7 +85,7 @@ int direct_conv_bwd_weight(cnn_ctx*, const ConvShape&, const float* x, const flo
 int mfma_conv_fwd(cnn_ctx*, const ConvShape&, const float* x, const float* w, float* y, int relu);
 int mfma_conv_bwd_data(cnn_ctx*, const ConvShape&, const float* dy, const float* w, float* dx, const float* act,
                        const unsigned char* arg = nullptr);
-int mfma_conv_bwd_weight(cnn_ctx*, const ConvShape&, const float* x, const float* dy, float* dw);
+int mfma_conv_bwd_weight(cnn_ctx*, const ConvShape&, const float* x, const float* dy, const GradSink& sink);
 size_t mfma_conv_bwd_weight_ws(const ConvShape&);
 size_t mfma_conv_bwd_data_ws(const ConvShape&);
 size_t mfma_conv_fwd_ws(const ConvShape&);
@@ -69,13 +94,16 @@ int mfma_conv_fwd_pool(cnn_ctx*, const ConvShape&, const float* x, const float* 
 // strided first layer (3 input feature maps, 11x11 / 4)
 int c3_strided_conv_fwd(cnn_ctx*, const ConvShape&, const float* x, const float* w, float* y, int relu);
 // few input feature maps (first layers), any kernel size / stride
-int smallc_conv_bwd_weight(cnn_ctx*, const ConvShape&, const float* x, const float* dy, float* dw);
+int smallc_conv_bwd_weight(cnn_ctx*, const ConvShape&, const float* x, const float* dy, const GradSink& sink);
 size_t smallc_conv_bwd_weight_ws(const ConvShape&);
 
 // C[M][Nn] = op(A) * op(B); row-major operands.
 //   a_kmajor == 0: A is [M][Kd] (contraction index contiguous);  != 0: A is [Kd][M]
 //   b_kmajor == 0: B is [Nn][Kd] (contraction index contiguous); != 0: B is [Kd][Nn]
-int mfma_gemm(cnn_ctx*, int M, int Nn, int Kd, const float* A, int a_kmajor, const float* B, int b_kmajor, float* C);
+// sink (optional): C is a weight gradient that goes into the SGD step instead of memory (C itself may then be null)
+int mfma_gemm(cnn_ctx*, int M, int Nn, int Kd, const float* A, int a_kmajor, const float* B, int b_kmajor, float* C,
+              const GradSink* sink = nullptr);
+bool mfma_gemm_serves(int M, int Nn, int Kd, int a_kmajor, int b_kmajor);
 size_t mfma_gemm_ws(int M, int Nn, int Kd);
 
 }  // namespace cnn

@@ -95,7 +95,7 @@ struct Stager {
 template <class G>
 __global__ void __launch_bounds__(G::T, 2)
 k_gemm(int M, int Nn, int Kd, int k_per_split, const float* __restrict__ A, const float* __restrict__ B,
-       float* __restrict__ Cout) {
+       GradSink sink) {
     constexpr int MT = G::MT, NT = G::NT, T = G::T;
     extern __shared__ __attribute__((aligned(16))) float lds[];      // two (A tile, B tile) buffers
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
@@ -104,7 +104,8 @@ k_gemm(int M, int Nn, int Kd, int k_per_split, const float* __restrict__ A, cons
     const int n0 = blockIdx.x * G::TN, m0 = blockIdx.y * G::TM;
     const int k_begin = blockIdx.z * k_per_split;
     const int k_end = min(k_begin + k_per_split, Kd);
-    float* out = Cout + (size_t)blockIdx.z * M * Nn;
+    // sink.dw = C, or the split's private copy [blockIdx.z][M][Nn]; sink.w is only set when there is one split
+    const size_t out0 = (size_t)blockIdx.z * M * Nn;
 
     f32x16 acc[MT][NT];
 #pragma unroll
@@ -217,6 +218,38 @@ k_gemm(int M, int Nn, int Kd, int k_per_split, const float* __restrict__ A, cons
         }
     }
 
+    if (sink.w) {
+        // SGD step on the tile's elements: all of a 32x32 block's reads are issued before its first write (the
+        // update is bound by memory latency otherwise); same arithmetic as sink_store
+#pragma unroll
+        for (int i = 0; i < MT; ++i)
+#pragma unroll
+            for (int j = 0; j < NT; ++j) {
+                const int n = n0 + (wn * NT + j) * 32 + l32;
+                if (n >= Nn) continue;
+                float wv[16], vv[16];
+#pragma unroll
+                for (int v = 0; v < 16; ++v) {
+                    const int m = m0 + (wm * MT + i) * 32 + 8 * (v / 4) + 4 * half + (v % 4);
+                    const size_t e = (size_t)(m < M ? m : M - 1) * Nn + n;
+                    wv[v] = sink.w[e];
+                    vv[v] = sink.v ? sink.v[e] : 0.f;
+                }
+#pragma unroll
+                for (int v = 0; v < 16; ++v) {
+                    const int m = m0 + (wm * MT + i) * 32 + 8 * (v / 4) + 4 * half + (v % 4);
+                    if (m >= M) continue;
+                    const size_t e = (size_t)m * Nn + n;
+                    float vel = acc[i][j][v];
+                    if (sink.v) {
+                        vel = fmaf(sink.mu, vv[v], vel);
+                        __builtin_nontemporal_store(vel, &sink.v[e]);
+                    }
+                    __builtin_nontemporal_store(fmaf(-sink.lr, vel, wv[v]), &sink.w[e]);
+                }
+            }
+        return;
+    }
 #pragma unroll
     for (int i = 0; i < MT; ++i)
 #pragma unroll
@@ -226,14 +259,14 @@ k_gemm(int M, int Nn, int Kd, int k_per_split, const float* __restrict__ A, cons
 #pragma unroll
             for (int v = 0; v < 16; ++v) {
                 const int m = m0 + (wm * MT + i) * 32 + 8 * (v / 4) + 4 * half + (v % 4);
-                if (m < M) out[(size_t)m * Nn + n] = acc[i][j][v];
+                if (m < M) sink.dw[out0 + (size_t)m * Nn + n] = acc[i][j][v];
             }
         }
 }
 
-// C[i] = sum over splits of partial[split][i], in split order (float4 lanes; MN % 4 == 0 not required).
+// C[i] (or the SGD step, sink) = sum over splits of partial[split][i], in split order.
 __global__ void __launch_bounds__(256) k_splitk_reduce(int nsplit, size_t MN, const float* __restrict__ partial,
-                                                      float* __restrict__ C) {
+                                                      GradSink sink) {
     for (size_t i = blockIdx.x * (size_t)256 + threadIdx.x; i < MN; i += (size_t)gridDim.x * 256) {
         float s0 = 0.f, s1 = 0.f;
         int s = 0;
@@ -242,7 +275,7 @@ __global__ void __launch_bounds__(256) k_splitk_reduce(int nsplit, size_t MN, co
             s1 += partial[(size_t)(s + 1) * MN + i];
         }
         if (s < nsplit) s0 += partial[(size_t)s * MN + i];
-        C[i] = s0 + s1;
+        sink_store(sink, i, s0 + s1);
     }
 }
 
@@ -272,8 +305,8 @@ GemmPlan plan_gemm(int M, int Nn, int Kd) {
 }
 
 template <class G>
-int launch(cnn_ctx* ctx, const GemmPlan& p, int M, int Nn, int Kd, const float* A, const float* B, float* C) {
-    float* dst = p.nsplit > 1 ? reinterpret_cast<float*>(ctx->ws) : C;
+int launch(cnn_ctx* ctx, const GemmPlan& p, int M, int Nn, int Kd, const float* A, const float* B, const GradSink& sink) {
+    const GradSink first = p.nsplit > 1 ? sink_dw(reinterpret_cast<float*>(ctx->ws)) : sink;
     constexpr int lds_bytes = 2 * G::BUF * (int)sizeof(float);
     static bool attr_done = false;
     if (!attr_done && lds_bytes > 48 * 1024) {
@@ -286,9 +319,11 @@ int launch(cnn_ctx* ctx, const GemmPlan& p, int M, int Nn, int Kd, const float* 
     static char name[96] = "";
     if (!name[0])
         snprintf(name, sizeof(name), "k_gemm<%dx%d %s%s>", G::TM, G::TN, G::AKM ? "At" : "A", G::BKM ? "B" : "Bt");
+    static char name_sgd[96] = "";
+    if (!name_sgd[0]) snprintf(name_sgd, sizeof(name_sgd), "%s+sgd", name);
     {
-        cnn::ProfScope ps(ctx, name, 2.0 * M * Nn * Kd);
-        hipLaunchKernelGGL(k_gemm<G>, grid, dim3(G::T), lds_bytes, ctx->stream, M, Nn, Kd, p.k_per_split, A, B, dst);
+        cnn::ProfScope ps(ctx, first.w ? name_sgd : name, 2.0 * M * Nn * Kd);
+        hipLaunchKernelGGL(k_gemm<G>, grid, dim3(G::T), lds_bytes, ctx->stream, M, Nn, Kd, p.k_per_split, A, B, first);
     }
     int st = cnn::launch_check(ctx, "gemm");
     if (st != CNN_OK || p.nsplit == 1) return st;
@@ -296,8 +331,8 @@ int launch(cnn_ctx* ctx, const GemmPlan& p, int M, int Nn, int Kd, const float* 
     size_t g = (MN + 255) / 256;
     if (g > 4096) g = 4096;
     {
-        cnn::ProfScope ps(ctx, "k_splitk_reduce", 0.0);
-        hipLaunchKernelGGL(k_splitk_reduce, dim3((unsigned)g), dim3(256), 0, ctx->stream, p.nsplit, MN, dst, C);
+        cnn::ProfScope ps(ctx, sink.w ? "k_splitk_reduce<sgd>" : "k_splitk_reduce", 0.0);
+        hipLaunchKernelGGL(k_splitk_reduce, dim3((unsigned)g), dim3(256), 0, ctx->stream, p.nsplit, MN, first.dw, sink);
     }
     return cnn::launch_check(ctx, "splitk_reduce");
 }
@@ -311,11 +346,17 @@ size_t mfma_gemm_ws(int M, int Nn, int Kd) {
     return plan_gemm(M, Nn, Kd).ws_bytes;
 }
 
-int mfma_gemm(cnn_ctx* ctx, int M, int Nn, int Kd, const float* A, int akm, const float* B, int bkm, float* C) {
+bool mfma_gemm_serves(int M, int Nn, int Kd, int akm, int bkm) {
     // float4 fetches along the contiguous index of each operand
-    if ((akm ? M : Kd) % 4 != 0 || (bkm ? Nn : Kd) % 4 != 0) return CNN_EUNSUPPORTED;
+    if ((akm ? M : Kd) % 4 != 0 || (bkm ? Nn : Kd) % 4 != 0) return false;
     // byte offsets inside the kernel are 32-bit
-    if ((size_t)M * Kd * sizeof(float) >= 0x7fffffffu || (size_t)Nn * Kd * sizeof(float) >= 0x7fffffffu) return CNN_EUNSUPPORTED;
+    return (size_t)M * Kd * sizeof(float) < 0x7fffffffu && (size_t)Nn * Kd * sizeof(float) < 0x7fffffffu;
+}
+
+int mfma_gemm(cnn_ctx* ctx, int M, int Nn, int Kd, const float* A, int akm, const float* B, int bkm, float* Cp,
+              const GradSink* sink) {
+    if (!mfma_gemm_serves(M, Nn, Kd, akm, bkm)) return CNN_EUNSUPPORTED;
+    const GradSink C = sink ? *sink : sink_dw(Cp);
     const GemmPlan p = plan_gemm(M, Nn, Kd);
     if (p.ws_bytes && (!ctx->ws || ctx->ws_bytes < p.ws_bytes)) return CNN_EWORKSPACE;
 #define GO(MT, NT, WGM, WGN)                                                                               \

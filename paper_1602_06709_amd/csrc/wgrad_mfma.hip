@@ -310,21 +310,48 @@ k_wgrad(WgGeo g, const float* __restrict__ x, const float* __restrict__ dy, floa
     }
 }
 
-// dw[(k*C + c)*RS + tap] = sum over splits of partial[split][tap][k*C + c], added in split order.
-__global__ void __launch_bounds__(256) k_wgrad_reduce(int nsplit, int RS, int KC, const float* __restrict__ partial,
-                                                     float* __restrict__ dw) {
+// element (k*C + c)*RS + tap of the gradient = sum over splits of partial[split][tap][k*C + c], added in split order;
+// the sum goes to dw or into the SGD step (sink).  One workgroup owns 64 consecutive (k, c) pairs: thread = (pair,
+// quarter of the taps) reads its taps' partials coalesced along the pairs, the sums turn through LDS, and the
+// 64*RS finished elements, contiguous in the gradient, leave (or update w, v) coalesced.
+template <int RS>
+__global__ void __launch_bounds__(256) k_wgrad_reduce(int nsplit, int KC, const float* __restrict__ partial, GradSink sink) {
+    __shared__ float turn[64 * RS];               // [64][RS]
+    constexpr int NT = (RS + 3) / 4;              // taps per thread: part, part + 4, ...
     const size_t total = (size_t)RS * KC;
-    for (size_t i = blockIdx.x * (size_t)256 + threadIdx.x; i < total; i += (size_t)gridDim.x * 256) {
-        const int tap = (int)(i / KC), kc = (int)(i % KC);
-        float s0 = 0.f, s1 = 0.f;
+    const int kcl = threadIdx.x & 63, part = threadIdx.x >> 6;
+    const int kc0 = blockIdx.x * 64, kc = kc0 + kcl;
+    if (kc < KC) {
+        // the thread's taps side by side, two splits per trip: 2 * NT independent loads in flight; per element the
+        // even splits add up in one sum and the odd ones in another, each in split order
+        float s0[NT], s1[NT];
+#pragma unroll
+        for (int t = 0; t < NT; ++t) s0[t] = s1[t] = 0.f;
+        const float* src = partial + (size_t)part * KC + kc;
         int s = 0;
         for (; s + 1 < nsplit; s += 2) {
-            s0 += partial[(size_t)s * total + i];
-            s1 += partial[(size_t)(s + 1) * total + i];
+            float a[NT], b[NT];
+#pragma unroll
+            for (int t = 0; t < NT; ++t) {
+                const bool ok = part + 4 * t < RS;
+                a[t] = ok ? src[(size_t)s * total + (size_t)4 * t * KC] : 0.f;
+                b[t] = ok ? src[(size_t)(s + 1) * total + (size_t)4 * t * KC] : 0.f;
+            }
+#pragma unroll
+            for (int t = 0; t < NT; ++t) { s0[t] += a[t]; s1[t] += b[t]; }
         }
-        if (s < nsplit) s0 += partial[(size_t)s * total + i];
-        dw[(size_t)kc * RS + tap] = s0 + s1;
+        if (s < nsplit) {
+#pragma unroll
+            for (int t = 0; t < NT; ++t)
+                if (part + 4 * t < RS) s0[t] += src[(size_t)s * total + (size_t)4 * t * KC];
+        }
+#pragma unroll
+        for (int t = 0; t < NT; ++t)
+            if (part + 4 * t < RS) turn[kcl * RS + part + 4 * t] = s0[t] + s1[t];
     }
+    __syncthreads();
+    const int live = min(64, KC - kc0) * RS;
+    for (int j = threadIdx.x; j < live; j += 256) sink_store(sink, (size_t)kc0 * RS + j, turn[j]);
 }
 
 struct Plan {
@@ -391,7 +418,7 @@ bool make_plan(const ConvShape& s, Plan* p) {
 }
 
 template <class G>
-int launch(cnn_ctx* ctx, const Plan& p, const ConvShape& s, const float* x, const float* dy, float* dw) {
+int launch(cnn_ctx* ctx, const Plan& p, const ConvShape& s, const float* x, const float* dy, const GradSink& sink) {
     if (ctx->ws_bytes < p.ws_bytes || !ctx->ws) return CNN_EWORKSPACE;
     static size_t attr_bytes = 48 * 1024;
     if (p.lds_bytes > attr_bytes) {
@@ -413,13 +440,11 @@ int launch(cnn_ctx* ctx, const Plan& p, const ConvShape& s, const float* x, cons
     }
     int st = cnn::launch_check(ctx, "wgrad");
     if (st != CNN_OK) return st;
-    const size_t total = (size_t)G::RS * s.K * s.C;
-    size_t gsz = (total + 255) / 256;
-    if (gsz > 4096) gsz = 4096;
+    const unsigned gsz = (unsigned)(((size_t)s.K * s.C + 63) / 64);
     {
-        cnn::ProfScope ps(ctx, "k_wgrad_reduce", 0.0);
-        hipLaunchKernelGGL(k_wgrad_reduce, dim3((unsigned)gsz), dim3(256), 0, ctx->stream, p.nsplit * p.g.col_tiles, G::RS,
-                           s.K * s.C, partial, dw);
+        cnn::ProfScope ps(ctx, sink.w ? "k_wgrad_reduce<sgd>" : "k_wgrad_reduce", 0.0);
+        hipLaunchKernelGGL(k_wgrad_reduce<G::RS>, dim3(gsz), dim3(256), 0, ctx->stream, p.nsplit * p.g.col_tiles,
+                           s.K * s.C, partial, sink);
     }
     return cnn::launch_check(ctx, "wgrad_reduce");
 }
@@ -445,7 +470,7 @@ size_t mfma_conv_bwd_weight_ws(const ConvShape& s) {
     return 0;
 }
 
-int mfma_conv_bwd_weight(cnn_ctx* ctx, const ConvShape& s, const float* x, const float* dy, float* dw) {
+int mfma_conv_bwd_weight(cnn_ctx* ctx, const ConvShape& s, const float* x, const float* dy, const GradSink& dw) {
     Plan p;
     if (make_plan<Wg3>(s, &p)) {
         const int tw = p.g.TW, nbi = p.g.NBI;

@@ -218,7 +218,7 @@ k_wgrad_smallc(SmallcArgs a, const float* __restrict__ x, const float* __restric
 // elements) and the splits many, so one workgroup sums 64 consecutive elements with 4 threads per element striding
 // over the splits (coalesced 256-byte reads), then adds the 4 strided sums in a fixed order.
 __global__ void __launch_bounds__(256) k_wgrad_reduce2(int nsplit, int RS, int KC, const float* __restrict__ partial,
-                                                      float* __restrict__ dw) {
+                                                      GradSink sink) {
     __shared__ float red[4][64];
     const int total = RS * KC;
     const int e = blockIdx.x * 64 + (threadIdx.x & 63), part = threadIdx.x >> 6;
@@ -236,7 +236,7 @@ __global__ void __launch_bounds__(256) k_wgrad_reduce2(int nsplit, int RS, int K
     if (part == 0 && e < total) {
         const int l = threadIdx.x & 63;
         const float t = (red[0][l] + red[1][l]) + (red[2][l] + red[3][l]);
-        dw[(size_t)(e % KC) * RS + e / KC] = t;
+        sink_store(sink, (size_t)(e % KC) * RS + e / KC, t);
     }
 }
 
@@ -297,7 +297,7 @@ SmallcPlan plan(const ConvShape& s) {
 }
 
 template <int KBK, int JB, int JW, int PW, int CC, int ST, int NPASS>
-int launch(cnn_ctx* ctx, const SmallcPlan& p, const ConvShape& s, const float* x, const float* dy, float* dw) {
+int launch(cnn_ctx* ctx, const SmallcPlan& p, const ConvShape& s, const float* x, const float* dy, const GradSink& sink) {
     auto kern = &k_wgrad_smallc<KBK, JB, JW, PW, CC, ST, NPASS>;
     static bool attr_done = false;
     if (!attr_done) {
@@ -318,9 +318,9 @@ int launch(cnn_ctx* ctx, const SmallcPlan& p, const ConvShape& s, const float* x
     if (st != CNN_OK) return st;
     const size_t total = (size_t)s.R * s.S * s.K * s.C;
     {
-        cnn::ProfScope ps(ctx, "k_wgrad_reduce2", 0.0);
+        cnn::ProfScope ps(ctx, sink.w ? "k_wgrad_reduce2<sgd>" : "k_wgrad_reduce2", 0.0);
         hipLaunchKernelGGL(k_wgrad_reduce2, dim3((unsigned)((total + 63) / 64)), dim3(256), 0, ctx->stream,
-                           p.nsplit * p.a.col_tiles, s.R * s.S, s.K * s.C, partial, dw);
+                           p.nsplit * p.a.col_tiles, s.R * s.S, s.K * s.C, partial, sink);
     }
     return cnn::launch_check(ctx, "wgrad_reduce2");
 }
@@ -334,7 +334,7 @@ size_t smallc_conv_bwd_weight_ws(const ConvShape& s) {
     return p.ok ? p.ws_bytes : 0;
 }
 
-int smallc_conv_bwd_weight(cnn_ctx* ctx, const ConvShape& s, const float* x, const float* dy, float* dw) {
+int smallc_conv_bwd_weight(cnn_ctx* ctx, const ConvShape& s, const float* x, const float* dy, const GradSink& dw) {
     const SmallcPlan p = plan(s);
     if (!p.ok) return CNN_EUNSUPPORTED;
     if (!ctx->ws || ctx->ws_bytes < p.ws_bytes) return CNN_EWORKSPACE;

@@ -1,6 +1,8 @@
 """Sequences libcnn calls into one training iteration of a layer list (paper Section 3.1 ordering:
 forward through all layers, then per layer weight gradient BEFORE backpropagation, the first layer
-skipping backpropagation, then one SGD update over the flat parameter arena).
+skipping backpropagation, then one SGD update over the flat parameter arena).  With fuse_sgd the update
+of a layer happens inside its weight gradient's reduction instead; that layer's backpropagation, which
+needs the weights of this iteration, is then issued first.
 
 This module only orders calls and owns buffers; all arithmetic happens inside libcnn kernels.
 Every call's inputs and outputs stay alive in distinct buffers and are recorded in `self.trace`
@@ -14,13 +16,16 @@ from . import synth
 
 
 class Net:
-    def __init__(self, ctx, wl: synth.Workload, weights=None, record=False, fuse=True, fuse_pool=True):
+    def __init__(self, ctx, wl: synth.Workload, weights=None, record=False, fuse=True, fuse_pool=True, fuse_sgd=True):
         """fuse=True folds every ReLU that follows a convolution into the convolution's store, and its derivative
         into the store of whatever produces the gradient in front of it (the next convolution's backpropagation or
         the max-pool backward); fuse=False calls one entry point per layer.
         fuse_pool (with fuse): a conv -> ReLU -> 2x2 max-pool chain becomes one call that stores only the pooled
-        activation and the window positions, where the library serves the shape that way."""
+        activation and the window positions, where the library serves the shape that way.
+        fuse_sgd: step() lets each layer's weight-gradient reduction apply the SGD update (no stored gradient, no
+        separate update pass), where the library serves the shape that way."""
         self.ctx, self.wl, self.record, self.fuse = ctx, wl, record, fuse
+        self.fuse_sgd = bool(fuse_sgd)
         self.fuse_pool = bool(fuse and fuse_pool)
         self.layers = list(wl.layers)
         dev = torch.device("cuda")
@@ -38,6 +43,8 @@ class Net:
         self.v_arena = torch.zeros(total, dtype=torch.float32, device=dev) if wl.momentum != 0.0 else None
         self.w = [self.w_arena[o:o + n].view(s) for o, n, s in zip(offs, sizes, wshapes)]
         self.dw = [self.dw_arena[o:o + n].view(s) for o, n, s in zip(offs, sizes, wshapes)]
+        self.v = ([self.v_arena[o:o + n].view(s) for o, n, s in zip(offs, sizes, wshapes)] if self.v_arena is not None
+                  else [None] * len(sizes))
         if weights is not None:
             for dst, src in zip(self.w, weights):
                 dst.copy_(torch.from_numpy(np.ascontiguousarray(src)))
@@ -138,8 +145,26 @@ class Net:
         self._rec("softmax_xent", len(self.layers) - 1, z, self.labels, self.loss_per_sample, self.gact[-1])
         return self.loss_per_sample
 
-    def backward(self):
-        """Expects gact[-1] to hold the gradient of the last activation (from loss() or set_upstream())."""
+    def _wgrad(self, i, wi, update):
+        """Weight gradient of conv layer i; with update, applied to the weights on the spot."""
+        ctx, L, xin, dy = self.ctx, self.layers[i], self._input_of(i), self.gact[i]
+        if update:
+            done = B.cnn_conv_bwd_weight_sgd(ctx, xin, dy, self.w[wi], self.v[wi], L[5], L[6], self.wl.lr, self.wl.momentum)
+            if done is not None:
+                self._rec("conv_bwd_weight_sgd", i, wi, xin, dy, self.w[wi], self.v[wi])
+                return
+        B.cnn_conv_bwd_weight(ctx, xin, dy, L[3], L[4], L[5], L[6], out=self.dw[wi])
+        self._rec("conv_bwd_weight", i, wi, xin, dy, self.dw[wi])
+        if update:
+            self._sgd_layer(wi)
+
+    def _sgd_layer(self, wi):
+        v = self.v[wi].view(-1) if self.v[wi] is not None else None
+        B.cnn_sgd_update(self.ctx, self.w[wi].view(-1), self.dw[wi].view(-1), v, self.wl.lr, self.wl.momentum)
+
+    def backward(self, update=False):
+        """Expects gact[-1] to hold the gradient of the last activation (from loss() or set_upstream()).
+        update=True also applies the SGD step, layer by layer, inside the weight gradients."""
         ctx = self.ctx
         wi = len(self.w)
         skip = set()
@@ -155,8 +180,8 @@ class Net:
             # is the input of layer i the output of a ReLU that was folded into the convolution before it?
             relu_in = (not first) and i >= 2 and self.layers[i - 1][0] == "relu" and self._fused_relu_after(i - 2)
             if kind == "conv":
-                B.cnn_conv_bwd_weight(ctx, xin, dy, L[3], L[4], L[5], L[6], out=self.dw[wi])
-                self._rec("conv_bwd_weight", i, wi, xin, dy, self.dw[wi])
+                if not update:       # the paper's order: weight gradient first
+                    self._wgrad(i, wi, False)
                 # is the input of layer i the output of ReLU -> pool behind a convolution (all folded in the forward pass)?
                 pool_in = (self.fuse_pool and i >= 3 and self.layers[i - 1][0] == "pool" and self.layers[i - 2][0] == "relu"
                            and self._fused_relu_after(i - 3))
@@ -176,10 +201,21 @@ class Net:
                     else:
                         B.cnn_conv_bwd_data(ctx, dy, self.w[wi], xin.shape[2], xin.shape[3], L[5], L[6], out=dxb)
                         self._rec("conv_bwd_data", i, wi, dy, self.w[wi], dxb)
+                if update:           # backpropagation has read this iteration's weights: they may change now
+                    self._wgrad(i, wi, True)
             elif kind == "fc":
-                B.cnn_fc_bwd(ctx, xin, self.w[wi], dy, need_dx=not first, need_dw=True,
-                             dx_out=None if first else dxb.view(xin.shape), dw_out=self.dw[wi])
-                self._rec("fc_bwd", i, wi, xin, self.w[wi], dy, None if first else dxb.view(xin.shape), self.dw[wi])
+                dx_out = None if first else dxb.view(xin.shape)
+                done = None
+                if update:
+                    done = B.cnn_fc_bwd_sgd(ctx, xin, self.w[wi], dy, self.v[wi], need_dx=not first, dx_out=dx_out,
+                                            lr=self.wl.lr, momentum=self.wl.momentum)
+                if done is not None:
+                    self._rec("fc_bwd_sgd", i, wi, xin, self.w[wi], dy, dx_out, self.v[wi])
+                else:
+                    B.cnn_fc_bwd(ctx, xin, self.w[wi], dy, need_dx=not first, need_dw=True, dx_out=dx_out, dw_out=self.dw[wi])
+                    self._rec("fc_bwd", i, wi, xin, self.w[wi], dy, dx_out, self.dw[wi])
+                    if update:
+                        self._sgd_layer(wi)
             elif kind == "relu":
                 # with the forward ReLU folded into the convolution only its output exists; a > 0 <=> z > 0
                 mask = self.act[i] if (i >= 1 and self._fused_relu_after(i - 1)) else xin
@@ -216,6 +252,9 @@ class Net:
         self.forward()
         if self.wl.loss:
             self.loss()
-        self.backward()
-        if self.wl.sgd:
-            self.sgd()
+        if self.wl.sgd and self.fuse_sgd:
+            self.backward(update=True)
+        else:
+            self.backward()
+            if self.wl.sgd:
+                self.sgd()

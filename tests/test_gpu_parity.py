@@ -3,6 +3,7 @@
 Bar: bit-exact for permutations, ReLU and max-pool; for contractions rel-L2 <= 1e-5 and
 |diff| <= 1e-4 * sum|a*b| per element.  All calls go through the C ABI (ctypes binding).
 """
+import dataclasses
 import sys
 
 import numpy as np
@@ -160,6 +161,91 @@ def test_sgd_update(cnn, ctx, n):
     P.check_elementwise("w0", P.np_(w2), wo, atol_scale=np.abs(w) + 0.01 * np.abs(g))
 
 
+def _check_fused_update(name, w0, v0, g_ref, sabs, w_got, v_got, lr, mu):
+    """w_got / v_got against the oracle's SGD step on the oracle's gradient: the gradient's contraction bound,
+    carried through the update, plus a few ulp of the update's own operands."""
+    wo, vo = oracle.sgd_update(w0, g_ref, v0, lr, mu)
+    sabs = np.asarray(sabs, np.float64).ravel()
+    ulp = 4 * 2.0 ** -23
+    vel = vo if vo is not None else np.asarray(g_ref, np.float64).ravel()
+    if vo is not None:
+        dv = np.abs(P.np_(v_got).astype(np.float64).ravel() - vo)
+        assert np.all(dv <= P.PER_ELEM * sabs + ulp * (mu * np.abs(v0.ravel()) + np.abs(vel))), name + ": v"
+        assert np.linalg.norm(P.np_(v_got).astype(np.float64).ravel() - vo) <= P.REL_L2 * np.linalg.norm(vo), name + ": v rel-L2"
+    dw_ = np.abs(P.np_(w_got).astype(np.float64).ravel() - wo)
+    assert np.all(dw_ <= lr * P.PER_ELEM * sabs + ulp * (np.abs(w0.ravel()) + lr * np.abs(vel))), name + ": w"
+    # the step actually taken, w0 - w, against lr * velocity (not drowned by |w|)
+    step_got = w0.astype(np.float64).ravel() - P.np_(w_got).astype(np.float64).ravel()
+    step_ref = w0.astype(np.float64).ravel() - wo
+    slack = 2.0 ** -23 * np.linalg.norm(w0)      # rounding of w itself
+    assert np.linalg.norm(step_got - step_ref) <= P.REL_L2 * np.linalg.norm(step_ref) + slack, name + ": step rel-L2"
+
+
+# (N, C, H, K, R, stride, pad): whole-tile and ragged 3x3, 5x5, the two first-layer kernels, one split / many splits
+WSGD_CASES = [(4, 64, 28, 128, 3, 1, 1), (3, 16, 28, 72, 3, 1, 1), (2, 32, 12, 64, 5, 1, 2), (2, 3, 32, 64, 3, 1, 1),
+              (2, 3, 63, 96, 11, 4, 0), (8, 128, 14, 256, 3, 1, 1), (1, 64, 56, 128, 3, 1, 1)]
+
+
+@pytest.mark.parametrize("case", WSGD_CASES)
+def test_conv_weight_gradient_with_the_sgd_step_folded_in(cnn, ctx, case):
+    N, C, H, K, R, stride, pad = case
+    say("wgrad+sgd case", case)
+    P_ = (H + 2 * pad - R) // stride + 1
+    x = synth.randn(95, 1, (N, C, H, H)); dy = synth.randn(95, 2, (N, K, P_, P_))
+    w0 = synth.randn(95, 3, (K, C, R, R), 0.05); v0 = synth.randn(95, 4, (K, C, R, R), 0.5)
+    g_ref, sabs = oracle.conv_bwd_weight(x, dy, R, R, stride, pad, with_abs=True)
+    dw = cnn.cnn_conv_bwd_weight(ctx, dev(x), dev(dy), R, R, stride, pad)
+    for lr, mu, use_v in [(0.01, 0.9, True), (0.05, 0.0, False)]:
+        w, v = dev(w0), (dev(v0) if use_v else None)
+        assert cnn.cnn_conv_bwd_weight_sgd(ctx, dev(x), dev(dy), w, v, stride, pad, lr, mu) is not None
+        w2, v2 = dev(w0), (dev(v0) if use_v else None)
+        cnn.cnn_sgd_update(ctx, w2.view(-1), dw.view(-1), v2.view(-1) if use_v else None, lr, mu)
+        torch.cuda.synchronize()
+        assert torch.equal(w, w2), "folded update differs from gradient + cnn_sgd_update"
+        if use_v:
+            assert torch.equal(v, v2)
+        _check_fused_update(f"wsgd{case}", w0, v0 if use_v else None, g_ref, sabs, w, v, lr, mu)
+
+
+def test_folded_sgd_refuses_what_only_the_plain_kernels_serve(cnn, ctx):
+    x = dev(synth.randn(95, 5, (2, 5, 9, 9))); dy = dev(synth.randn(95, 6, (2, 7, 9, 9)))
+    w0 = synth.randn(95, 7, (7, 5, 3, 3)); w = dev(w0)
+    assert cnn.cnn_conv_bwd_weight_sgd(ctx, x, dy, w, None, 1, 1, 0.1, 0.0) is None
+    xf = dev(synth.randn(95, 8, (5, 6))); dyf = dev(synth.randn(95, 9, (5, 10)))     # I % 4 != 0
+    wf0 = synth.randn(95, 10, (10, 6)); wf = dev(wf0)
+    dxf = torch.full((5, 6), 7.0, device="cuda")
+    assert cnn.cnn_fc_bwd_sgd(ctx, xf, wf, dyf, None, True, dxf, 0.1, 0.0) is None
+    torch.cuda.synchronize()
+    assert np.array_equal(P.np_(w), w0) and np.array_equal(P.np_(wf), wf0) and bool((dxf == 7.0).all())
+
+
+@pytest.mark.parametrize("case", FC_CASES + [(64, 25088, 512)])
+def test_fc_backward_with_the_sgd_step_folded_in(cnn, ctx, case):
+    N, I, O = case
+    if I % 4 or O % 4:
+        pytest.skip("served by the plain kernels only (covered by the refusal test)")
+    say("fc+sgd case", case)
+    x = synth.randn(96, 1, (N, I)); w0 = synth.randn(96, 2, (O, I), 0.05); dy = synth.randn(96, 3, (N, O))
+    v0 = synth.randn(96, 4, (O, I), 0.5)
+    g_ref, sabs = oracle.fc_bwd_weight(x, dy, with_abs=True)
+    dx_u, dw = cnn.cnn_fc_bwd(ctx, dev(x), dev(w0), dev(dy))
+    for lr, mu, use_v in [(0.01, 0.9, True), (0.05, 0.0, False)]:
+        w, v = dev(w0), (dev(v0) if use_v else None)
+        r = cnn.cnn_fc_bwd_sgd(ctx, dev(x), w, dev(dy), v, True, None, lr, mu)
+        assert r is not None
+        w2, v2 = dev(w0), (dev(v0) if use_v else None)
+        cnn.cnn_sgd_update(ctx, w2.view(-1), dw.view(-1), v2.view(-1) if use_v else None, lr, mu)
+        torch.cuda.synchronize()
+        assert torch.equal(r[0], dx_u), "dx must come from the weights before the update"
+        assert torch.equal(w, w2) and (not use_v or torch.equal(v, v2))
+        _check_fused_update(f"fcsgd{case}", w0, v0 if use_v else None, g_ref, sabs, w, v, lr, mu)
+    # first layer: no dx
+    w = dev(w0)
+    r = cnn.cnn_fc_bwd_sgd(ctx, dev(x), w, dev(dy), None, False, None, 0.05, 0.0)
+    torch.cuda.synchronize()
+    assert r is not None and r[0] is None and torch.equal(w, w2)
+
+
 @pytest.mark.parametrize("sw", [4, 8, 16, 32])
 def test_blocked_layouts_bit_exact(cnn, ctx, sw):
     x = synth.randn(95, 1, (3, 19, 7, 5)); w = synth.randn(95, 2, (21, 19, 3, 3))
@@ -298,6 +384,28 @@ def test_fused_conv_relu_pool_equals_the_unfused_sequence(cnn, ctx):
     # odd output sizes are refused before anything is launched
     L = cnn.lib(); z = dev(np.zeros((1, 1, 5, 5), np.float32)); b = torch.zeros(4, dtype=torch.uint8, device="cuda")
     assert L.cnn_conv_fwd_relu_pool(ctx.handle, 1, 1, 5, 5, 1, 3, 3, 1, 1, z.data_ptr(), z.data_ptr(), z.data_ptr(), b.data_ptr()) == -1
+
+
+@pytest.mark.parametrize("cfg", [2, 5, 4, 3])
+def test_training_steps_with_folded_sgd_equal_the_separate_update(cnn, ctx, cfg):
+    # two iterations (the second one uses the first one's velocity) of each workload, once with the update inside
+    # the weight gradients and once as gradient arena + one cnn_sgd_update: same weights and velocity, bit for bit
+    from paper_1602_06709_amd.net import Net
+    wl = synth.workload(cfg, 8 if cfg in (3, 4) else None)
+    if not wl.sgd:       # workloads defined without an update take one here
+        wl = dataclasses.replace(wl, sgd=True, lr=0.01, momentum=0.9)
+    say(f"folded-sgd steps cfg{cfg} N={wl.input_shape[0]}")
+    nets = [Net(ctx, wl, synth.make_weights(wl), fuse_sgd=f) for f in (True, False)]
+    for it in range(2):
+        for net in nets:
+            net.set_input(synth.make_input(wl), synth.make_labels(wl) if wl.loss else None)
+            if not wl.loss:
+                net.set_upstream(synth.make_upstream(wl))
+            net.step()
+        torch.cuda.synchronize()
+        assert torch.equal(nets[0].w_arena, nets[1].w_arena), f"weights differ after iteration {it}"
+        if nets[0].v_arena is not None:
+            assert torch.equal(nets[0].v_arena, nets[1].v_arena), f"velocity differs after iteration {it}"
 
 
 def test_config5_dnn7_n1024_sampled(cnn, ctx):
