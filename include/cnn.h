@@ -55,7 +55,8 @@ enum {
     CNN_OP_CONV_BWD_WEIGHT = 2,
     CNN_OP_FC_FWD = 3,     /* N, I = C, O = K; H = W = R = S = 1 */
     CNN_OP_FC_BWD = 4,
-    CNN_OP_CONV_FWD_RELU_POOL = 5
+    CNN_OP_CONV_FWD_RELU_POOL = 5,
+    CNN_OP_BLOCK_SEARCH = 6  /* cnn_block_search / cnn_block_search_traversal; the dimensions are ignored */
 };
 
 /* options for cnn_set_option() */
@@ -199,6 +200,55 @@ int cnn_sigmoid_fwd(cnn_ctx* ctx, size_t n, const float* z, float* a);
 int cnn_sigmoid_bwd(cnn_ctx* ctx, size_t n, const float* a, const float* da, float* dz);
 int cnn_softmax_xent(cnn_ctx* ctx, int N, int O, const float* z, const int32_t* label,
                      float* loss_per_sample, float* dz);
+
+/* ---- Cache-blocking model (Section 2.2).  fp32 data (size_data = 4 bytes).
+ *   cnn_bf_plane: bytes per FLOP of the loop over one (image, input feature, output feature) triple with everything
+ *     read from memory: 4 * (out_w*out_h + in_w*in_h + k_w*k_h) / (2 * k_w*k_h*out_w*out_h), in_x = out_x*s + k_x - 1.
+ *   cnn_bf_layer: the ratio when the whole layer is read once.
+ *   cnn_bf_block_traversal: the ratio of an output block (images x ofm_block x rows x cols) that stays in
+ *     accumulators while all ifm input features stream past it (the section's remark that walking along the input
+ *     features precludes reading the output block): 4 * (out + ifm*(ofm_block*k_h*k_w + images*in_h*in_w)) /
+ *     (2 * out * ifm * k_h*k_w), out = images*ofm_block*rows*cols.
+ *   These three run on the host and return -1 for a non-positive argument.
+ *
+ *   cnn_block_search: the section's exhaustive search, on the GPU.  Over all blocks (b1_0 images, b1_1 output
+ *     features, b2_0 input features, b1_2 x b1_3 output pixels, b2_2 x b2_3 kernel taps), b1_1 a multiple of simd
+ *     (or ofm itself when ofm < simd), with BS = 4 * (output block + weight block + input block) < cache_bytes, the
+ *     one of least B/F = BS / CPB, CPB = 2 * b1_0*b1_1*b2_0*b1_2*b1_3*b2_2*b2_3.  Ties: the first block in loop order
+ *     (b1_0, b1_1, b2_0, b1_2, b1_3, b2_2, b2_3 ascending, leftmost slowest).
+ *   cnn_block_search_traversal: the same search for a machine that keeps the output block in accumulators
+ *     (4 * b1_0*b1_1*b1_2*b1_3 <= acc_bytes) and streams weights and inputs through a double-buffered staging memory
+ *     in chunks of b2_0 input features (2 * 4 * b2_0 * (b1_1*k_h*k_w + b1_0*in_h*in_w) <= stage_bytes, b2_0 a
+ *     multiple of chunk); minimises cnn_bf_block_traversal.  block[5], block[6] are 0.
+ *   result: DEVICE memory, 8-byte aligned, written by kernels on the context's stream (no synchronisation here).
+ *   found = 0 (block all 0, bf 0) when no block fits.  feasible = number of blocks that fit.
+ *   Workspace: cnn_workspace_bytes(CNN_OP_BLOCK_SEARCH, ...).  CNN_EUNSUPPORTED for layers so large that a block's
+ *   byte count would not fit 62 bits. */
+typedef struct cnn_block_result {
+    int32_t block[7];
+    int32_t found;
+    double bf;
+    uint64_t feasible;
+} cnn_block_result;
+double cnn_bf_plane(int out_h, int out_w, int k_h, int k_w, int stride);
+double cnn_bf_layer(int minibatch, int ifm, int ofm, int out_h, int out_w, int k_h, int k_w, int stride);
+double cnn_bf_block_traversal(int ifm, int k_h, int k_w, int stride, int images, int ofm_block, int rows, int cols);
+int cnn_block_search(cnn_ctx* ctx, int minibatch, int ifm, int ofm, int out_h, int out_w, int k_h, int k_w, int stride,
+                     int64_t cache_bytes, int simd, cnn_block_result* result);
+int cnn_block_search_traversal(cnn_ctx* ctx, int minibatch, int ifm, int ofm, int out_h, int out_w, int k_h, int k_w,
+                               int stride, int64_t acc_bytes, int64_t stage_bytes, int simd, int chunk,
+                               cnn_block_result* result);
+
+/* The tile this library's planner gives a convolution pass (op = CNN_OP_CONV_FWD, CNN_OP_CONV_FWD_RELU_POOL or
+ * CNN_OP_CONV_BWD_DATA), and its cnn_bf_block_traversal ratio, for comparison with what the search finds for the
+ * machine's limits.  Host only.  tile[0] output features per workgroup (for backpropagation: input features, the
+ * pass's outputs), [1] output rows per tile (rows of the whole minibatch numbered through), [2] output columns,
+ * [3] contraction features per staged chunk, [4] contraction slices of the tail workgroups (1 = none), [5] LDS
+ * bytes per workgroup, [6] workgroups, [7] accumulator capacity in pixels.  For the ratio a tile of whole images
+ * counts as [1] / out_h images of out_h rows, any other as one image of [1] rows.  CNN_EUNSUPPORTED where the tiled
+ * matrix-core kernel does not serve the shape. */
+int cnn_conv_tile_info(int op, int N, int C, int H, int W, int K, int R, int S, int stride, int pad, int32_t* tile,
+                       double* bf);
 
 #ifdef __cplusplus
 }

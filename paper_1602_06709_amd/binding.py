@@ -46,6 +46,12 @@ SIGNATURES = {
     "cnn_sgd_update": (_i, [_vp, _sz, _vp, _vp, _vp, _f, _f]),
     "cnn_conv_bwd_weight_sgd": (_i, [_vp] + [_i] * 9 + [_vp] * 4 + [_f, _f]),
     "cnn_fc_bwd_sgd": (_i, [_vp, _i, _i, _i, _vp, _vp, _vp, _vp, _vp, _f, _f]),
+    "cnn_bf_plane": (C.c_double, [_i] * 5),
+    "cnn_bf_layer": (C.c_double, [_i] * 8),
+    "cnn_bf_block_traversal": (C.c_double, [_i] * 8),
+    "cnn_block_search": (_i, [_vp] + [_i] * 8 + [C.c_int64, _i, _vp]),
+    "cnn_block_search_traversal": (_i, [_vp] + [_i] * 8 + [C.c_int64, C.c_int64, _i, _i, _vp]),
+    "cnn_conv_tile_info": (_i, [_i] * 10 + [_vp, C.POINTER(C.c_double)]),
     "cnn_packed_act_elems": (_sz, [_i] * 5),
     "cnn_packed_wt_elems": (_sz, [_i] * 6),
     "cnn_pack_act": (_i, [_vp] + [_i] * 5 + [_vp] * 2),
@@ -311,6 +317,49 @@ def cnn_fc_bwd_sgd(ctx, x, w, dy, v=None, need_dx=True, dx_out=None, lr=0.01, mo
         return None
     _check(st, ctx.handle)
     return dx, w
+
+
+# ---------------------------------------------------------------- cache-blocking model (Section 2.2)
+OP_BLOCK_SEARCH = 6
+
+
+def _block_result(buf, n):
+    """(block tuple or None, B/F, feasible count) from the 48-byte cnn_block_result in `buf` (a uint8 tensor)."""
+    import numpy as np
+    raw = buf.cpu().numpy().tobytes()
+    blk = np.frombuffer(raw, np.int32, 8, 0)
+    bf = float(np.frombuffer(raw, np.float64, 1, 32)[0])
+    feasible = int(np.frombuffer(raw, np.uint64, 1, 40)[0])
+    return (tuple(int(v) for v in blk[:n]) if blk[7] else None), bf, feasible
+
+
+def cnn_block_search(ctx, layer, cache_bytes, simd):
+    """layer = (minibatch, ifm, ofm, out_h, out_w, k_h, k_w, stride).  Returns (block[7] or None, B/F, feasible)."""
+    ctx.reserve_for(OP_BLOCK_SEARCH, 1, 1, 1, 1, 1, 1, 1, 1, 0)
+    res = torch.zeros(48, dtype=torch.uint8, device="cuda")
+    _check(lib().cnn_block_search(ctx.handle, *[int(v) for v in layer], int(cache_bytes), int(simd), res.data_ptr()),
+           ctx.handle)
+    return _block_result(res, 7)
+
+
+def cnn_block_search_traversal(ctx, layer, acc_bytes, stage_bytes, simd, chunk):
+    """Returns (block[5] = (images, ofm block, ifm chunk, rows, cols) or None, B/F, feasible)."""
+    ctx.reserve_for(OP_BLOCK_SEARCH, 1, 1, 1, 1, 1, 1, 1, 1, 0)
+    res = torch.zeros(48, dtype=torch.uint8, device="cuda")
+    _check(lib().cnn_block_search_traversal(ctx.handle, *[int(v) for v in layer], int(acc_bytes), int(stage_bytes),
+                                            int(simd), int(chunk), res.data_ptr()), ctx.handle)
+    return _block_result(res, 5)
+
+
+def cnn_conv_tile_info(op, N, Cc, H, W, K, R, S, stride, pad):
+    """(tile[8], B/F) of the planner's tile for a convolution pass, or None where the tiled kernel does not serve."""
+    tile = (C.c_int32 * 8)()
+    bf = C.c_double(0.0)
+    st = lib().cnn_conv_tile_info(op, N, Cc, H, W, K, R, S, stride, pad, C.cast(tile, C.c_void_p), C.byref(bf))
+    if st == EUNSUPPORTED:
+        return None
+    _check(st, None)
+    return list(tile), bf.value
 
 
 # ---------------------------------------------------------------- layouts (Section 2.3)

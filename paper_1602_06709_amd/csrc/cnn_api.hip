@@ -126,6 +126,7 @@ int cnn_profile_reset(cnn_ctx* ctx) {
 }
 
 size_t cnn_workspace_bytes(int op, int N, int C, int H, int W, int K, int R, int S, int stride, int pad) {
+    if (op == CNN_OP_BLOCK_SEARCH) return cnn::block_search_ws();
     ConvShape s;
     if (make_shape(N, C, H, W, K, R, S, stride, pad, &s) != CNN_OK) return 0;
     switch (op) {
@@ -242,6 +243,25 @@ int cnn_conv_bwd_weight_sgd(cnn_ctx* ctx, int N, int C, int H, int W, int K, int
     st = cnn::mfma_conv_bwd_weight(ctx, s, x, dy, sink);
     if (st != CNN_EUNSUPPORTED) return st;
     return cnn::smallc_conv_bwd_weight(ctx, s, x, dy, sink);
+}
+
+int cnn_conv_tile_info(int op, int N, int C, int H, int W, int K, int R, int S, int stride, int pad, int32_t* tile,
+                       double* bf) {
+    if (!tile || !bf) return CNN_EINVAL;
+    ConvShape s;
+    int st = make_shape(N, C, H, W, K, R, S, stride, pad, &s);
+    if (st != CNN_OK) return st;
+    if (op != CNN_OP_CONV_FWD && op != CNN_OP_CONV_FWD_RELU_POOL && op != CNN_OP_CONV_BWD_DATA) return CNN_EINVAL;
+    if (!cnn::mfma_conv_tile_info(s, op, tile)) return CNN_EUNSUPPORTED;
+    // backpropagation is the same kernel with the roles of the feature maps swapped and stride 1
+    const int ifm = op == CNN_OP_CONV_BWD_DATA ? K : C;
+    const int out_rows = op == CNN_OP_CONV_BWD_DATA ? H : s.P;
+    // a tile of whole images counts as that many images (each with its own halo rows); one that ends inside an
+    // image is counted like a single taller image
+    const int images = tile[1] % out_rows == 0 ? tile[1] / out_rows : 1;
+    *bf = cnn_bf_block_traversal(ifm, R, S, op == CNN_OP_CONV_BWD_DATA ? 1 : stride, images, tile[0], tile[1] / images,
+                                 tile[2]);
+    return CNN_OK;
 }
 
 // Fully-connected layers: the conv loop nest with k_h = k_w = out_h = out_w = 1 (Section 2.1), i.e. GEMMs.

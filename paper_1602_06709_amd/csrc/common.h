@@ -91,6 +91,8 @@ size_t mfma_conv_bwd_data_ws(const ConvShape&);
 size_t mfma_conv_fwd_ws(const ConvShape&);
 size_t mfma_conv_fwd_pool_ws(const ConvShape&);
 int mfma_conv_fwd_pool(cnn_ctx*, const ConvShape&, const float* x, const float* w, float* a, unsigned char* arg);
+bool mfma_conv_tile_info(const ConvShape&, int op, int32_t tile[8]);
+size_t block_search_ws();
 // strided first layer (3 input feature maps, 11x11 / 4)
 int c3_strided_conv_fwd(cnn_ctx*, const ConvShape&, const float* x, const float* w, float* y, int relu);
 // few input feature maps (first layers), any kernel size / stride

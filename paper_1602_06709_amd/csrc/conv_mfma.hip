@@ -806,6 +806,25 @@ static bool bwd_plan(const ConvShape& s, ConvPlan* p) {
     return p->g.HO == s.H && p->g.WO == s.W;
 }
 
+// The planner's tile for one pass, for reporting (see cnn_conv_tile_info).
+bool mfma_conv_tile_info(const ConvShape& s, int op, int32_t tile[8]) {
+    ConvPlan p;
+    bool ok = false;
+    if (op == CNN_OP_CONV_FWD) ok = make_plan(s.R, s.S, s.pad, s.stride, s.N, s.C, s.K, s.H, s.W, &p);
+    else if (op == CNN_OP_CONV_FWD_RELU_POOL) ok = make_plan(s.R, s.S, s.pad, s.stride, s.N, s.C, s.K, s.H, s.W, &p, true);
+    else if (op == CNN_OP_CONV_BWD_DATA) ok = bwd_plan(s, &p);
+    if (!ok) return false;
+    tile[0] = p.v->mb;
+    tile[1] = p.g.TR;
+    tile[2] = p.g.WO;
+    tile[3] = p.v->CB;
+    tile[4] = p.g.nsl > 0 ? p.g.nsl : 1;
+    tile[5] = (int32_t)p.lds_bytes;
+    tile[6] = p.g.ptiles * p.g.mtiles;
+    tile[7] = p.v->wn * p.v->nt * 32;
+    return true;
+}
+
 static size_t wt_bytes(const ConvShape& s) {   // mirrored transpose of the weights, rounded up to 256 bytes
     return ((size_t)s.K * s.C * s.R * s.S * sizeof(float) + 255) / 256 * 256;
 }

@@ -123,3 +123,52 @@ def test_missing_library_is_an_error(monkeypatch, tmp_path):
     monkeypatch.setattr(binding._build, "LIB", str(tmp_path / "nope.so"))
     with pytest.raises(binding.CnnError):
         binding.lib()
+
+
+def test_blocking_model_host_functions_match_the_oracle(L):
+    from oracle import blocking as OB
+    for (n, c, k, p, q, r, s_, st) in [(6, 512, 1024, 12, 12, 3, 3, 1), (2, 3, 96, 56, 56, 11, 11, 4), (5, 7, 9, 4, 6, 2, 3, 2)]:
+        assert L.cnn_bf_plane(p, q, r, s_, st) == pytest.approx(OB.bf_plane(p, q, r, s_, st), rel=1e-14)
+        assert L.cnn_bf_layer(n, c, k, p, q, r, s_, st) == pytest.approx(OB.bf_layer(n, c, k, p, q, r, s_, st), rel=1e-14)
+        for blk in [(1, 8, 4, 2, 3), (n, k, c, p, q), (2, 16, 4, 1, q)]:
+            want = OB.trav_bytes(blk, c, r, s_, st) / OB.trav_flops(blk, c, r, s_)
+            assert L.cnn_bf_block_traversal(c, r, s_, st, blk[0], blk[1], blk[3], blk[4]) == pytest.approx(want, rel=1e-14)
+    assert L.cnn_bf_plane(0, 3, 3, 3, 1) == -1.0 and L.cnn_bf_layer(1, 1, 1, 1, 1, 1, 1, 0) == -1.0
+    assert round(L.cnn_bf_plane(12, 12, 3, 3, 1), 2) == 0.54 and round(L.cnn_bf_layer(6, 512, 1024, 12, 12, 3, 3, 1), 3) == 0.003
+
+
+def test_tile_report_and_block_search_validation(L):
+    from oracle import blocking as OB
+    tile = (C.c_int32 * 8)()
+    bf = C.c_double()
+    tp = C.cast(tile, C.c_void_p)
+    # VGG-A 128 -> 256 features at 56x56, minibatch 64: 128-feature tiles of whole output rows
+    assert L.cnn_conv_tile_info(0, 64, 128, 56, 56, 256, 3, 3, 1, 1, tp, C.byref(bf)) == 0
+    t = list(tile)
+    assert t[0] == 128 and t[2] == 56 and t[3] == 4 and t[1] * t[2] <= t[7] and 0 < t[5] <= 160 * 1024
+    assert t[6] == 2 * -(-64 * 56 // t[1])
+    want = OB.trav_bytes((1, t[0], t[3], t[1], t[2]), 128, 3, 3) / OB.trav_flops((1, t[0], t[3], t[1], t[2]), 128, 3, 3)
+    assert bf.value == pytest.approx(want, rel=1e-14)
+    # the tile's ratio lies between the whole layer's and the unblocked loop's, and below the chip's own
+    # 8 TB/s / 157.3 TFLOP/s = 0.051 bytes per FLOP
+    assert OB.bf_layer(64, 128, 256, 56, 56, 3, 3) < bf.value < 0.051 < OB.bf_plane(56, 56, 3, 3)
+    # backpropagation: the pass's outputs are the layer's input features
+    assert L.cnn_conv_tile_info(1, 64, 64, 112, 112, 128, 3, 3, 1, 1, tp, C.byref(bf)) == 0 and tile[0] == 64
+    assert L.cnn_conv_tile_info(0, 2, 5, 9, 9, 7, 7, 7, 2, 0, tp, C.byref(bf)) == -2      # no tiled kernel for 7x7 / 2
+    assert L.cnn_conv_tile_info(2, 64, 128, 56, 56, 256, 3, 3, 1, 1, tp, C.byref(bf)) == -1
+    assert L.cnn_conv_tile_info(0, 64, 128, 56, 56, 256, 3, 3, 1, 1, None, C.byref(bf)) == -1
+    h = C.c_void_p()
+    assert L.cnn_create(C.byref(h), None) == 0
+    try:
+        res = (C.c_double * 6)()
+        rp = C.cast(res, C.c_void_p)
+        assert L.cnn_block_search(h, 1, 8, 8, 4, 4, 3, 3, 1, 4096, 8, None) == -1
+        assert L.cnn_block_search(h, 0, 8, 8, 4, 4, 3, 3, 1, 4096, 8, rp) == -1
+        assert L.cnn_block_search(h, 1, 8, 8, 4, 4, 3, 3, 1, 0, 8, rp) == -1
+        assert L.cnn_block_search(h, 1, 8, 8, 4, 4, 3, 3, 1, 4096, 0, rp) == -1
+        assert L.cnn_block_search_traversal(h, 1, 8, 8, 4, 4, 3, 3, 1, 4096, 4096, 8, 0, rp) == -1
+        assert L.cnn_block_search(h, 1, 8, 8, 4, 4, 3, 3, 1, 4096, 8, rp) == -3                # no workspace attached
+        assert L.cnn_block_search(h, 1 << 20, 1 << 20, 1 << 20, 1 << 10, 1 << 10, 3, 3, 1, 4096, 8, rp) == -2
+        assert L.cnn_workspace_bytes(6, 0, 0, 0, 0, 0, 0, 0, 0, 0) > 0
+    finally:
+        assert L.cnn_destroy(h) == 0
