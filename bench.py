@@ -89,9 +89,11 @@ def main():
     torch.cuda.synchronize()
     prof_steps = [] if args.no_profile else [i for i in range(args.steps) if i % max(1, args.profile_every) == 0]
     ctx.profile_reset()
+    marks = []
     t0 = time.perf_counter()
     for i in range(args.steps):
         ctx.profile(i in prof_steps)         # a host-side flag: no GPU work, no synchronisation
+        net.marks = marks if i in prof_steps else None     # which profile entries belong to which call (host list)
         step()
     torch.cuda.synchronize()
     dt = time.perf_counter() - t0
@@ -123,10 +125,31 @@ def main():
 
     # ---- per-kernel table from the library's own events
     kern = {}
+    layers_out = []
     if not args.no_profile:
-        for name, fl, ms in ctx.profile_entries():
+        entries = ctx.profile_entries()
+        for name, fl, ms in entries:
             k = kern.setdefault(name, [0, 0.0, 0.0])
             k[0] += 1; k[1] += fl; k[2] += ms
+        # per layer and pass: every kernel a call launched (second-stage reductions, weight transposes included)
+        per_call, lo = {}, 0
+        for op, layer, hi in marks:
+            c = per_call.setdefault((layer, op), [0.0, 0.0])
+            for name, fl, ms in entries[lo:hi]:
+                c[0] += fl; c[1] += ms
+            lo = hi
+        for (layer, op), (fl, ms) in sorted(per_call.items(), key=lambda kv: (kv[0][0] < 0, kv[0])):
+            ms_step = ms / len(prof_steps)
+            desc = "-" if layer < 0 else " ".join(str(t) for t in wl.layers[layer])
+            tf = fl / (ms * 1e-3) / 1e12 if fl and ms > 0 else None
+            layers_out.append({"layer": layer, "desc": desc, "call": op, "ms": ms_step, "tflops": tf,
+                               "frac_fp32_mfma_peak": tf / PEAK_FP32_MFMA_TFLOPS if tf else None})
+        if args.per_kernel:
+            for r in layers_out:
+                print("layer %3d %-26s %-28s %8.4f ms  %s" % (
+                    r["layer"], r["desc"], r["call"], r["ms"],
+                    ("%6.1f TF/s  %4.1f%% of fp32 MFMA peak" % (r["tflops"], 100 * r["frac_fp32_mfma_peak"])) if r["tflops"] else ""),
+                    file=sys.stderr)
     roofline = None
     kernels_out = []
     if kern:
@@ -200,6 +223,7 @@ def main():
         "profiled_steps": prof_steps,
         "cpu_baseline": cpu,
         "kernels": kernels_out,
+        "layers": layers_out,
         "context": {"paper_vgg_a_training_images_per_s": 30, "paper_hardware": "2 x 16-core Xeon E5-2698v3 (Section 5.1)"},
     }
     print(json.dumps(out))

@@ -152,6 +152,10 @@ class Context:
     def profile_reset(self):
         _check(lib().cnn_profile_reset(self._h))
 
+    def profile_count(self):
+        """Number of profile entries recorded so far (host-side counter)."""
+        return lib().cnn_profile_count(self._h)
+
     def profile_entries(self):
         """[(kernel name, algorithmic flops, milliseconds)] of every kernel launched while profiling was on."""
         out = []

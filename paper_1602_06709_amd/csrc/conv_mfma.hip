@@ -430,6 +430,9 @@ k_conv_tiled(ConvGeo g, const float* __restrict__ in, const float* __restrict__ 
         }
         return;
     }
+    // The epilogues that read a second tensor issue all 16 reads of a 32x32 block before its first store, without
+    // branches (lanes and features outside the tensor read a clamped, valid address): one trip to memory per block
+    // instead of one per element.
     if (g.epi == EPI_UNPOOL) {
         // lane = pixel (p, q) of the pooled map: its 2x2 window of the full-size gradient is written as two float2,
         // consecutive lanes writing consecutive 8-byte pairs of rows 2p and 2p+1
@@ -438,24 +441,53 @@ k_conv_tiled(ConvGeo g, const float* __restrict__ in, const float* __restrict__ 
         for (int j = 0; j < NT; ++j) {
             const int i = (wn * NT + j) * 32 + l32;
             const int orow = row0 + i / g.WO;
-            if (i >= g.NPIX || orow >= nrows) continue;
-            const int n = orow / g.HO, p = orow % g.HO, q = i % g.WO;
+            const bool ok = i < g.NPIX && orow < nrows;
+            const int n = ok ? orow / g.HO : 0, p = ok ? orow % g.HO : 0, q = ok ? i % g.WO : 0;
             const size_t o0 = ((size_t)n * M) * out_plane + (size_t)p * g.WO + q;
             const size_t f0 = ((size_t)n * M) * 4 * out_plane + (size_t)(2 * p) * (2 * g.WO) + 2 * q;
+            float act[16];
+            int pos[16];
 #pragma unroll
             for (int v = 0; v < 16; ++v) {
                 const int m = m0 + wm * 32 + 8 * (v / 4) + 4 * half + (v % 4);
-                if (m < M) {
-                    const size_t o = o0 + (size_t)m * out_plane;
-                    const float r = aux[o] > 0.f ? acc[j][v] : 0.f;
-                    const int pos = arg_out[o];
+                const size_t o = o0 + (size_t)(m < M ? m : M - 1) * out_plane;
+                act[v] = aux[o];
+                pos[v] = arg_out[o];
+            }
+#pragma unroll
+            for (int v = 0; v < 16; ++v) {
+                const int m = m0 + wm * 32 + 8 * (v / 4) + 4 * half + (v % 4);
+                if (ok && m < M) {
+                    const float r = act[v] > 0.f ? acc[j][v] : 0.f;
                     f32x2* d = reinterpret_cast<f32x2*>(out_base + f0 + (size_t)m * 4 * out_plane);
                     f32x2 top, bot;
-                    top.x = pos == 0 ? r : 0.f; top.y = pos == 1 ? r : 0.f;
-                    bot.x = pos == 2 ? r : 0.f; bot.y = pos == 3 ? r : 0.f;
+                    top.x = pos[v] == 0 ? r : 0.f; top.y = pos[v] == 1 ? r : 0.f;
+                    bot.x = pos[v] == 2 ? r : 0.f; bot.y = pos[v] == 3 ? r : 0.f;
                     d[0] = top;
                     d[g.WO] = bot;        // next row of the full-size map: 2*WO floats = WO pairs further
                 }
+            }
+        }
+        return;
+    }
+    if (g.epi == EPI_MASK) {
+        // fused ReLU derivative: the gradient passes where the forward activation was positive
+#pragma unroll
+        for (int j = 0; j < NT; ++j) {
+            const int i = (wn * NT + j) * 32 + l32;
+            const int orow = row0 + i / g.WO;
+            const bool ok = i < g.NPIX && orow < nrows;
+            const size_t o0 = ok ? ((size_t)(orow / g.HO) * M) * out_plane + (size_t)(orow % g.HO) * g.WO + i % g.WO : 0;
+            float act[16];
+#pragma unroll
+            for (int v = 0; v < 16; ++v) {
+                const int m = m0 + wm * 32 + 8 * (v / 4) + 4 * half + (v % 4);
+                act[v] = aux[o0 + (size_t)(m < M ? m : M - 1) * out_plane];
+            }
+#pragma unroll
+            for (int v = 0; v < 16; ++v) {
+                const int m = m0 + wm * 32 + 8 * (v / 4) + 4 * half + (v % 4);
+                if (ok && m < M) out_base[o0 + (size_t)m * out_plane] = act[v] > 0.f ? acc[j][v] : 0.f;
             }
         }
         return;
@@ -474,7 +506,6 @@ k_conv_tiled(ConvGeo g, const float* __restrict__ in, const float* __restrict__ 
             if (m < M) {
                 float r = acc[j][v];
                 if (g.epi == EPI_RELU) r = r > 0.f ? r : 0.f;                                      // fused ReLU
-                else if (g.epi == EPI_MASK) r = aux[o0 + (size_t)m * out_plane] > 0.f ? r : 0.f;   // fused ReLU derivative
                 o[(size_t)m * out_plane] = r;
             }
         }

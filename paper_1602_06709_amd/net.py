@@ -68,6 +68,7 @@ class Net:
         self.labels = torch.zeros(n, dtype=torch.int32, device=dev)
         self.loss_per_sample = torch.empty(n, dtype=torch.float32, device=dev)
         self.trace = []
+        self.marks = None   # a list while a caller wants (op, layer, profile-entry count after the call) per call
         self._reserve()
 
     # ------------------------------------------------------------ workspace
@@ -89,6 +90,8 @@ class Net:
     def _rec(self, *item):
         if self.record:
             self.trace.append(item)
+        if self.marks is not None:
+            self.marks.append((item[0], item[1], self.ctx.profile_count()))
 
     def _input_of(self, i):
         j = i - 1
@@ -161,6 +164,8 @@ class Net:
     def _sgd_layer(self, wi):
         v = self.v[wi].view(-1) if self.v[wi] is not None else None
         B.cnn_sgd_update(self.ctx, self.w[wi].view(-1), self.dw[wi].view(-1), v, self.wl.lr, self.wl.momentum)
+        if self.marks is not None:
+            self.marks.append(("sgd_update", -1, self.ctx.profile_count()))
 
     def backward(self, update=False):
         """Expects gact[-1] to hold the gradient of the last activation (from loss() or set_upstream()).
@@ -236,6 +241,8 @@ class Net:
 
     def sgd(self):
         B.cnn_sgd_update(self.ctx, self.w_arena, self.dw_arena, self.v_arena, self.wl.lr, self.wl.momentum)
+        if self.marks is not None:
+            self.marks.append(("sgd_update", -1, self.ctx.profile_count()))
 
     # ------------------------------------------------------------ helpers
     def set_input(self, x_np, labels_np=None):
