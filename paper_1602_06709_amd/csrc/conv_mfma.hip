@@ -652,6 +652,8 @@ const Variant kVariants[] = {
     V(3, 3, 4, 2, 2, 7, 1, 4, 1, 0, 0),
     // 5x5: 64-feature tiles, two wave columns
     V(5, 5, 4, 2, 2, 3, 4, 4, 2, 0, 0), V(5, 5, 4, 2, 2, 4, 4, 4, 2, 0, 0), V(5, 5, 4, 2, 2, 7, 4, 4, 2, 0, 0),
+    // 5x5: 32-feature tiles, four wave columns (feature counts that are odd multiples of 32: 96-feature backpropagation)
+    V(5, 5, 4, 1, 4, 5, 4, 4, 2, 0, 0),
 };
 #undef V
 
@@ -697,7 +699,8 @@ bool make_plan(int R, int S, int pad, int stride, int N, int J, int M, int HI, i
             if (THI * WLD > v.maxplane) continue;                    // the threads must cover the staged plane
             const int images = (THI + VH - 1) / VH + 1;              // images the staged rows of one tile can touch
             if ((size_t)images * J * HI * WI * sizeof(float) >= 0x7fffffffu) continue;
-            const double eff = ((double)nrows * WO) / ((double)ptiles * cap);
+            // MFMA lanes doing useful work: pixels of the tiles, and features of the feature tiles
+            const double eff = ((double)nrows * WO) / ((double)ptiles * cap) * ((double)M / ((M + v.mb - 1) / v.mb * v.mb));
             for (int padded = (stride == 1 ? 1 : 0); padded >= 0; --padded) {
                 // LDS row stride: padded so consecutive pixels stay in consecutive banks across the end of a row
                 const int WLDP = padded ? WO + 32 * ((WLD - WO + 31) / 32) : WLD;
@@ -720,7 +723,7 @@ bool make_plan(int R, int S, int pad, int stride, int N, int J, int M, int HI, i
                     // as one of its workgroups: then the smaller pixel tile wins, not the better filled one
                     const int nch = (J + v.CB - 1) / v.CB, max_nsl = nch / 8 < 1 ? 1 : (nch / 8 > 16 ? 16 : nch / 8);
                     const long units = (long)ptiles * ((M + v.mb - 1) / v.mb);
-                    if (units * max_nsl <= 256) score *= 224.0 / cap / eff;
+                    if (units * max_nsl <= 256) score *= 7.0 / v.nt / eff;     // time of one workgroup ~ pixel blocks per wave
                 }
                 if (found && score <= best + 1e-9) continue;
                 found = true;

@@ -79,6 +79,8 @@ CONV_CASES = [  # N, C, H, K, R, pad       (square images, stride 1)
     (3, 64, 12, 128, 3, 1),     # ... 12x12
     (7, 8, 7, 40, 3, 1),        # 7x7 images: one pixel tile spans several images
     (3, 128, 10, 24, 3, 1),     # long contraction, few outputs: every unit sliced
+    (3, 96, 28, 40, 5, 0),      # 5x5 with 96 input features: backpropagation in 32-feature tiles (four wave columns)
+    (2, 32, 20, 96, 5, 2),      # ... and the forward pass with 96 output features
 ]
 
 
