@@ -31,17 +31,22 @@ constexpr int KC = 32;   // contraction elements per LDS chunk
 constexpr int kOutOfRange = (int)0x80000000;   // buffer-load byte offset beyond any descriptor used here -> reads 0
 constexpr int kRsrcWord3 = 0x00020000;         // raw buffer descriptor of 32-bit elements
 
-template <int MT_, int NT_, int WGM_, int WGN_, bool AKM_, bool BKM_>
+// KS: wave groups that share a tile and split every chunk's contraction steps between them (their accumulators are
+// added through LDS at the end).  With one workgroup per compute unit it doubles the waves per SIMD, which is what
+// hides the LDS and barrier latencies when the grid is a single round.
+template <int MT_, int NT_, int WGM_, int WGN_, bool AKM_, bool BKM_, int KS_>
 struct GemmCfg {
-    static constexpr int MT = MT_, NT = NT_, WGM = WGM_, WGN = WGN_;
+    static constexpr int MT = MT_, NT = NT_, WGM = WGM_, WGN = WGN_, KS = KS_;
     static constexpr bool AKM = AKM_, BKM = BKM_;
-    static constexpr int TM = 32 * MT * WGM, TN = 32 * NT * WGN, T = 64 * WGM * WGN;
+    static constexpr int TM = 32 * MT * WGM, TN = 32 * NT * WGN, T = 64 * WGM * WGN * KS;
     static constexpr int A_LDS = AKM ? KC * TM : TM * (KC + 1);
     static constexpr int B_LDS = BKM ? KC * TN : TN * (KC + 1);
     static constexpr int BUF = (A_LDS + B_LDS + 3) / 4 * 4;          // one (A tile, B tile) buffer, 16-byte multiple
     static constexpr int A4 = TM * KC / 4, B4 = TN * KC / 4;
     static constexpr int AS = (A4 + T - 1) / T, BS = (B4 + T - 1) / T;
     static_assert(A4 % T == 0 && B4 % T == 0, "every thread stages whole float4 slots");
+    static_assert(KS == 1 || KS == 2, "one or two wave groups");
+    static_assert(KS == 1 || WGM * WGN * MT * NT * 1024 <= 2 * BUF, "the accumulator exchange fits the operand buffers");
 };
 
 // One operand tile of ROWS x KC elements: per-thread staging slots (float4 each).
@@ -93,14 +98,15 @@ struct Stager {
 };
 
 template <class G>
-__global__ void __launch_bounds__(G::T, 2)
+__global__ void __launch_bounds__(G::T, G::KS == 1 ? 2 : 1)
 k_gemm(int M, int Nn, int Kd, int k_per_split, const float* __restrict__ A, const float* __restrict__ B,
        GradSink sink) {
     constexpr int MT = G::MT, NT = G::NT, T = G::T;
     extern __shared__ __attribute__((aligned(16))) float lds[];      // two (A tile, B tile) buffers
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
     const int half = lane >> 5, l32 = lane & 31;
-    const int wm = wave % G::WGM, wn = wave / G::WGM;
+    const int kg = wave / (G::WGM * G::WGN), wt = wave % (G::WGM * G::WGN);     // wave group, wave within the tile
+    const int wm = wt % G::WGM, wn = wt / G::WGM;
     const int n0 = blockIdx.x * G::TN, m0 = blockIdx.y * G::TM;
     const int k_begin = blockIdx.z * k_per_split;
     const int k_end = min(k_begin + k_per_split, Kd);
@@ -137,10 +143,12 @@ k_gemm(int M, int Nn, int Kd, int k_per_split, const float* __restrict__ A, cons
         // LDS read pointers: element (row, k) at row*sr + k*sk; the high wave half starts KC/2 further along k
         constexpr int a_sr = G::AKM ? 1 : KC + 1, a_sk = G::AKM ? G::TM : 1;
         constexpr int b_sr = G::BKM ? 1 : KC + 1, b_sk = G::BKM ? G::TN : 1;
-        const lds_float* ap = (const lds_float*)(lds + (wm * MT * 32 + l32) * a_sr + half * (KC / 2) * a_sk);
-        const lds_float* bp = (const lds_float*)(lds + G::A_LDS + (wn * NT * 32 + l32) * b_sr + half * (KC / 2) * b_sk);
-        // operands of group g: two k-steps (kk = 2g, 2g+1) for every row / column block of the wave
-        constexpr int NG = KC / 4;
+        // operands of group g: two k-steps (kk = 2g, 2g+1) for every row / column block of the wave; wave group kg
+        // takes the chunk's groups [kg * NG, (kg + 1) * NG)
+        constexpr int NG = KC / 4 / G::KS;
+        const lds_float* ap = (const lds_float*)(lds + (wm * MT * 32 + l32) * a_sr + (half * (KC / 2) + kg * 2 * NG) * a_sk);
+        const lds_float* bp = (const lds_float*)(lds + G::A_LDS + (wn * NT * 32 + l32) * b_sr +
+                                                 (half * (KC / 2) + kg * 2 * NG) * b_sk);
         auto read_group = [&](int g, float (&a)[MT][2], float (&b)[NT][2]) {
 #pragma unroll
             for (int i = 0; i < MT; ++i)
@@ -218,6 +226,28 @@ k_gemm(int M, int Nn, int Kd, int k_per_split, const float* __restrict__ A, cons
         }
     }
 
+    if (G::KS > 1) {
+        // the second wave group hands its accumulators to the first through LDS (free now): [wave][block][v][lane]
+        __syncthreads();
+        float* ex = lds + (size_t)wt * MT * NT * 1024 + lane;
+        if (kg == 1) {
+#pragma unroll
+            for (int i = 0; i < MT; ++i)
+#pragma unroll
+                for (int j = 0; j < NT; ++j)
+#pragma unroll
+                    for (int v = 0; v < 16; ++v) ex[((i * NT + j) * 16 + v) * 64] = acc[i][j][v];
+        }
+        __syncthreads();
+        if (kg == 1) return;
+#pragma unroll
+        for (int i = 0; i < MT; ++i)
+#pragma unroll
+            for (int j = 0; j < NT; ++j)
+#pragma unroll
+                for (int v = 0; v < 16; ++v) acc[i][j][v] += ex[((i * NT + j) * 16 + v) * 64];
+    }
+
     if (sink.w) {
         // SGD step on the tile's elements: all of a 32x32 block's reads are issued before its first write (the
         // update is bound by memory latency otherwise); same arithmetic as sink_store
@@ -280,7 +310,7 @@ __global__ void __launch_bounds__(256) k_splitk_reduce(int nsplit, size_t MN, co
 }
 
 struct GemmPlan {
-    int tm, tn, nsplit, k_per_split;
+    int tm, tn, ks, nsplit, k_per_split;
     size_t ws_bytes;
 };
 
@@ -290,6 +320,12 @@ GemmPlan plan_gemm(int M, int Nn, int Kd) {
     // too few 128-row tiles to fill the chip and a short contraction: 64-row tiles (twice as many workgroups) beat
     // splitting the contraction, which needs the partial products written, read back and added
     if (p.tm == 128 && (long)((M + 127) / 128) * ((Nn + 127) / 128) < 256 && Kd <= 4096) p.tm = 64;
+    // a few rounds of 128-row tiles whose last round is mostly empty: the busiest compute unit works through
+    // ceil(tiles / 256) tiles, and 64-row tiles cut that in finer steps (584 tiles: 3 x 128 rows against 5 x 64)
+    if (p.tm == 128) {
+        const long t128 = (long)((M + 127) / 128) * ((Nn + 127) / 128), t64 = (long)((M + 63) / 64) * ((Nn + 127) / 128);
+        if (t128 > 256 && t128 <= 4 * 256 && ((t64 + 255) / 256) * 64 * 10 < ((t128 + 255) / 256) * 128 * 9) p.tm = 64;
+    }
     p.tn = 128;
     const long tiles = (long)((M + p.tm - 1) / p.tm) * ((Nn + p.tn - 1) / p.tn);
     int want = tiles >= 256 ? 1 : (int)((512 + tiles - 1) / tiles);
@@ -301,6 +337,8 @@ GemmPlan plan_gemm(int M, int Nn, int Kd) {
     p.k_per_split = cps * KC;
     p.nsplit = (Kd + p.k_per_split - 1) / p.k_per_split;
     p.ws_bytes = p.nsplit > 1 ? (size_t)p.nsplit * M * Nn * sizeof(float) : 0;
+    // a grid of at most one workgroup per compute unit: two wave groups per tile
+    p.ks = tiles * p.nsplit <= 256 ? 2 : 1;
     return p;
 }
 
@@ -318,7 +356,8 @@ int launch(cnn_ctx* ctx, const GemmPlan& p, int M, int Nn, int Kd, const float* 
     dim3 grid((unsigned)((Nn + G::TN - 1) / G::TN), (unsigned)((M + G::TM - 1) / G::TM), (unsigned)p.nsplit);
     static char name[96] = "";
     if (!name[0])
-        snprintf(name, sizeof(name), "k_gemm<%dx%d %s%s>", G::TM, G::TN, G::AKM ? "At" : "A", G::BKM ? "B" : "Bt");
+        snprintf(name, sizeof(name), "k_gemm<%dx%d %s%s%s>", G::TM, G::TN, G::AKM ? "At" : "A", G::BKM ? "B" : "Bt",
+                 G::KS == 2 ? " x2" : "");
     static char name_sgd[96] = "";
     if (!name_sgd[0]) snprintf(name_sgd, sizeof(name_sgd), "%s+sgd", name);
     {
@@ -359,15 +398,17 @@ int mfma_gemm(cnn_ctx* ctx, int M, int Nn, int Kd, const float* A, int akm, cons
     const GradSink C = sink ? *sink : sink_dw(Cp);
     const GemmPlan p = plan_gemm(M, Nn, Kd);
     if (p.ws_bytes && (!ctx->ws || ctx->ws_bytes < p.ws_bytes)) return CNN_EWORKSPACE;
-#define GO(MT, NT, WGM, WGN)                                                                               \
-    do {                                                                                                   \
-        if (!akm && !bkm) return launch<GemmCfg<MT, NT, WGM, WGN, false, false>>(ctx, p, M, Nn, Kd, A, B, C); \
-        if (!akm && bkm) return launch<GemmCfg<MT, NT, WGM, WGN, false, true>>(ctx, p, M, Nn, Kd, A, B, C);   \
-        if (akm && bkm) return launch<GemmCfg<MT, NT, WGM, WGN, true, true>>(ctx, p, M, Nn, Kd, A, B, C);     \
-        return launch<GemmCfg<MT, NT, WGM, WGN, true, false>>(ctx, p, M, Nn, Kd, A, B, C);                    \
+#define GO(MT, NT, WGM, WGN, KS)                                                                               \
+    do {                                                                                                       \
+        if (!akm && !bkm) return launch<GemmCfg<MT, NT, WGM, WGN, false, false, KS>>(ctx, p, M, Nn, Kd, A, B, C); \
+        if (!akm && bkm) return launch<GemmCfg<MT, NT, WGM, WGN, false, true, KS>>(ctx, p, M, Nn, Kd, A, B, C);   \
+        if (akm && bkm) return launch<GemmCfg<MT, NT, WGM, WGN, true, true, KS>>(ctx, p, M, Nn, Kd, A, B, C);     \
+        return launch<GemmCfg<MT, NT, WGM, WGN, true, false, KS>>(ctx, p, M, Nn, Kd, A, B, C);                    \
     } while (0)
-    if (p.tm == 64) GO(2, 1, 1, 4);
-    GO(2, 2, 2, 2);
+    if (p.tm == 64 && p.ks == 2) GO(2, 1, 1, 4, 2);
+    if (p.tm == 64) GO(2, 1, 1, 4, 1);
+    if (p.ks == 2) GO(2, 2, 2, 2, 2);
+    GO(2, 2, 2, 2, 1);
 #undef GO
 }
 
