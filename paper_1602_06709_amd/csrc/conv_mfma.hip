@@ -96,7 +96,7 @@ constexpr int kOutOfRange = (int)0x80000000;   // buffer-load byte offset beyond
 constexpr int kRsrcWord3 = 0x00020000;         // raw buffer descriptor of 32-bit elements
 
 template <class G>
-__global__ void __launch_bounds__(G::T, G::VEC == 1 ? 3 : 2)   // first layers are memory-phase bound: a third workgroup per CU helps
+__global__ void __launch_bounds__(G::T, 2)
 k_conv_tiled(ConvGeo g, const float* __restrict__ in, const float* __restrict__ wt, const float* __restrict__ aux,
              float* __restrict__ out_base, float* __restrict__ partial, unsigned char* arg_out) {
     constexpr int R = G::R, S = G::S, RS = G::RS, CB = G::CB, NT = G::NT, T = G::T, TG = G::TG;
@@ -654,6 +654,10 @@ const Variant kVariants[] = {
     V(5, 5, 4, 2, 2, 3, 4, 4, 2, 0, 0), V(5, 5, 4, 2, 2, 4, 4, 4, 2, 0, 0), V(5, 5, 4, 2, 2, 7, 4, 4, 2, 0, 0),
     // 5x5: 32-feature tiles, four wave columns (feature counts that are odd multiples of 32: 96-feature backpropagation)
     V(5, 5, 4, 1, 4, 5, 4, 4, 2, 0, 0),
+    // 7x7: 64-feature tiles, two wave columns; and with fewer than 4 contraction channels (strided first layers:
+    // up to 12 staged positions per thread and channel for the tall input tile a stride-2 pixel tile needs)
+    V(7, 7, 4, 2, 2, 3, 4, 4, 2, 0, 0), V(7, 7, 4, 2, 2, 4, 4, 4, 2, 0, 0),
+    V(7, 7, 4, 2, 2, 7, 1, 12, 1, 0, 0),
 };
 #undef V
 
@@ -681,7 +685,7 @@ bool make_plan(int R, int S, int pad, int stride, int N, int J, int M, int HI, i
     for (const Variant& v : kVariants) {
         if (v.R != R || v.S != S) continue;
         if (v.vec == 4 ? (J % v.CB != 0 || (J * R * S) % 4 != 0) : J >= 4) continue;
-        if (v.vec == 4 && R != 5 && (M <= 64 ? v.mb != 64 : v.mb != 128)) continue;
+        if (v.vec == 4 && R == 3 && (M <= 64 ? v.mb != 64 : v.mb != 128)) continue;
         const int cap = v.nt * v.wn * 32;
         if (WO > cap) continue;
         const int tr_max = (long)(cap / WO) < nrows ? cap / WO : (int)nrows;
@@ -706,7 +710,8 @@ bool make_plan(int R, int S, int pad, int stride, int N, int J, int M, int HI, i
                 const int WLDP = padded ? WO + 32 * ((WLD - WO + 31) / 32) : WLD;
                 const int PLANEP = THI * WLDP;
                 const int lds_buf = v.mb * v.wstr + v.CB * PLANEP;
-                size_t lds_bytes = (size_t)lds_buf * 2 * sizeof(float);   // two buffers
+                // two buffers; the single-chunk kernels (first layers) only ever use the first
+                size_t lds_bytes = (size_t)lds_buf * (v.vec == 1 ? 1 : 2) * sizeof(float);
                 if (pool && lds_bytes < (size_t)v.mb * (TR * WO / 2) * sizeof(float))
                     lds_bytes = (size_t)v.mb * (TR * WO / 2) * sizeof(float);   // the pooling exchange reuses them
                 if (lds_bytes > 156 * 1024) continue;

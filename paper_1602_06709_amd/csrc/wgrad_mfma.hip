@@ -453,6 +453,9 @@ int launch(cnn_ctx* ctx, const Plan& p, const ConvShape& s, const float* x, cons
 // row per wave (10 waves)
 using Wg3 = WgCfg<3, 3, 4, 2, 1, 4>;
 using Wg5 = WgCfg<5, 5, 2, 1, 5, 8>;
+// 7x7 -> 32 k x 32 c, one kernel row per wave (7 waves: 112 accumulator registers each leave no room for more
+// waves per SIMD)
+using Wg7 = WgCfg<7, 7, 1, 1, 7, 8>;
 // 3x3 with whole tiles (C % 64 == 0, K % 128 == 0) and the step geometry (TW, NBI) of VGG-A's 112 / 56-pixel,
 // 28-pixel and 14-pixel layers and of OverFeat-FAST's 12-pixel layers
 using Wg3F56 = WgCfg<3, 3, 4, 2, 1, 4, 56, 1>;
@@ -466,7 +469,7 @@ namespace cnn {
 
 size_t mfma_conv_bwd_weight_ws(const ConvShape& s) {
     Plan p;
-    if (make_plan<Wg3>(s, &p) || make_plan<Wg5>(s, &p)) return p.ws_bytes;
+    if (make_plan<Wg3>(s, &p) || make_plan<Wg5>(s, &p) || make_plan<Wg7>(s, &p)) return p.ws_bytes;
     return 0;
 }
 
@@ -483,6 +486,7 @@ int mfma_conv_bwd_weight(cnn_ctx* ctx, const ConvShape& s, const float* x, const
         return launch<Wg3>(ctx, p, s, x, dy, dw);
     }
     if (make_plan<Wg5>(s, &p)) return launch<Wg5>(ctx, p, s, x, dy, dw);
+    if (make_plan<Wg7>(s, &p)) return launch<Wg7>(ctx, p, s, x, dy, dw);
     return CNN_EUNSUPPORTED;
 }
 

@@ -242,7 +242,7 @@ __global__ void __launch_bounds__(256) k_wgrad_reduce2(int nsplit, int RS, int K
 
 struct SmallcPlan {
     SmallcArgs a;
-    int variant;          // 0: K <= 32, J <= 32; 1: K <= 64, J <= 32; 2: K <= 96, J <= 384, stride 4
+    int variant;          // 0: K <= 32, J <= 32; 1: K <= 64, J <= 32; 2: K <= 96, J <= 384, stride 4; 3: ... stride 2
     int pw, nsplit;
     size_t lds_bytes, ws_bytes;
     bool ok;
@@ -257,12 +257,13 @@ SmallcPlan plan(const ConvShape& s) {
     if (J <= 32 && s.K <= 32 && s.stride == 1) { p.variant = 0; kbk = 1; p.pw = 4; }
     else if (J <= 32 && s.K <= 64 && s.stride == 1) { p.variant = 1; kbk = 2; p.pw = 4; }
     else if (J <= 384 && s.K <= 96 && s.stride == 4) { p.variant = 2; kbk = 3; p.pw = 1; }
+    else if (J <= 384 && s.K <= 96 && s.stride == 2) { p.variant = 3; kbk = 3; p.pw = 1; }
     else return p;
     SmallcArgs& a = p.a;
     a.N = s.N; a.C = s.C; a.H = s.H; a.W = s.W; a.K = s.K; a.R = s.R; a.S = s.S; a.stride = s.stride; a.pad = s.pad;
     a.P = s.P; a.Q = s.Q;
     // column tile: largest even divisor of Q within the lanes the dy staging covers (128 for stride 1, 64 else)
-    const int tw_max = p.variant == 2 ? 64 : 112;
+    const int tw_max = p.variant >= 2 ? 64 : 112;
     int tw = 0;
     for (int t = 2; t <= s.Q && t <= tw_max; t += 2)
         if (s.Q % t == 0) tw = t;
@@ -340,7 +341,8 @@ int smallc_conv_bwd_weight(cnn_ctx* ctx, const ConvShape& s, const float* x, con
     if (!ctx->ws || ctx->ws_bytes < p.ws_bytes) return CNN_EWORKSPACE;
     if (p.variant == 0) return launch<1, 1, 1, 4, 3, 1, 2>(ctx, p, s, x, dy, dw);
     if (p.variant == 1) return launch<2, 1, 1, 4, 3, 1, 2>(ctx, p, s, x, dy, dw);
-    return launch<3, 3, 4, 1, 3, 4, 1>(ctx, p, s, x, dy, dw);
+    if (p.variant == 2) return launch<3, 3, 4, 1, 3, 4, 1>(ctx, p, s, x, dy, dw);
+    return launch<3, 3, 4, 1, 3, 2, 1>(ctx, p, s, x, dy, dw);
 }
 
 }  // namespace cnn

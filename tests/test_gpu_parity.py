@@ -81,6 +81,8 @@ CONV_CASES = [  # N, C, H, K, R, pad       (square images, stride 1)
     (3, 128, 10, 24, 3, 1),     # long contraction, few outputs: every unit sliced
     (3, 96, 28, 40, 5, 0),      # 5x5 with 96 input features: backpropagation in 32-feature tiles (four wave columns)
     (2, 32, 20, 96, 5, 2),      # ... and the forward pass with 96 output features
+    (2, 16, 20, 40, 7, 3),      # 7x7 'same'
+    (3, 32, 14, 72, 7, 0),      # 7x7, 14 -> 8
 ]
 
 
@@ -98,6 +100,22 @@ def test_conv_three_passes_tiled_geometries(cnn, ctx, case):
     P.check_contraction("y", P.np_(y), *oracle.conv_fwd(x, w, 1, pad, with_abs=True))
     P.check_contraction("dx", P.np_(dx), *oracle.conv_bwd_data(dy, w, H, H, 1, pad, with_abs=True))
     P.check_contraction("dw", P.np_(dw), *oracle.conv_bwd_weight(x, dy, R, R, 1, pad, with_abs=True))
+
+
+@pytest.mark.parametrize("case", [(2, 3, 64, 64, 7, 2, 3), (3, 3, 37, 40, 7, 2, 0), (2, 3, 224, 96, 7, 2, 3), (2, 1, 30, 24, 7, 1, 3)])
+def test_first_layer_7x7(cnn, ctx, case):
+    # few input features under a 7x7 kernel, stride 2 (and 1): single-chunk tiled forward, small-C weight gradient
+    N, C, H, K, R, stride, pad = case
+    say("7x7 first-layer case", case)
+    P_ = (H + 2 * pad - R) // stride + 1
+    x = synth.randn(91, 1, (N, C, H, H)); w = synth.randn(91, 2, (K, C, R, R), 0.1); dy = synth.randn(91, 3, (N, K, P_, P_))
+    y = cnn.cnn_conv_fwd(ctx, dev(x), dev(w), stride, pad)
+    dw = cnn.cnn_conv_bwd_weight(ctx, dev(x), dev(dy), R, R, stride, pad)
+    dx = cnn.cnn_conv_bwd_data(ctx, dev(dy), dev(w), H, H, stride, pad)
+    torch.cuda.synchronize()
+    P.check_contraction("y", P.np_(y), *oracle.conv_fwd(x, w, stride, pad, with_abs=True))
+    P.check_contraction("dw", P.np_(dw), *oracle.conv_bwd_weight(x, dy, R, R, stride, pad, with_abs=True))
+    P.check_contraction("dx", P.np_(dx), *oracle.conv_bwd_data(dy, w, H, H, stride, pad, with_abs=True))
 
 
 def test_conv_generic_shapes_fall_back_and_match(cnn, ctx):
