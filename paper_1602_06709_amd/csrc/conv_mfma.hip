@@ -64,6 +64,10 @@ struct ConvGeo {
     // remaining tail_per_xcd units are each cut into nsl slices of chunks_per_slice channel chunks, one workgroup per
     // slice, whose partial results go to a scratch buffer and are added up by k_tile_reduce.
     int full_per_xcd, tail_per_xcd, nsl, chunks_per_slice;
+    // flat != 0 (a grid within one round whose pixel tiles do not divide evenly over the 8 XCDs): workgroup
+    // blockIdx.x is slice blockIdx.x % nsl of unit blockIdx.x / nsl, units numbered (pixel tile, feature tile); the
+    // hardware's round-robin then spreads them over all XCDs instead of leaving some without work.
+    int flat;
     int epi;
     int lds_buf;                   // elements of one (filter tile, input tile) buffer
 };
@@ -115,16 +119,27 @@ k_conv_tiled(ConvGeo g, const float* __restrict__ in, const float* __restrict__ 
     // Workgroups are handed to the 8 XCDs round-robin by linear id.  Give each XCD (its own L2) a contiguous range
     // of pixel tiles and run the output-feature tiles of one pixel tile back to back on it, so the input tile, and
     // the halo rows it shares with the next tile, come from HBM once instead of once per feature tile.
-    const int xcd = blockIdx.x & 7, seq = blockIdx.x >> 3;
-    int unit = seq, slice = -1;
-    if (seq >= g.full_per_xcd) {
-        const int t = seq - g.full_per_xcd;
-        unit = g.full_per_xcd + t / g.nsl;
-        slice = t % g.nsl;
+    int ptile, m0, slice = -1;
+    size_t tix;                          // index of a sliced unit's partial tiles in the scratch buffer
+    if (g.flat) {
+        const int ul = blockIdx.x / g.nsl;
+        if (g.nsl > 1) slice = blockIdx.x % g.nsl;
+        ptile = ul / g.mtiles;
+        m0 = (ul % g.mtiles) * G::MB;
+        tix = ul;
+    } else {
+        const int xcd = blockIdx.x & 7, seq = blockIdx.x >> 3;
+        int unit = seq;
+        if (seq >= g.full_per_xcd) {
+            const int t = seq - g.full_per_xcd;
+            unit = g.full_per_xcd + t / g.nsl;
+            slice = t % g.nsl;
+        }
+        ptile = xcd * g.per_xcd + unit / g.mtiles;
+        m0 = (unit % g.mtiles) * G::MB;
+        tix = (size_t)xcd * g.tail_per_xcd + (unit - g.full_per_xcd);
     }
-    const int ptile = xcd * g.per_xcd + unit / g.mtiles;
     if (ptile >= g.ptiles) return;   // whole workgroup leaves: no barrier is left behind
-    const int m0 = (unit % g.mtiles) * G::MB;
     const int row0 = ptile * g.TR, nrows = N * g.HO;      // first output row of the tile, rows of the minibatch
     const int n0 = row0 / g.HO;                           // image the tile starts in
     const int v0 = n0 * g.VH + (row0 % g.HO) * g.stride;  // its first staged row, numbered through the extended images
@@ -358,7 +373,6 @@ k_conv_tiled(ConvGeo g, const float* __restrict__ in, const float* __restrict__ 
     if (slice >= 0) {
         // partial tile [MB][NPIXB] of tail unit (xcd, unit - full_per_xcd), slice `slice`; no guards: the scratch
         // buffer holds whole tiles and the reduction skips what lies outside the tensor
-        const size_t tix = (size_t)xcd * g.tail_per_xcd + (unit - g.full_per_xcd);
         float* po = partial + (tix * g.nsl + slice) * (size_t)(G::MB * G::NPIXB);
 #pragma unroll
         for (int j = 0; j < NT; ++j) {
@@ -536,13 +550,32 @@ __global__ void __launch_bounds__(256) k_transpose_flip(int K, int C, int RS, co
 
 // Adds up the slices of every tail unit in slice order and stores the tile with the epilogue applied.
 // grid = (tail units, MB / 8): one block owns 8 feature rows of one tile.
+// sum over the slices' partial tiles of one element, in slice order; four reads in flight at a time
+__device__ __forceinline__ float slice_sum(const float* __restrict__ p, size_t tile, int nsl) {
+    float r = 0.f;
+    int s = 0;
+    for (; s + 3 < nsl; s += 4) {
+        const float a0 = p[(size_t)s * tile], a1 = p[(size_t)(s + 1) * tile], a2 = p[(size_t)(s + 2) * tile],
+                    a3 = p[(size_t)(s + 3) * tile];
+        r = (((r + a0) + a1) + a2) + a3;
+    }
+    for (; s < nsl; ++s) r += p[(size_t)s * tile];
+    return r;
+}
+
 __global__ void __launch_bounds__(256) k_tile_reduce(ConvGeo g, int MB, int cap, const float* __restrict__ partial,
                                                     const float* __restrict__ aux, float* __restrict__ out,
                                                     unsigned char* arg_out) {
-    const int xcd = blockIdx.x / g.tail_per_xcd, unit = g.full_per_xcd + blockIdx.x % g.tail_per_xcd;
-    const int ptile = xcd * g.per_xcd + unit / g.mtiles;
+    int ptile, m0;
+    if (g.flat) {
+        ptile = blockIdx.x / g.mtiles;
+        m0 = (blockIdx.x % g.mtiles) * MB;
+    } else {
+        const int xcd = blockIdx.x / g.tail_per_xcd, unit = g.full_per_xcd + blockIdx.x % g.tail_per_xcd;
+        ptile = xcd * g.per_xcd + unit / g.mtiles;
+        m0 = (unit % g.mtiles) * MB;
+    }
     if (ptile >= g.ptiles) return;
-    const int m0 = (unit % g.mtiles) * MB;
     const int row0 = ptile * g.TR, nrows = g.N * g.HO;
     const size_t out_plane = (size_t)g.HO * g.WO, tile = (size_t)MB * cap;
     const float* pt = partial + (size_t)blockIdx.x * g.nsl * tile;
@@ -558,8 +591,7 @@ __global__ void __launch_bounds__(256) k_tile_reduce(ConvGeo g, int MB, int cap,
             int idx = 0;
             for (int w4 = 0; w4 < 4; ++w4) {
                 const int i = (2 * pr + w4 / 2) * g.WO + 2 * pq + (w4 & 1);
-                float r = 0.f;
-                for (int s = 0; s < g.nsl; ++s) r += pt[s * tile + (size_t)ml * cap + i];
+                float r = slice_sum(pt + (size_t)ml * cap + i, tile, g.nsl);
                 r = r > 0.f ? r : 0.f;
                 if (w4 == 0 || r > best) { best = r; idx = w4; }
             }
@@ -573,8 +605,7 @@ __global__ void __launch_bounds__(256) k_tile_reduce(ConvGeo g, int MB, int cap,
         const int ml = blockIdx.y * 8 + e / cap, i = e % cap;
         const int orow = row0 + i / g.WO;
         if (i >= g.NPIX || orow >= nrows || m0 + ml >= g.M) continue;
-        float r = 0.f;
-        for (int s = 0; s < g.nsl; ++s) r += pt[s * tile + (size_t)ml * cap + i];
+        float r = slice_sum(pt + (size_t)ml * cap + i, tile, g.nsl);
         if (g.epi == EPI_UNPOOL) {
             const size_t plane = (size_t)(orow / g.HO) * g.M + m0 + ml;
             const size_t o = plane * out_plane + (size_t)(orow % g.HO) * g.WO + i % g.WO;
@@ -610,7 +641,7 @@ int launch(cnn_ctx* ctx, const LaunchArgs& a) {
         if (e != hipSuccess) return cnn::hip_check(ctx, e, "hipFuncSetAttribute(conv_tiled)");
         attr_bytes = a.lds_bytes;
     }
-    dim3 grid((unsigned)(8 * (a.g.full_per_xcd + a.g.tail_per_xcd * a.g.nsl)));
+    dim3 grid((unsigned)(a.g.flat ? a.g.ptiles * a.g.mtiles * a.g.nsl : 8 * (a.g.full_per_xcd + a.g.tail_per_xcd * a.g.nsl)));
     static char name[96] = "";
     if (!name[0] && G::WLDP_CT)
         snprintf(name, sizeof(name), "k_conv_tiled<%dx%d CB%d WM%d WN%d NT%d ld%d/%d>", G::R, G::S, G::CB, G::WM, G::WN,
@@ -665,6 +696,7 @@ struct ConvPlan {
     const Variant* v;
     ConvGeo g;
     size_t lds_bytes, partial_bytes;
+    int reduce_units;                  // units whose partial tiles k_tile_reduce adds up (0: none)
 };
 
 
@@ -758,23 +790,24 @@ bool make_plan(int R, int S, int pad, int stride, int N, int J, int M, int HI, i
     const long units = 8L * upx;
     const int nchunks = (J + v.CB - 1) / v.CB;
     const double ov_job = (8.0 / 4.0e12) / (2.0 * J * R * S / (0.85 * 157.3e12));
-    const long rounds = units > 256 ? units / 256 : 0, tail = units - rounds * 256;
+    const long slots = 256;            // workgroups per round: one per compute unit
+    const long rounds = units > slots ? units / slots : 0, tail = units - rounds * slots;
     int best_tail = 0, best_nsl = 1;
     if (rounds == 0) {
         // a grid within one round: slice every unit just far enough that (almost) every compute unit gets a
         // workgroup; finer slices only add partial-tile traffic (measured at minibatch 4)
         const long live = (long)g.ptiles * g.mtiles;               // without the empty units that pad the last XCD's range
         int nsl = 1;
-        while (live * nsl < 208 && nsl < 16 && nchunks / (nsl + 1) >= 8) ++nsl;
+        while (live * nsl < slots * 13 / 16 && nsl < 16 && nchunks / (nsl + 1) >= 8) ++nsl;
         best_nsl = nsl;
         if (nsl > 1) best_tail = (int)units;
     } else if (tail > 0) {
         double best_t = 0.0;
         for (int nsl = 1; nsl <= 16; ++nsl) {
             if (nsl > 1 && nchunks / nsl < 8) break;               // at least 8 chunks per slice
-            const long k = (tail * nsl + 255) / 256;               // slices on the busiest compute unit
+            const long k = (tail * nsl + slots - 1) / slots;       // slices on the busiest compute unit
             double t = (double)rounds + (double)k / nsl;
-            if (nsl > 1) t += (double)(tail * nsl) / 256.0 * ov_job;
+            if (nsl > 1) t += (double)(tail * nsl) / (double)slots * ov_job;
             if (nsl == 1 || t < best_t * 0.98) { best_t = t; best_nsl = nsl; }
         }
         if (best_nsl > 1) best_tail = (int)tail;
@@ -787,7 +820,10 @@ bool make_plan(int R, int S, int pad, int stride, int N, int J, int M, int HI, i
     g.full_per_xcd = upx - g.tail_per_xcd;
     g.nsl = best_tail ? best_nsl : 1;
     g.chunks_per_slice = (nchunks + g.nsl - 1) / g.nsl;
-    p->partial_bytes = (size_t)best_tail * g.nsl * v.mb * (v.nt * v.wn * 32) * sizeof(float);
+    g.flat = rounds == 0 && g.ptiles % 8 != 0;
+    const long sliced_units = g.flat ? (g.nsl > 1 ? (long)g.ptiles * g.mtiles : 0) : best_tail;
+    p->partial_bytes = (size_t)sliced_units * g.nsl * v.mb * (v.nt * v.wn * 32) * sizeof(float);
+    p->reduce_units = (int)sliced_units;
     return true;
 }
 
@@ -797,10 +833,10 @@ int run_plan(cnn_ctx* ctx, ConvPlan& p, const float* in, const float* wt, float*
     p.g.epi = epi;
     LaunchArgs a{p.g, p.lds_bytes, in, wt, aux, out, ws, arg};
     int st = p.v->fn(ctx, a);
-    if (st != CNN_OK || p.g.tail_per_xcd == 0) return st;
+    if (st != CNN_OK || p.reduce_units == 0) return st;
     {
         cnn::ProfScope ps(ctx, "k_tile_reduce", 0.0);
-        hipLaunchKernelGGL(k_tile_reduce, dim3((unsigned)(8 * p.g.tail_per_xcd), (unsigned)(p.v->mb / 8)), dim3(256), 0,
+        hipLaunchKernelGGL(k_tile_reduce, dim3((unsigned)p.reduce_units, (unsigned)(p.v->mb / 8)), dim3(256), 0,
                            ctx->stream, p.g, p.v->mb, p.v->nt * p.v->wn * 32, ws, aux, out, arg);
     }
     return cnn::launch_check(ctx, "tile_reduce");

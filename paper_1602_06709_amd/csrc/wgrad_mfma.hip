@@ -322,13 +322,25 @@ __global__ void __launch_bounds__(256) k_wgrad_reduce(int nsplit, int KC, const 
     const int kcl = threadIdx.x & 63, part = threadIdx.x >> 6;
     const int kc0 = blockIdx.x * 64, kc = kc0 + kcl;
     if (kc < KC) {
-        // the thread's taps side by side, two splits per trip: 2 * NT independent loads in flight; per element the
+        // the thread's taps side by side, eight splits per trip: 8 * NT independent loads in flight; per element the
         // even splits add up in one sum and the odd ones in another, each in split order
         float s0[NT], s1[NT];
 #pragma unroll
         for (int t = 0; t < NT; ++t) s0[t] = s1[t] = 0.f;
         const float* src = partial + (size_t)part * KC + kc;
         int s = 0;
+        for (; s + 7 < nsplit; s += 8) {
+            float a[8][NT];
+#pragma unroll
+            for (int u = 0; u < 8; ++u)
+#pragma unroll
+                for (int t = 0; t < NT; ++t)
+                    a[u][t] = part + 4 * t < RS ? src[(size_t)(s + u) * total + (size_t)4 * t * KC] : 0.f;
+#pragma unroll
+            for (int u = 0; u < 8; u += 2)
+#pragma unroll
+                for (int t = 0; t < NT; ++t) { s0[t] += a[u][t]; s1[t] += a[u + 1][t]; }
+        }
         for (; s + 1 < nsplit; s += 2) {
             float a[NT], b[NT];
 #pragma unroll
