@@ -102,6 +102,34 @@ def test_conv_three_passes_tiled_geometries(cnn, ctx, case):
     P.check_contraction("dw", P.np_(dw), *oracle.conv_bwd_weight(x, dy, R, R, 1, pad, with_abs=True))
 
 
+# (N, C, H, W, K, R, S, stride, pad): images that are not square, through every kernel family
+RECT_CASES = [(2, 16, 20, 36, 40, 3, 3, 1, 1), (3, 8, 30, 14, 72, 3, 3, 1, 1), (2, 32, 12, 56, 130, 3, 3, 1, 1),
+              (2, 16, 24, 40, 48, 5, 5, 1, 2), (2, 16, 18, 26, 40, 7, 7, 1, 3), (2, 3, 40, 64, 64, 3, 3, 1, 1),
+              (2, 3, 51, 75, 96, 11, 11, 4, 0), (2, 3, 50, 70, 64, 7, 7, 2, 3), (2, 64, 14, 28, 128, 3, 3, 1, 1),
+              (2, 16, 21, 33, 40, 3, 3, 2, 1)]
+
+
+@pytest.mark.parametrize("case", RECT_CASES)
+def test_conv_three_passes_rectangular_images(cnn, ctx, case):
+    N, C, H, W, K, R, S, stride, pad = case
+    say("rectangular case", case)
+    P_, Q_ = (H + 2 * pad - R) // stride + 1, (W + 2 * pad - S) // stride + 1
+    x = synth.randn(89, 1, (N, C, H, W)); w = synth.randn(89, 2, (K, C, R, S), 0.1); dy = synth.randn(89, 3, (N, K, P_, Q_))
+    y = cnn.cnn_conv_fwd(ctx, dev(x), dev(w), stride, pad)
+    dx = cnn.cnn_conv_bwd_data(ctx, dev(dy), dev(w), H, W, stride, pad)
+    dw = cnn.cnn_conv_bwd_weight(ctx, dev(x), dev(dy), R, S, stride, pad)
+    torch.cuda.synchronize()
+    P.check_contraction("y", P.np_(y), *oracle.conv_fwd(x, w, stride, pad, with_abs=True))
+    P.check_contraction("dx", P.np_(dx), *oracle.conv_bwd_data(dy, w, H, W, stride, pad, with_abs=True))
+    P.check_contraction("dw", P.np_(dw), *oracle.conv_bwd_weight(x, dy, R, S, stride, pad, with_abs=True))
+    if P_ % 2 == 0 and Q_ % 2 == 0:
+        r = cnn.cnn_conv_fwd_relu_pool(ctx, dev(x), dev(w), stride, pad)
+        if r is not None:
+            a2, arg2 = cnn.cnn_maxpool2_fwd(ctx, cnn.cnn_conv_fwd_relu(ctx, dev(x), dev(w), stride, pad))
+            torch.cuda.synchronize()
+            assert torch.equal(r[0], a2) and torch.equal(r[1], arg2)
+
+
 @pytest.mark.parametrize("case", [(2, 3, 64, 64, 7, 2, 3), (3, 3, 37, 40, 7, 2, 0), (2, 3, 224, 96, 7, 2, 3), (2, 1, 30, 24, 7, 1, 3)])
 def test_first_layer_7x7(cnn, ctx, case):
     # few input features under a 7x7 kernel, stride 2 (and 1): single-chunk tiled forward, small-C weight gradient
