@@ -166,6 +166,25 @@ def test_conv_generic_shapes_fall_back_and_match(cnn, ctx):
         P.check_contraction("dw", P.np_(dw), *oracle.conv_bwd_weight(x, dy, R, S, st, pad, with_abs=True))
 
 
+def test_conv_degenerate_shapes(cnn, ctx):
+    # images of one pixel / one row / smaller than the kernel's reach, a single feature on either side, padding
+    # beyond the kernel (outputs that see only zeros), a ragged 513-feature layer, one image
+    for (N, C, H, W, K, R, S, st, pad) in [(1, 4, 3, 3, 1, 3, 3, 1, 1), (1, 16, 1, 1, 32, 3, 3, 1, 1), (1, 4, 2, 50, 8, 3, 3, 1, 1),
+                                           (1, 8, 5, 5, 40, 3, 3, 1, 3), (2, 16, 8, 8, 16, 5, 5, 1, 4), (2, 1, 8, 8, 1, 3, 3, 1, 1),
+                                           (1, 4, 8, 8, 513, 3, 3, 1, 1), (1, 64, 14, 14, 128, 3, 3, 1, 1), (1, 3, 7, 7, 5, 7, 7, 2, 3),
+                                           (3, 16, 4, 4, 8, 7, 7, 1, 3), (1, 3, 11, 11, 96, 11, 11, 4, 0)]:
+        say("degenerate conv", (N, C, H, W, K, R, S, st, pad))
+        x = synth.randn(88, 1, (N, C, H, W)); w = synth.randn(88, 2, (K, C, R, S))
+        y = cnn.cnn_conv_fwd(ctx, dev(x), dev(w), st, pad)
+        dy = synth.randn(88, 3, tuple(y.shape))
+        dx = cnn.cnn_conv_bwd_data(ctx, dev(dy), dev(w), H, W, st, pad)
+        dw = cnn.cnn_conv_bwd_weight(ctx, dev(x), dev(dy), R, S, st, pad)
+        torch.cuda.synchronize()
+        P.check_contraction("y", P.np_(y), *oracle.conv_fwd(x, w, st, pad, with_abs=True))
+        P.check_contraction("dx", P.np_(dx), *oracle.conv_bwd_data(dy, w, H, W, st, pad, with_abs=True))
+        P.check_contraction("dw", P.np_(dw), *oracle.conv_bwd_weight(x, dy, R, S, st, pad, with_abs=True))
+
+
 def test_bwd_weight_is_bitwise_repeatable(cnn, ctx):
     x = dev(synth.randn(92, 1, (4, 32, 28, 28))); dy = dev(synth.randn(92, 2, (4, 64, 28, 28)))
     a = cnn.cnn_conv_bwd_weight(ctx, x, dy, 3, 3, 1, 1).clone()
