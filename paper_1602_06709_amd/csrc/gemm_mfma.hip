@@ -239,14 +239,81 @@ k_gemm(int M, int Nn, int Kd, int k_per_split, const float* __restrict__ A, cons
                     for (int v = 0; v < 16; ++v) ex[((i * NT + j) * 16 + v) * 64] = acc[i][j][v];
         }
         __syncthreads();
-        if (kg == 1) return;
+        if (kg == 0) {
 #pragma unroll
-        for (int i = 0; i < MT; ++i)
+            for (int i = 0; i < MT; ++i)
 #pragma unroll
-            for (int j = 0; j < NT; ++j)
+                for (int j = 0; j < NT; ++j)
 #pragma unroll
-                for (int v = 0; v < 16; ++v) acc[i][j][v] += ex[((i * NT + j) * 16 + v) * 64];
+                    for (int v = 0; v < 16; ++v) acc[i][j][v] += ex[((i * NT + j) * 16 + v) * 64];
+        }
     }
+
+    if ((Nn & 3) == 0) {
+        // Rows of C are 16-byte aligned: the tile turns through LDS ([TM][TN], lane = column: conflict-free) and
+        // leaves as float4, 512 contiguous bytes per tile row, with every thread of the workgroup taking part; the
+        // SGD form reads w and v the same way, four float4 pairs in flight per thread.
+        constexpr int TM = G::TM, TN = G::TN;
+        __syncthreads();                     // operand buffers and exchange slots are no longer read
+        if (kg == 0) {
+#pragma unroll
+            for (int i = 0; i < MT; ++i)
+#pragma unroll
+                for (int j = 0; j < NT; ++j)
+#pragma unroll
+                    for (int v = 0; v < 16; ++v)
+                        lds[((wm * MT + i) * 32 + 8 * (v / 4) + 4 * half + (v % 4)) * TN + (wn * NT + j) * 32 + l32] = acc[i][j][v];
+        }
+        __syncthreads();
+        constexpr int ITER = TM * TN / 4 / T;      // float4 per thread: 4 to 16
+        static_assert(TM * TN <= 2 * G::BUF, "the output tile fits the operand buffers");
+        auto where = [&](int it, size_t* e) {
+            const int idx = tid + it * T, row = idx / (TN / 4), c4 = idx % (TN / 4);
+            const int m = m0 + row, n = n0 + 4 * c4;
+            const bool ok = m < M && n < Nn;
+            *e = ok ? (size_t)m * Nn + n : 0;
+            return ok;
+        };
+        if (sink.w) {
+            // the accumulators are in LDS, their registers are free: every read of w and v the thread needs is issued
+            // before the first update (up to 32 float4 in flight per thread; the update is latency-bound otherwise)
+            f32x4 wq[ITER], vq[ITER];
+#pragma unroll
+            for (int it = 0; it < ITER; ++it) {
+                size_t e;
+                where(it, &e);
+                wq[it] = *reinterpret_cast<const f32x4*>(sink.w + e);
+                if (sink.v) vq[it] = *reinterpret_cast<const f32x4*>(sink.v + e);
+            }
+#pragma unroll
+            for (int it = 0; it < ITER; ++it) {
+                size_t e;
+                if (!where(it, &e)) continue;
+                const int idx = tid + it * T;
+                const f32x4 gq = *(const lds_f32x4*)(lds + (idx / (TN / 4)) * TN + 4 * (idx % (TN / 4)));
+                f32x4 vel = gq, o;
+                if (sink.v) {
+                    vel.x = fmaf(sink.mu, vq[it].x, gq.x); vel.y = fmaf(sink.mu, vq[it].y, gq.y);
+                    vel.z = fmaf(sink.mu, vq[it].z, gq.z); vel.w = fmaf(sink.mu, vq[it].w, gq.w);
+                    __builtin_nontemporal_store(vel, reinterpret_cast<f32x4*>(sink.v + e));
+                }
+                o.x = fmaf(-sink.lr, vel.x, wq[it].x); o.y = fmaf(-sink.lr, vel.y, wq[it].y);
+                o.z = fmaf(-sink.lr, vel.z, wq[it].z); o.w = fmaf(-sink.lr, vel.w, wq[it].w);
+                __builtin_nontemporal_store(o, reinterpret_cast<f32x4*>(sink.w + e));
+            }
+        } else {
+            float* dst = sink.dw + out0;
+#pragma unroll
+            for (int it = 0; it < ITER; ++it) {
+                size_t e;
+                if (!where(it, &e)) continue;
+                const int idx = tid + it * T;
+                *reinterpret_cast<f32x4*>(dst + e) = *(const lds_f32x4*)(lds + (idx / (TN / 4)) * TN + 4 * (idx % (TN / 4)));
+            }
+        }
+        return;
+    }
+    if (kg == 1) return;
 
     if (sink.w) {
         // SGD step on the tile's elements: all of a 32x32 block's reads are issued before its first write (the
