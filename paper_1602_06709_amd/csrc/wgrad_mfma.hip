@@ -363,7 +363,32 @@ __global__ void __launch_bounds__(256) k_wgrad_reduce(int nsplit, int KC, const 
     }
     __syncthreads();
     const int live = min(64, KC - kc0) * RS;
-    for (int j = threadIdx.x; j < live; j += 256) sink_store(sink, (size_t)kc0 * RS + j, turn[j]);
+    if (sink.w) {
+        // SGD form: all reads of w and v first (same arithmetic as sink_store)
+        constexpr int IT = (64 * RS + 255) / 256;
+        float wv[IT], vv[IT];
+#pragma unroll
+        for (int t = 0; t < IT; ++t) {
+            const int j = threadIdx.x + 256 * t;
+            const size_t e = (size_t)kc0 * RS + (j < live ? j : 0);
+            wv[t] = sink.w[e];
+            vv[t] = sink.v ? sink.v[e] : 0.f;
+        }
+#pragma unroll
+        for (int t = 0; t < IT; ++t) {
+            const int j = threadIdx.x + 256 * t;
+            if (j >= live) continue;
+            const size_t e = (size_t)kc0 * RS + j;
+            float vel = turn[j];
+            if (sink.v) {
+                vel = fmaf(sink.mu, vv[t], vel);
+                sink.v[e] = vel;
+            }
+            sink.w[e] = fmaf(-sink.lr, vel, wv[t]);
+        }
+        return;
+    }
+    for (int j = threadIdx.x; j < live; j += 256) sink.dw[(size_t)kc0 * RS + j] = turn[j];
 }
 
 struct Plan {
