@@ -131,7 +131,7 @@ size_t cnn_workspace_bytes(int op, int N, int C, int H, int W, int K, int R, int
     if (make_shape(N, C, H, W, K, R, S, stride, pad, &s) != CNN_OK) return 0;
     switch (op) {
         case CNN_OP_CONV_FWD: return cnn::mfma_conv_fwd_ws(s);
-        case CNN_OP_CONV_FWD_RELU_POOL: return cnn::mfma_conv_fwd_pool_ws(s);
+        case CNN_OP_CONV_FWD_RELU_POOL: return cnn::c3_pool_serves(s) ? 0 : cnn::mfma_conv_fwd_pool_ws(s);
         case CNN_OP_CONV_BWD_DATA: return cnn::mfma_conv_bwd_data_ws(s);
         case CNN_OP_CONV_BWD_WEIGHT: {
             const size_t a = cnn::mfma_conv_bwd_weight_ws(s);
@@ -177,6 +177,8 @@ int cnn_conv_fwd_relu_pool(cnn_ctx* ctx, int N, int C, int H, int W, int K, int 
     if (st != CNN_OK) return st;
     if ((s.P | s.Q) & 1) return CNN_EINVAL;
     if (ctx->force_direct) return CNN_EUNSUPPORTED;
+    st = cnn::c3_pool_conv_fwd(ctx, s, x, w, a, arg);
+    if (st != CNN_EUNSUPPORTED) return st;
     return cnn::mfma_conv_fwd_pool(ctx, s, x, w, a, arg);
 }
 

@@ -93,6 +93,9 @@ size_t mfma_conv_fwd_pool_ws(const ConvShape&);
 int mfma_conv_fwd_pool(cnn_ctx*, const ConvShape&, const float* x, const float* w, float* a, unsigned char* arg);
 bool mfma_conv_tile_info(const ConvShape&, int op, int32_t tile[8]);
 size_t block_search_ws();
+// 3x3 first layer (3 input feature maps, 224 columns, 64 features) with ReLU + 2x2 max-pool in the epilogue
+int c3_pool_conv_fwd(cnn_ctx*, const ConvShape&, const float* x, const float* w, float* a, unsigned char* arg);
+bool c3_pool_serves(const ConvShape&);
 // strided first layer (3 input feature maps, 11x11 / 4)
 int c3_strided_conv_fwd(cnn_ctx*, const ConvShape&, const float* x, const float* w, float* y, int relu);
 // few input feature maps (first layers), any kernel size / stride

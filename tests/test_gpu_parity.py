@@ -475,6 +475,25 @@ def test_training_steps_with_folded_sgd_equal_the_separate_update(cnn, ctx, cfg)
             assert torch.equal(nets[0].v_arena, nets[1].v_arena), f"velocity differs after iteration {it}"
 
 
+@pytest.mark.parametrize("case", [(28, 224), (56, 100), (40, 158)])
+def test_first_layer_band_kernel_with_pool(cnn, ctx, case):
+    # 3 -> 64 features, 3x3 / pad 1, 224 columns, conv -> ReLU -> 2x2 max-pool in one kernel that walks bands of 14
+    # rows (served from 448 bands up): whole bands, a ragged last band (100 = 7 x 14 + 2; 158 = 11 x 14 + 4), all
+    # elements against the oracle; the unfused sequence must agree wherever the window's maximum is not a near-tie
+    N, H = case
+    say("first-layer band kernel", case)
+    x = synth.randn(87, 1, (N, 3, H, 224)); w = synth.randn(87, 2, (64, 3, 3, 3), 0.2)
+    r = cnn.cnn_conv_fwd_relu_pool(ctx, dev(x), dev(w), 1, 1)
+    assert r is not None
+    a, arg = r
+    torch.cuda.synchronize()
+    P.check_trace_item(("conv_fwd_relu_pool", 0, 0, dev(x), dev(w), a, arg), 0, [("conv", 3, 64, 3, 3, 1, 1)], True)
+    a2, arg2 = cnn.cnn_maxpool2_fwd(ctx, cnn.cnn_conv_fwd_relu(ctx, dev(x), dev(w), 1, 1))
+    torch.cuda.synchronize()
+    assert float((a - a2).abs().max()) <= 1e-4
+    assert float((arg != arg2).float().mean()) < 1e-3
+
+
 def test_config5_dnn7_n1024_sampled(cnn, ctx):
     _run_and_check(cnn, ctx, 5, None, False, n_samples=20000)
 
