@@ -42,6 +42,8 @@ struct WgCfg {
     static constexpr int R = R_, S = S_, KW = KW_, CW = CW_, RW = RW_, NSLOT = NSLOT_;
     static constexpr int TW_CT = TW_, NBI_CT = NBI_;
     static constexpr bool FIXED = TW_ != 0;
+    // the waves share the tile's feature rows evenly: every wave stages whole rows at compile-time strides
+    static constexpr bool EVEN = TW_ != 0 && (32 * CW_) % (KW_ * CW_ * RW_) == 0 && (32 * KW_) % (KW_ * CW_ * RW_) == 0;
     static constexpr int RS = R * S, RPW = R / RW;
     static constexpr int KB = 32 * KW, CBK = 32 * CW;
     static constexpr int T = 64 * KW * CW * RW;
@@ -53,8 +55,8 @@ struct WgCfg {
     static constexpr int QLOOP_CT = NBI_ == 1 ? TW_ / 2 : TW_;                 // columns per wave half and image
     static constexpr int NPAIRS_CT = (NBI_ == 1 ? 1 : NBI_ / 2) * ((QLOOP_CT + 1) / 2);
     static_assert(R % RW == 0 && NSLOT >= R + 1 && (NSLOT & (NSLOT - 1)) == 0, "ring geometry");
-    static_assert(!FIXED || (CBK % NWAVE == 0 && KB % NWAVE == 0 && QLOOP_CT % 2 == 0 && NBI_ * (TW_ + S - 1) <= 64),
-                  "fixed geometry: whole feature rows per wave, even column share per wave half");
+    static_assert(!FIXED || (QLOOP_CT % 2 == 0 && NBI_ * (TW_ + S - 1) <= 64),
+                  "fixed geometry: even column share per wave half");
 };
 
 template <class G>
@@ -106,8 +108,8 @@ k_wgrad(WgGeo g, const float* __restrict__ x, const float* __restrict__ dy, floa
     // scalar row indices relative to the tile's first row; the scalar part of a buffer address is not range-checked
     const int x_rows = min(G::CBK, C - c0), d_rows = min(G::KB, K - k0);
     // staging destinations of this wave's first feature row (fixed geometry) or of the tile's first row
-    lds_float* const xw = (lds_float*)(xl + (G::FIXED ? wave * XSTR : 0) + xb * NSLOT * WLD + lx % WLD);   // + ring slot
-    lds_float* const dw_ = (lds_float*)(dyl + (G::FIXED ? wave * DSTR : 0) + db * TW + ld % TW);           // + buffer
+    lds_float* const xw = (lds_float*)(xl + (G::EVEN ? wave * XSTR : 0) + xb * NSLOT * WLD + lx % WLD);   // + ring slot
+    lds_float* const dw_ = (lds_float*)(dyl + (G::EVEN ? wave * DSTR : 0) + db * TW + ld % TW);           // + buffer
 
     f32x16 acc[G::RPW][S];
 #pragma unroll
@@ -140,7 +142,7 @@ k_wgrad(WgGeo g, const float* __restrict__ x, const float* __restrict__ dy, floa
         int sx = so + wave * x_plane;
 #pragma unroll
         for (int i = 0; i < G::XS; ++i) {
-            const int off = G::FIXED ? sx : so + min(wave + i * G::NWAVE, x_rows - 1) * x_plane;
+            const int off = G::EVEN ? sx : so + min(wave + i * G::NWAVE, x_rows - 1) * x_plane;
             xr[i] = __builtin_bit_cast(float, __builtin_amdgcn_raw_buffer_load_b32(rs_x, xo, off, 0));
             sx += G::NWAVE * x_plane;
         }
@@ -151,7 +153,7 @@ k_wgrad(WgGeo g, const float* __restrict__ x, const float* __restrict__ dy, floa
         int sy = sd + wave * d_plane;
 #pragma unroll
         for (int i = 0; i < G::DS; ++i) {
-            const int off = G::FIXED ? sy : sd + min(wave + i * G::NWAVE, d_rows - 1) * d_plane;
+            const int off = G::EVEN ? sy : sd + min(wave + i * G::NWAVE, d_rows - 1) * d_plane;
             dr[i] = __builtin_bit_cast(float, __builtin_amdgcn_raw_buffer_load_b32(rs_dy, dyo, off, 0));
             sy += G::NWAVE * d_plane;
         }
@@ -161,10 +163,10 @@ k_wgrad(WgGeo g, const float* __restrict__ x, const float* __restrict__ dy, floa
     auto stage = [&](int u) {
         lds_float* xd = xw + (u & (NSLOT - 1)) * WLD;
 #pragma unroll
-        for (int i = 0; i < G::XS; ++i) xd[(G::FIXED ? i * G::NWAVE : min(wave + i * G::NWAVE, G::CBK - 1)) * XSTR] = xr[i];
+        for (int i = 0; i < G::XS; ++i) xd[(G::EVEN ? i * G::NWAVE : min(wave + i * G::NWAVE, G::CBK - 1)) * XSTR] = xr[i];
         lds_float* dd = dw_ + (u & 1) * G::KB * DSTR;
 #pragma unroll
-        for (int i = 0; i < G::DS; ++i) dd[(G::FIXED ? i * G::NWAVE : min(wave + i * G::NWAVE, G::KB - 1)) * DSTR] = dr[i];
+        for (int i = 0; i < G::DS; ++i) dd[(G::EVEN ? i * G::NWAVE : min(wave + i * G::NWAVE, G::KB - 1)) * DSTR] = dr[i];
     };
 
     // operands of pixel pair (b, q) of step u: a[2], bv[r][S+1] (the two pixels' taps overlap in S-1 columns);
@@ -499,6 +501,8 @@ using Wg3F56 = WgCfg<3, 3, 4, 2, 1, 4, 56, 1>;
 using Wg3F28 = WgCfg<3, 3, 4, 2, 1, 4, 28, 2>;
 using Wg3F14 = WgCfg<3, 3, 4, 2, 1, 4, 14, 4>;
 using Wg3F12 = WgCfg<3, 3, 4, 2, 1, 4, 12, 4>;
+// 5x5 with whole tiles and the step geometry of OverFeat-FAST's 24-pixel layer (two images per step)
+using Wg5F24 = WgCfg<5, 5, 2, 1, 5, 8, 24, 2>;
 
 }  // namespace
 
@@ -522,7 +526,10 @@ int mfma_conv_bwd_weight(cnn_ctx* ctx, const ConvShape& s, const float* x, const
         }
         return launch<Wg3>(ctx, p, s, x, dy, dw);
     }
-    if (make_plan<Wg5>(s, &p)) return launch<Wg5>(ctx, p, s, x, dy, dw);
+    if (make_plan<Wg5>(s, &p)) {
+        if (s.C % Wg5::CBK == 0 && s.K % Wg5::KB == 0 && p.g.TW == 24 && p.g.NBI == 2) return launch<Wg5F24>(ctx, p, s, x, dy, dw);
+        return launch<Wg5>(ctx, p, s, x, dy, dw);
+    }
     if (make_plan<Wg7>(s, &p)) return launch<Wg7>(ctx, p, s, x, dy, dw);
     return CNN_EUNSUPPORTED;
 }

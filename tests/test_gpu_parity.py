@@ -81,6 +81,7 @@ CONV_CASES = [  # N, C, H, K, R, pad       (square images, stride 1)
     (3, 128, 10, 24, 3, 1),     # long contraction, few outputs: every unit sliced
     (3, 96, 28, 40, 5, 0),      # 5x5 with 96 input features: backpropagation in 32-feature tiles (four wave columns)
     (2, 32, 20, 96, 5, 2),      # ... and the forward pass with 96 output features
+    (3, 32, 28, 64, 5, 0),      # 5x5, 28 -> 24, whole tiles: fixed-geometry weight gradient, odd N
     (2, 16, 20, 40, 7, 3),      # 7x7 'same'
     (3, 32, 14, 72, 7, 0),      # 7x7, 14 -> 8
 ]
