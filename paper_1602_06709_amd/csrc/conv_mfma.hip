@@ -791,12 +791,14 @@ bool make_plan(int R, int S, int pad, int stride, int N, int J, int M, int HI, i
     const int nchunks = (J + v.CB - 1) / v.CB;
     const double ov_job = (8.0 / 4.0e12) / (2.0 * J * R * S / (0.85 * 157.3e12));
     const long slots = 256;            // workgroups per round: one per compute unit
-    const long rounds = units > slots ? units / slots : 0, tail = units - rounds * slots;
+    // units that exist (the XCD ranges are padded with empty ones when the pixel tiles do not divide by 8); if they
+    // fit one round they are not padded at all (flat numbering, below)
+    const long live = (long)g.ptiles * g.mtiles;
+    const long rounds = live > slots ? units / slots : 0, tail = units - rounds * slots;
     int best_tail = 0, best_nsl = 1;
     if (rounds == 0) {
         // a grid within one round: slice every unit just far enough that (almost) every compute unit gets a
         // workgroup; finer slices only add partial-tile traffic (measured at minibatch 4)
-        const long live = (long)g.ptiles * g.mtiles;               // without the empty units that pad the last XCD's range
         int nsl = 1;
         while (live * nsl < slots * 13 / 16 && nsl < 16 && nchunks / (nsl + 1) >= 8) ++nsl;
         best_nsl = nsl;
