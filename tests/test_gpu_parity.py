@@ -186,6 +186,41 @@ def test_conv_degenerate_shapes(cnn, ctx):
         P.check_contraction("dw", P.np_(dw), *oracle.conv_bwd_weight(x, dy, R, S, st, pad, with_abs=True))
 
 
+def _random_shapes(count, seed):
+    rng = np.random.default_rng(seed)
+    out = []
+    while len(out) < count:
+        R = int(rng.choice([1, 3, 3, 3, 5, 5, 7]))
+        st = int(rng.choice([1, 1, 1, 2]))
+        pad = int(rng.integers(0, R // 2 + 2))
+        H, W = int(rng.integers(R, 44)), int(rng.integers(R, 44))
+        C = int(rng.choice([1, 3, 4, 8, 12, 16, 24, 32, 64, 96]))
+        K = int(rng.choice([1, 8, 31, 32, 40, 64, 72, 96, 128, 136]))
+        N = int(rng.integers(1, 6))
+        if (H + 2 * pad - R) // st + 1 < 1 or (W + 2 * pad - R) // st + 1 < 1:
+            continue
+        out.append((N, C, H, W, K, R, R, st, pad))
+    return out
+
+
+@pytest.mark.parametrize("chunk", [0, 1, 2])
+def test_conv_seeded_random_shapes(cnn, ctx, chunk):
+    # 3 x 14 seeded shapes over kernel sizes 1 / 3 / 5 / 7, strides 1 / 2, paddings up to R/2 + 1, ragged feature
+    # counts and rectangular images: whichever kernel serves each pass must match the oracle
+    for case in _random_shapes(14, 1000 + chunk):
+        N, C, H, W, K, R, S, st, pad = case
+        say("random conv", case)
+        x = synth.randn(86, 1, (N, C, H, W)); w = synth.randn(86, 2, (K, C, R, S), 0.2)
+        y = cnn.cnn_conv_fwd(ctx, dev(x), dev(w), st, pad)
+        dy = synth.randn(86, 3, tuple(y.shape))
+        dx = cnn.cnn_conv_bwd_data(ctx, dev(dy), dev(w), H, W, st, pad)
+        dw = cnn.cnn_conv_bwd_weight(ctx, dev(x), dev(dy), R, S, st, pad)
+        torch.cuda.synchronize()
+        P.check_contraction("y", P.np_(y), *oracle.conv_fwd(x, w, st, pad, with_abs=True))
+        P.check_contraction("dx", P.np_(dx), *oracle.conv_bwd_data(dy, w, H, W, st, pad, with_abs=True))
+        P.check_contraction("dw", P.np_(dw), *oracle.conv_bwd_weight(x, dy, R, S, st, pad, with_abs=True))
+
+
 def test_bwd_weight_is_bitwise_repeatable(cnn, ctx):
     x = dev(synth.randn(92, 1, (4, 32, 28, 28))); dy = dev(synth.randn(92, 2, (4, 64, 28, 28)))
     a = cnn.cnn_conv_bwd_weight(ctx, x, dy, 3, 3, 1, 1).clone()
