@@ -230,7 +230,8 @@ def test_bwd_weight_is_bitwise_repeatable(cnn, ctx):
 
 
 # ------------------------------------------------------------------ fully connected
-FC_CASES = [(64, 1024, 1000), (64, 440, 2048), (5, 36, 20), (130, 256, 136), (256, 2048, 520), (64, 25088, 256)]
+FC_CASES = [(64, 1024, 1000), (64, 440, 2048), (5, 36, 20), (130, 256, 136), (256, 2048, 520), (64, 25088, 256),
+            (1, 4096, 1024), (7, 100, 52), (33, 260, 1000), (1024, 64, 64), (300, 1028, 260), (4, 8, 4)]
 
 
 @pytest.mark.parametrize("case", FC_CASES)
