@@ -56,7 +56,8 @@ enum {
     CNN_OP_FC_FWD = 3,     /* N, I = C, O = K; H = W = R = S = 1 */
     CNN_OP_FC_BWD = 4,
     CNN_OP_CONV_FWD_RELU_POOL = 5,
-    CNN_OP_BLOCK_SEARCH = 6  /* cnn_block_search / cnn_block_search_traversal; the dimensions are ignored */
+    CNN_OP_BLOCK_SEARCH = 6, /* cnn_block_search / cnn_block_search_traversal; the dimensions are ignored */
+    CNN_OP_CONV_BWD_WEIGHT_UNPOOL = 7   /* 0 where cnn_conv_bwd_weight_unpool does not serve the shape */
 };
 
 /* options for cnn_set_option() */
@@ -169,6 +170,21 @@ int cnn_conv_bwd_weight_sgd(cnn_ctx* ctx, int N, int C, int H, int W, int K, int
                             const float* x, const float* dy, float* w, float* v, float lr, float momentum);
 int cnn_fc_bwd_sgd(cnn_ctx* ctx, int N, int I, int O, const float* x, float* w, const float* dy, float* dx, float* v,
                    float lr, float momentum);
+
+/* ---- Weight gradient of a first layer whose output went through ReLU and a 2x2 max-pool (Section 3.1: the first
+ *   layer has no backpropagation, so the full-size gradient in front of the pool is needed by nobody else):
+ *     dw = cnn_conv_bwd_weight(x, cnn_maxpool2_bwd(dpool, arg))
+ *   dpool [N][K][P/2][Q/2] is the gradient behind the pool, already multiplied by the ReLU derivative (what
+ *   cnn_conv_bwd_data_relu of the next layer stores when given the pooled activation as x_act); arg are the window
+ *   positions written by cnn_conv_fwd_relu_pool or cnn_maxpool2_fwd.  The full-size gradient is formed on the way
+ *   into LDS and never exists in memory.  The _sgd form folds the update in as cnn_conv_bwd_weight_sgd does.
+ *   Workspace: cnn_workspace_bytes(CNN_OP_CONV_BWD_WEIGHT_UNPOOL, ...).  CNN_EUNSUPPORTED (nothing launched) unless
+ *   C = 3, 3x3, stride 1, K <= 64 and P, Q even. */
+int cnn_conv_bwd_weight_unpool(cnn_ctx* ctx, int N, int C, int H, int W, int K, int R, int S, int stride, int pad,
+                               const float* x, const float* dpool, const uint8_t* arg, float* dw);
+int cnn_conv_bwd_weight_unpool_sgd(cnn_ctx* ctx, int N, int C, int H, int W, int K, int R, int S, int stride, int pad,
+                                   const float* x, const float* dpool, const uint8_t* arg, float* w, float* v, float lr,
+                                   float momentum);
 
 /* ---- Section 2.3 data layouts; pure permutations (bit-exact), lanes past C (or K) are written as 0.
  *   activations:        [N][C][H][W]  <->  [N][ceil(C/SW)][H][W][SW]

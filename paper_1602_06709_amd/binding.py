@@ -46,6 +46,8 @@ SIGNATURES = {
     "cnn_sgd_update": (_i, [_vp, _sz, _vp, _vp, _vp, _f, _f]),
     "cnn_conv_bwd_weight_sgd": (_i, [_vp] + [_i] * 9 + [_vp] * 4 + [_f, _f]),
     "cnn_fc_bwd_sgd": (_i, [_vp, _i, _i, _i, _vp, _vp, _vp, _vp, _vp, _f, _f]),
+    "cnn_conv_bwd_weight_unpool": (_i, [_vp] + [_i] * 9 + [_vp] * 4),
+    "cnn_conv_bwd_weight_unpool_sgd": (_i, [_vp] + [_i] * 9 + [_vp] * 5 + [_f, _f]),
     "cnn_bf_plane": (C.c_double, [_i] * 5),
     "cnn_bf_layer": (C.c_double, [_i] * 8),
     "cnn_bf_block_traversal": (C.c_double, [_i] * 8),
@@ -303,6 +305,35 @@ def cnn_conv_bwd_weight_sgd(ctx, x, dy, w, v=None, stride=1, pad=0, lr=0.01, mom
         return None
     _check(st, ctx.handle)
     return w
+
+
+OP_CONV_BWD_WEIGHT_UNPOOL = 7
+
+
+def conv_bwd_weight_unpool_serves(N, Cc, H, W, K, R, S, stride, pad):
+    return lib().cnn_workspace_bytes(OP_CONV_BWD_WEIGHT_UNPOOL, N, Cc, H, W, K, R, S, stride, pad) > 0
+
+
+def cnn_conv_bwd_weight_unpool(ctx, x, dpool, arg, R, S, stride=1, pad=0, out=None, w=None, v=None, lr=0.01, momentum=0.0):
+    """dw = conv_bwd_weight(x, maxpool2_bwd(dpool, arg)) without the full-size gradient; with w given, the SGD step
+    on w (and v) instead of storing dw.  Returns None (nothing launched) where the library does not serve the shape."""
+    N, Cc, H, W = x.shape
+    K = dpool.shape[1]
+    P, Q = out_dim(H, R, stride, pad), out_dim(W, S, stride, pad)
+    assert tuple(dpool.shape) == (N, K, P // 2, Q // 2) and tuple(arg.shape) == tuple(dpool.shape)
+    ctx.reserve_for(OP_CONV_BWD_WEIGHT_UNPOOL, N, Cc, H, W, K, R, S, stride, pad)
+    if w is not None:
+        st = lib().cnn_conv_bwd_weight_unpool_sgd(ctx.handle, N, Cc, H, W, K, R, S, stride, pad, _t(x), _t(dpool),
+                                                  _t(arg, torch.uint8), _t(w), _t(v) if v is not None else None, lr, momentum)
+        res = w
+    else:
+        res = out if out is not None else torch.empty((K, Cc, R, S), dtype=torch.float32, device=x.device)
+        st = lib().cnn_conv_bwd_weight_unpool(ctx.handle, N, Cc, H, W, K, R, S, stride, pad, _t(x), _t(dpool),
+                                              _t(arg, torch.uint8), _t(res))
+    if st == EUNSUPPORTED:
+        return None
+    _check(st, ctx.handle)
+    return res
 
 
 def cnn_fc_bwd_sgd(ctx, x, w, dy, v=None, need_dx=True, dx_out=None, lr=0.01, momentum=0.0):

@@ -130,6 +130,7 @@ size_t cnn_workspace_bytes(int op, int N, int C, int H, int W, int K, int R, int
     ConvShape s;
     if (make_shape(N, C, H, W, K, R, S, stride, pad, &s) != CNN_OK) return 0;
     switch (op) {
+        case CNN_OP_CONV_BWD_WEIGHT_UNPOOL: return cnn::smallc_unpool_serves(s) ? cnn::smallc_conv_bwd_weight_ws(s) : 0;
         case CNN_OP_CONV_FWD: return cnn::mfma_conv_fwd_ws(s);
         case CNN_OP_CONV_FWD_RELU_POOL: return cnn::c3_pool_serves(s) ? 0 : cnn::mfma_conv_fwd_pool_ws(s);
         case CNN_OP_CONV_BWD_DATA: return cnn::mfma_conv_bwd_data_ws(s);
@@ -264,6 +265,27 @@ int cnn_conv_tile_info(int op, int N, int C, int H, int W, int K, int R, int S, 
     *bf = cnn_bf_block_traversal(ifm, R, S, op == CNN_OP_CONV_BWD_DATA ? 1 : stride, images, tile[0], tile[1] / images,
                                  tile[2]);
     return CNN_OK;
+}
+
+static int bwd_weight_unpool_impl(cnn_ctx* ctx, int N, int C, int H, int W, int K, int R, int S, int stride, int pad,
+                                  const float* x, const float* dpool, const uint8_t* arg, const GradSink& sink) {
+    if (!ctx || !x || !dpool || !arg || !aligned16(x) || !aligned16(dpool)) return CNN_EINVAL;
+    ConvShape s;
+    int st = make_shape(N, C, H, W, K, R, S, stride, pad, &s);
+    if (st != CNN_OK) return st;
+    if (ctx->force_direct) return CNN_EUNSUPPORTED;
+    return cnn::smallc_conv_bwd_weight_unpool(ctx, s, x, dpool, arg, sink);
+}
+int cnn_conv_bwd_weight_unpool(cnn_ctx* ctx, int N, int C, int H, int W, int K, int R, int S, int stride, int pad,
+                               const float* x, const float* dpool, const uint8_t* arg, float* dw) {
+    if (!dw || !aligned16(dw)) return CNN_EINVAL;
+    return bwd_weight_unpool_impl(ctx, N, C, H, W, K, R, S, stride, pad, x, dpool, arg, sink_dw(dw));
+}
+int cnn_conv_bwd_weight_unpool_sgd(cnn_ctx* ctx, int N, int C, int H, int W, int K, int R, int S, int stride, int pad,
+                                   const float* x, const float* dpool, const uint8_t* arg, float* w, float* v, float lr,
+                                   float momentum) {
+    if (!w || !aligned16(w) || (v && !aligned16(v))) return CNN_EINVAL;
+    return bwd_weight_unpool_impl(ctx, N, C, H, W, K, R, S, stride, pad, x, dpool, arg, GradSink{nullptr, w, v, lr, momentum});
 }
 
 // Fully-connected layers: the conv loop nest with k_h = k_w = out_h = out_w = 1 (Section 2.1), i.e. GEMMs.

@@ -101,6 +101,10 @@ int c3_strided_conv_fwd(cnn_ctx*, const ConvShape&, const float* x, const float*
 // few input feature maps (first layers), any kernel size / stride
 int smallc_conv_bwd_weight(cnn_ctx*, const ConvShape&, const float* x, const float* dy, const GradSink& sink);
 size_t smallc_conv_bwd_weight_ws(const ConvShape&);
+// ... with the gradient given behind a 2x2 max-pool (pooled size + window positions)
+int smallc_conv_bwd_weight_unpool(cnn_ctx*, const ConvShape&, const float* x, const float* dpool, const unsigned char* arg,
+                                  const GradSink& sink);
+bool smallc_unpool_serves(const ConvShape&);
 
 // C[M][Nn] = op(A) * op(B); row-major operands.
 //   a_kmajor == 0: A is [M][Kd] (contraction index contiguous);  != 0: A is [Kd][M]

@@ -31,9 +31,13 @@ struct SmallcArgs {
 
 // KBK: 32-blocks of output features; JB: 32-blocks of j per wave; JW x PW waves: JW split j, PW split the row's
 // pixel pairs; CC input features; ST stride; NPASS = ceil(TW / 64) lanes-passes over a dy row.
-template <int KBK, int JB, int JW, int PW, int CC, int ST, int NPASS>
+// POOL: dy is the gradient behind a 2x2 max-pool, [N][K][P/2][Q/2], with the window positions parg of the pool's
+// forward pass: the full-size gradient row (zero except at each window's recorded position) is formed on the way
+// into LDS and never exists in memory.
+template <int KBK, int JB, int JW, int PW, int CC, int ST, int NPASS, bool POOL>
 __global__ void __launch_bounds__(256)
-k_wgrad_smallc(SmallcArgs a, const float* __restrict__ x, const float* __restrict__ dy, float* __restrict__ partial) {
+k_wgrad_smallc(SmallcArgs a, const float* __restrict__ x, const float* __restrict__ dy, const unsigned char* __restrict__ parg,
+               float* __restrict__ partial) {
     constexpr int KROWS = 32 * KBK, RPWV = KROWS / 4;       // dy rows per wave
     extern __shared__ float lds[];
     float* xl = lds;                              // [CC][nslot][WLD]
@@ -71,6 +75,7 @@ k_wgrad_smallc(SmallcArgs a, const float* __restrict__ x, const float* __restric
             for (int v = 0; v < 16; ++v) acc[i][b][v] = 0.f;
 
     float xr[ST][CC], dr[RPWV][NPASS];
+    int da[POOL ? RPWV : 1][1];      // POOL: the window position recorded for the fetched element
 
     // the ST newest input rows of output row p (image n): rows p*ST - pad + R - ST + i
     auto fetch_x = [&](int n, int p) {
@@ -85,6 +90,20 @@ k_wgrad_smallc(SmallcArgs a, const float* __restrict__ x, const float* __restric
         }
     };
     auto fetch_dy = [&](int n, int p) {
+        if (POOL) {
+            // lane l takes the pooled element of columns (2l, 2l+1), row p/2: one read serves two columns and both
+            // rows of the pair
+            const int PP = a.P / 2, QP = a.Q / 2;
+#pragma unroll
+            for (int i = 0; i < RPWV; ++i) {
+                const int k = wave + 4 * i;
+                const bool ok = k < a.K && 2 * lane < a.TW;
+                const size_t e = ok ? (((size_t)n * a.K + k) * PP + (p >> 1)) * QP + (q0 >> 1) + lane : 0;
+                dr[i][0] = dy[e];
+                da[POOL ? i : 0][0] = parg[e];
+            }
+            return;
+        }
         const float* ds = dy + ((size_t)n * a.K * a.P + p) * a.Q + q0;
 #pragma unroll
         for (int i = 0; i < RPWV; ++i) {
@@ -134,16 +153,30 @@ k_wgrad_smallc(SmallcArgs a, const float* __restrict__ x, const float* __restric
 #pragma unroll
                     for (int c = 0; c < CC; ++c) xl[c * a.cpl + ((hb + i + a.pad) & mask) * a.WLD + tid] = xr[i][c];
             }
+            if (POOL) {
+                // the gradient belongs to the window position 2 * (row parity) + (column parity); the other column gets 0
+                if (2 * lane < a.TW) {
 #pragma unroll
-            for (int i = 0; i < RPWV; ++i)
+                    for (int i = 0; i < RPWV; ++i) {
+                        const bool live = wave + 4 * i < a.K;
+                        const int pos = da[POOL ? i : 0][0] - 2 * (p & 1);
+                        float* d = dyl + (buf * KROWS + wave + 4 * i) * a.dstr + 2 * lane;
+                        d[0] = (live && pos == 0) ? dr[i][0] : 0.f;
+                        d[1] = (live && pos == 1) ? dr[i][0] : 0.f;
+                    }
+                }
+            } else {
 #pragma unroll
-                for (int h = 0; h < NPASS; ++h)
-                    if (lane + 64 * h < a.TW) dyl[(buf * KROWS + wave + 4 * i) * a.dstr + lane + 64 * h] = dr[i][h];
+                for (int i = 0; i < RPWV; ++i)
+#pragma unroll
+                    for (int h = 0; h < NPASS; ++h)
+                        if (lane + 64 * h < a.TW) dyl[(buf * KROWS + wave + 4 * i) * a.dstr + lane + 64 * h] = dr[i][h];
+            }
             __syncthreads();
             fresh = false;
             if (g + 1 < g_end) {
                 const int n1 = (g + 1) / a.P, p1 = (g + 1) % a.P;
-                fetch_dy(n1, p1);
+                if (!POOL || !(p1 & 1)) fetch_dy(n1, p1);     // POOL: an odd row reads what the even row before it read
                 if (p1 == 0 || ST >= a.R) fresh = true;
                 else fetch_x(n1, p1);
             }
@@ -318,9 +351,10 @@ SmallcPlan plan(const ConvShape& s) {
     return p;
 }
 
-template <int KBK, int JB, int JW, int PW, int CC, int ST, int NPASS>
-int launch(cnn_ctx* ctx, const SmallcPlan& p, const ConvShape& s, const float* x, const float* dy, const GradSink& sink) {
-    auto kern = &k_wgrad_smallc<KBK, JB, JW, PW, CC, ST, NPASS>;
+template <int KBK, int JB, int JW, int PW, int CC, int ST, int NPASS, bool POOL = false>
+int launch(cnn_ctx* ctx, const SmallcPlan& p, const ConvShape& s, const float* x, const float* dy, const GradSink& sink,
+           const unsigned char* parg = nullptr) {
+    auto kern = &k_wgrad_smallc<KBK, JB, JW, PW, CC, ST, NPASS, POOL>;
     static bool attr_done = false;
     if (!attr_done) {
         hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(kern), hipFuncAttributeMaxDynamicSharedMemorySize,
@@ -330,11 +364,11 @@ int launch(cnn_ctx* ctx, const SmallcPlan& p, const ConvShape& s, const float* x
     }
     float* partial = reinterpret_cast<float*>(ctx->ws);
     static char name[64] = "";
-    if (!name[0]) snprintf(name, sizeof(name), "k_wgrad_smallc<KB%d JB%d JW%d PW%d ST%d>", KBK, JB, JW, PW, ST);
+    if (!name[0]) snprintf(name, sizeof(name), "k_wgrad_smallc<KB%d JB%d JW%d PW%d ST%d%s>", KBK, JB, JW, PW, ST, POOL ? " unpool" : "");
     {
         cnn::ProfScope ps(ctx, name, cnn::conv_flops(s));
         hipLaunchKernelGGL(kern, dim3((unsigned)(p.nsplit * p.a.col_tiles)), dim3(256), p.lds_bytes, ctx->stream, p.a, x, dy,
-                           partial);
+                           parg, partial);
     }
     int st = cnn::launch_check(ctx, "wgrad_smallc");
     if (st != CNN_OK) return st;
@@ -354,6 +388,21 @@ namespace cnn {
 size_t smallc_conv_bwd_weight_ws(const ConvShape& s) {
     const SmallcPlan p = plan(s);
     return p.ok ? p.ws_bytes : 0;
+}
+
+// dw = conv_bwd_weight(x, maxpool2_bwd(dpool, arg)): the stride-1 variants (3x3 first layers), even output sizes
+bool smallc_unpool_serves(const ConvShape& s) {
+    const SmallcPlan p = plan(s);
+    return p.ok && p.variant <= 1 && !((s.P | s.Q) & 1);
+}
+
+int smallc_conv_bwd_weight_unpool(cnn_ctx* ctx, const ConvShape& s, const float* x, const float* dpool, const unsigned char* arg,
+                                  const GradSink& dw) {
+    if (!smallc_unpool_serves(s)) return CNN_EUNSUPPORTED;
+    const SmallcPlan p = plan(s);
+    if (!ctx->ws || ctx->ws_bytes < p.ws_bytes) return CNN_EWORKSPACE;
+    if (p.variant == 0) return launch<1, 1, 1, 4, 3, 1, 2, true>(ctx, p, s, x, dpool, dw, arg);
+    return launch<2, 1, 1, 4, 3, 1, 2, true>(ctx, p, s, x, dpool, dw, arg);
 }
 
 int smallc_conv_bwd_weight(cnn_ctx* ctx, const ConvShape& s, const float* x, const float* dy, const GradSink& dw) {

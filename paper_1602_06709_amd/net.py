@@ -68,6 +68,7 @@ class Net:
         self.labels = torch.zeros(n, dtype=torch.int32, device=dev)
         self.loss_per_sample = torch.empty(n, dtype=torch.float32, device=dev)
         self.trace = []
+        self._pooled_ok, self._pooled_first = None, False
         self.marks = None   # a list while a caller wants (op, layer, profile-entry count after the call) per call
         self._reserve()
 
@@ -148,9 +149,28 @@ class Net:
         self._rec("softmax_xent", len(self.layers) - 1, z, self.labels, self.loss_per_sample, self.gact[-1])
         return self.loss_per_sample
 
+    def _pooled_wgrad_serves(self):
+        """Can the first layer's weight gradient be taken from the gradient behind its ReLU + pool?"""
+        if self._pooled_ok is None:
+            L, n = self.layers[0], self.wl.input_shape
+            self._pooled_ok = (L[0] == "conv" and self.fuse_pool and
+                               B.conv_bwd_weight_unpool_serves(n[0], L[1], n[2], n[3], L[2], L[3], L[4], L[5], L[6]))
+        return self._pooled_ok
+
     def _wgrad(self, i, wi, update):
         """Weight gradient of conv layer i; with update, applied to the weights on the spot."""
         ctx, L, xin, dy = self.ctx, self.layers[i], self._input_of(i), self.gact[i]
+        if i == 0 and self._pooled_first:
+            self._pooled_first = False
+            dpool, arg = self.gact[2], self.arg[2]
+            if update:
+                B.cnn_conv_bwd_weight_unpool(ctx, xin, dpool, arg, L[3], L[4], L[5], L[6], w=self.w[wi], v=self.v[wi],
+                                             lr=self.wl.lr, momentum=self.wl.momentum)
+                self._rec("conv_bwd_weight_unpool_sgd", i, wi, xin, dpool, arg, self.w[wi], self.v[wi])
+            else:
+                B.cnn_conv_bwd_weight_unpool(ctx, xin, dpool, arg, L[3], L[4], L[5], L[6], out=self.dw[wi])
+                self._rec("conv_bwd_weight_unpool", i, wi, xin, dpool, arg, self.dw[wi])
+            return
         if update:
             done = B.cnn_conv_bwd_weight_sgd(ctx, xin, dy, self.w[wi], self.v[wi], L[5], L[6], self.wl.lr, self.wl.momentum)
             if done is not None:
@@ -191,14 +211,21 @@ class Net:
                 pool_in = (self.fuse_pool and i >= 3 and self.layers[i - 1][0] == "pool" and self.layers[i - 2][0] == "relu"
                            and self._fused_relu_after(i - 3))
                 unpooled = None
-                if not first and pool_in:
+                if pool_in and i == 3 and self._pooled_wgrad_serves():
+                    # the convolution in front of that ReLU + pool is the first layer: only its weight gradient wants
+                    # the gradient, and it takes it at pooled size (Section 3.1: no backpropagation there)
+                    B.cnn_conv_bwd_data_relu(ctx, dy, self.w[wi], xin, L[5], L[6], out=self.gact[i - 1])
+                    self._rec("conv_bwd_data_relu", i, wi, dy, self.w[wi], xin, self.gact[i - 1])
+                    skip.update((i - 1, i - 2))
+                    self._pooled_first = True
+                elif not first and pool_in:
                     # gradient in front of that ReLU + pool, straight into the earlier convolution's slot
                     unpooled = B.cnn_conv_bwd_data_unpool_relu(ctx, dy, self.w[wi], self.arg[i - 1], xin, L[5], L[6],
                                                                out=self.gact[i - 3])
                 if unpooled is not None:
                     self._rec("conv_bwd_data_unpool_relu", i, wi, dy, self.w[wi], self.arg[i - 1], xin, self.gact[i - 3])
                     skip.update((i - 1, i - 2))
-                elif not first:
+                elif not first and not (pool_in and i == 3 and self._pooled_first):
                     if relu_in:      # gradient in front of that ReLU, straight into the earlier convolution's slot
                         B.cnn_conv_bwd_data_relu(ctx, dy, self.w[wi], xin, L[5], L[6], out=self.gact[i - 2])
                         self._rec("conv_bwd_data_relu", i, wi, dy, self.w[wi], xin, self.gact[i - 2])

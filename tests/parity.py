@@ -155,6 +155,18 @@ def check_trace_item(item, cfg, layers, full, n_samples=20000, n_samples_wgrad=1
         idx = sample(cfg, 3000 + i, dw.size, n_samples_wgrad)
         ref, s = oracle.conv_bwd_weight_at(x, dy, L[3], L[4], idx, L[5], L[6])
         return check_contraction(name, dw.ravel()[idx], ref, s)
+    if op == "conv_bwd_weight_unpool":
+        # weight gradient from the gradient behind a 2x2 max-pool: the oracle un-pools, then takes the plain gradient
+        _, _, wi, x, dpool, arg, dw = item
+        x, dpool, arg, dw = np_(x), np_(dpool), np_(arg), np_(dw)
+        P_, Q_ = 2 * dpool.shape[2], 2 * dpool.shape[3]
+        dy = oracle.maxpool2_bwd(dpool, arg, P_, Q_)
+        if full:
+            ref, s = oracle.conv_bwd_weight(x, dy, L[3], L[4], L[5], L[6], with_abs=True)
+            return check_contraction(name, dw, ref, s)
+        idx = sample(cfg, 3000 + i, dw.size, n_samples_wgrad)
+        ref, s = oracle.conv_bwd_weight_at(x, dy, L[3], L[4], idx, L[5], L[6])
+        return check_contraction(name, dw.ravel()[idx], ref, s)
     if op == "fc_fwd":
         _, _, wi, x, w, y = item
         x, w, y = np_(x), np_(w), np_(y)

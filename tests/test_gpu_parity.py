@@ -531,6 +531,50 @@ def test_first_layer_band_kernel_with_pool(cnn, ctx, case):
     assert float((arg != arg2).float().mean()) < 1e-3
 
 
+@pytest.mark.parametrize("case", [(2, 3, 224, 224, 64, 1), (3, 3, 30, 44, 40, 1), (5, 3, 18, 24, 16, 0), (2, 3, 64, 130, 64, 1),
+                                  (16, 3, 224, 224, 64, 1)])
+def test_first_layer_weight_gradient_from_the_pooled_gradient(cnn, ctx, case):
+    # dw = conv_bwd_weight(x, maxpool2_bwd(dpool, arg)) without the full-size gradient: bit for bit what the two calls
+    # give (same kernel, the gradient formed on its way into LDS), and against the oracle; plain and with the SGD
+    # step folded in; then a shape the kernel does not serve is refused
+    N, C, H, W, K, pad = case
+    say("pooled weight gradient", case)
+    P_, Q_ = H + 2 * pad - 2, W + 2 * pad - 2
+    x = synth.randn(89, 1, (N, C, H, W))
+    dpool = synth.randn(89, 2, (N, K, P_ // 2, Q_ // 2))
+    dpool[0, 0, :2] = 0.0                                                       # a closed ReLU region
+    arg = (synth.randn(89, 3, dpool.shape) * 1e3).astype(np.int64) % 4
+    arg = arg.astype(np.uint8)
+    assert cnn.conv_bwd_weight_unpool_serves(N, C, H, W, K, 3, 3, 1, pad)
+    dw = cnn.cnn_conv_bwd_weight_unpool(ctx, dev(x), dev(dpool), dev(arg), 3, 3, 1, pad)
+    assert dw is not None
+    full = cnn.cnn_maxpool2_bwd(ctx, dev(dpool), dev(arg), P_, Q_)
+    dw2 = cnn.cnn_conv_bwd_weight(ctx, dev(x), full, 3, 3, 1, pad)
+    torch.cuda.synchronize()
+    assert torch.equal(dw, dw2)
+    P.check_trace_item(("conv_bwd_weight_unpool", 0, 0, dev(x), dev(dpool), dev(arg), dw), 0, [("conv", C, K, 3, 3, 1, pad)],
+                       N * H * W <= 2 * 224 * 224, n_samples_wgrad=600)
+    w0 = synth.randn(89, 4, (K, C, 3, 3), 0.1); v0 = synth.randn(89, 5, (K, C, 3, 3), 0.01)
+    w1, v1 = dev(w0), dev(v0)
+    cnn.cnn_conv_bwd_weight_unpool(ctx, dev(x), dev(dpool), dev(arg), 3, 3, 1, pad, w=w1, v=v1, lr=0.05, momentum=0.9)
+    w2, v2 = dev(w0), dev(v0)
+    cnn.cnn_sgd_update(ctx, w2.view(-1), dw2.view(-1), v2.view(-1), 0.05, 0.9)
+    torch.cuda.synchronize()
+    assert torch.equal(w1, w2) and torch.equal(v1, v2)
+
+
+def test_pooled_weight_gradient_refuses_other_shapes(cnn, ctx):
+    for (N, C, H, W, K, R, st, pad) in [(2, 3, 39, 39, 8, 11, 4, 0), (2, 3, 31, 30, 16, 3, 1, 0), (2, 16, 28, 28, 32, 3, 1, 1),
+                                        (2, 3, 64, 64, 96, 3, 1, 1)]:
+        assert not cnn.conv_bwd_weight_unpool_serves(N, C, H, W, K, R, R, st, pad)
+        P_, Q_ = (H + 2 * pad - R) // st + 1, (W + 2 * pad - R) // st + 1
+        if P_ % 2 or Q_ % 2:
+            continue
+        x = dev(synth.randn(88, 1, (N, C, H, W))); dp = dev(synth.randn(88, 2, (N, K, P_ // 2, Q_ // 2)))
+        arg = torch.zeros(dp.shape, dtype=torch.uint8, device="cuda")
+        assert cnn.cnn_conv_bwd_weight_unpool(ctx, x, dp, arg, R, R, st, pad) is None
+
+
 def test_config5_dnn7_n1024_sampled(cnn, ctx):
     _run_and_check(cnn, ctx, 5, None, False, n_samples=20000)
 
