@@ -63,7 +63,8 @@ enum {
 /* options for cnn_set_option() */
 enum {
     CNN_OPT_FORCE_DIRECT = 0, /* value != 0: route conv / fc calls to the plain one-thread-per-output kernels
-                                 (kept as the any-shape fallback); default 0 */
+                                 (any shape, slow; otherwise only reached by tensors the matrix-core kernels cannot
+                                 index); default 0 */
     CNN_OPT_PROFILE = 1       /* value != 0: bracket every kernel the library launches with a pair of HIP events
                                  on the context's stream (host-side objects only); read back with cnn_profile_*.
                                  Recording stops silently after 16384 entries until cnn_profile_reset(). default 0 */

@@ -135,8 +135,11 @@ size_t cnn_workspace_bytes(int op, int N, int C, int H, int W, int K, int R, int
         case CNN_OP_CONV_FWD_RELU_POOL: return cnn::c3_pool_serves(s) ? 0 : cnn::mfma_conv_fwd_pool_ws(s);
         case CNN_OP_CONV_BWD_DATA: return cnn::mfma_conv_bwd_data_ws(s);
         case CNN_OP_CONV_BWD_WEIGHT: {
+            // the kernels are tried in this order; one that does not serve the shape reports 0
             const size_t a = cnn::mfma_conv_bwd_weight_ws(s);
-            return a ? a : cnn::smallc_conv_bwd_weight_ws(s);
+            if (a) return a;
+            const size_t b = cnn::smallc_conv_bwd_weight_ws(s);
+            return b ? b : cnn::igemm_conv_bwd_weight_ws(s);
         }
         case CNN_OP_FC_FWD: return cnn::mfma_gemm_ws(N, K, C);
         case CNN_OP_FC_BWD: {
@@ -154,9 +157,15 @@ static int conv_fwd_impl(cnn_ctx* ctx, int N, int C, int H, int W, int K, int R,
     int st = make_shape(N, C, H, W, K, R, S, stride, pad, &s);
     if (st != CNN_OK) return st;
     if (!ctx->force_direct) {
+        if (s.stride > 1 && s.C >= 16) {
+            st = cnn::igemm_conv_fwd(ctx, s, x, w, y, relu);
+            if (st != CNN_EUNSUPPORTED) return st;
+        }
         st = cnn::mfma_conv_fwd(ctx, s, x, w, y, relu);
         if (st != CNN_EUNSUPPORTED) return st;
         st = cnn::c3_strided_conv_fwd(ctx, s, x, w, y, relu);
+        if (st != CNN_EUNSUPPORTED) return st;
+        st = cnn::igemm_conv_fwd(ctx, s, x, w, y, relu);
         if (st != CNN_EUNSUPPORTED) return st;
     }
     return cnn::direct_conv_fwd(ctx, s, x, w, y, relu);
@@ -191,6 +200,8 @@ static int conv_bwd_data_impl(cnn_ctx* ctx, int N, int C, int H, int W, int K, i
     if (st != CNN_OK) return st;
     if (!ctx->force_direct) {
         st = cnn::mfma_conv_bwd_data(ctx, s, dy, w, dx, act);
+        if (st != CNN_EUNSUPPORTED) return st;
+        st = cnn::igemm_conv_bwd_data(ctx, s, dy, w, dx, act);
         if (st != CNN_EUNSUPPORTED) return st;
     }
     return cnn::direct_conv_bwd_data(ctx, s, dy, w, dx, act);
@@ -228,6 +239,8 @@ int cnn_conv_bwd_weight(cnn_ctx* ctx, int N, int C, int H, int W, int K, int R, 
         if (st != CNN_EUNSUPPORTED) return st;
         st = cnn::smallc_conv_bwd_weight(ctx, s, x, dy, sink_dw(dw));
         if (st != CNN_EUNSUPPORTED) return st;
+        st = cnn::igemm_conv_bwd_weight(ctx, s, x, dy, sink_dw(dw));
+        if (st != CNN_EUNSUPPORTED) return st;
     }
     return cnn::direct_conv_bwd_weight(ctx, s, x, dy, dw);
 }
@@ -245,7 +258,9 @@ int cnn_conv_bwd_weight_sgd(cnn_ctx* ctx, int N, int C, int H, int W, int K, int
     const GradSink sink{nullptr, w, v, lr, momentum};
     st = cnn::mfma_conv_bwd_weight(ctx, s, x, dy, sink);
     if (st != CNN_EUNSUPPORTED) return st;
-    return cnn::smallc_conv_bwd_weight(ctx, s, x, dy, sink);
+    st = cnn::smallc_conv_bwd_weight(ctx, s, x, dy, sink);
+    if (st != CNN_EUNSUPPORTED) return st;
+    return cnn::igemm_conv_bwd_weight(ctx, s, x, dy, sink);
 }
 
 int cnn_conv_tile_info(int op, int N, int C, int H, int W, int K, int R, int S, int stride, int pad, int32_t* tile,

@@ -106,6 +106,12 @@ int smallc_conv_bwd_weight_unpool(cnn_ctx*, const ConvShape&, const float* x, co
                                   const GradSink& sink);
 bool smallc_unpool_serves(const ConvShape&);
 
+// implicit GEMM with a gathered operand: any kernel size, stride and padding (everything the kernels above leave)
+int igemm_conv_fwd(cnn_ctx*, const ConvShape&, const float* x, const float* w, float* y, int relu);
+int igemm_conv_bwd_data(cnn_ctx*, const ConvShape&, const float* dy, const float* w, float* dx, const float* act);
+int igemm_conv_bwd_weight(cnn_ctx*, const ConvShape&, const float* x, const float* dy, const GradSink& sink);
+size_t igemm_conv_bwd_weight_ws(const ConvShape&);
+
 // C[M][Nn] = op(A) * op(B); row-major operands.
 //   a_kmajor == 0: A is [M][Kd] (contraction index contiguous);  != 0: A is [Kd][M]
 //   b_kmajor == 0: B is [Nn][Kd] (contraction index contiguous); != 0: B is [Kd][Nn]

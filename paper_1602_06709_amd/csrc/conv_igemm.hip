@@ -1,0 +1,452 @@
+// Convolution as an implicit GEMM on the gfx950 matrix cores, for every shape the specialised kernels do not cover
+// (kernel sizes other than 3x3 / 5x5 / 7x7, rectangular kernels, strided backpropagation and strided weight
+// gradients with many input features).  The three loop nests of Section 3.1 are one contraction each:
+//   forward          y [k][(n,p,q)]   = sum over (c,r,s)  w[k][(c,r,s)]   * x [n][c][p*st-pad+r][q*st-pad+s]
+//   backpropagation  dx[c][(n,h,w)]   = sum over (k,r,s)  w[k][c][r][s]   * dy[n][k][(h+pad-r)/st][(w+pad-s)/st]
+//   weight gradient  dw[k][(c,r,s)]   = sum over (n,p,q)  dy[n][k][p][q]  * x [n][c][p*st-pad+r][q*st-pad+s]
+// (an element outside its tensor contributes 0).  Strided backpropagation runs once per phase
+// ((h + pad) mod st, (w + pad) mod st): the input elements of one phase see only the kernel taps r = phase + st r',
+// so each phase is a dense contraction over its own taps and no product is spent on positions the stride skips.
+// Nothing is copied or unfolded in memory: the second operand is gathered element by element on its way into LDS.
+// An element's address is the sum of a part that depends on its position along the contraction and a part that
+// depends on its output column; the part that is fixed for a thread sits in registers, the part that varies comes
+// from a small table in LDS (per chunk of the contraction: rebuilt two chunks ahead; per output column: built once).
+//
+// Workgroup: 2 x 2 waves, each WMT x WNT blocks of 32 x 32 (v_mfma_f32_32x32x2_f32); chunks of 32 contraction
+// elements, two LDS buffers, one barrier per chunk; the next chunk's elements are fetched into registers before the
+// chunk's MFMAs and stored to LDS after them.  The weight gradient splits the contraction over workgroups and adds
+// the partial products in a fixed order (Section 3.1: the sum over the minibatch).
+#include <stdio.h>
+
+#include "common.h"
+
+namespace {
+
+typedef float f32x16 __attribute__((ext_vector_type(16)));
+
+constexpr int KC = 32;
+constexpr int kFar = 1 << 24;     // a coordinate no image reaches: marks table entries and columns past the end
+enum { FWD = 0, BWD = 1, WGR = 2 };
+
+struct IgArgs {
+    int N, C, H, W, K, R, S, st, pad, P, Q;
+    int M, Nn, Kd;             // the GEMM's sizes: rows, columns, contraction
+    int k_per_split;
+    int relu;
+};
+
+// Backpropagation, one phase (a, b) of the stride: input rows h0 + st i (i < Hn) see kernel rows a + st r' (r' < Rn)
+// at output row hb + i - r'; columns alike.
+struct Phase {
+    int a, b, h0, w0, Hn, Wn, Rn, Sn, hb, wb;
+};
+__device__ __forceinline__ Phase make_phase(const IgArgs& g, int z) {
+    Phase f;
+    f.a = z / g.st; f.b = z - f.a * g.st;
+    f.h0 = ((f.a - g.pad) % g.st + g.st) % g.st;
+    f.w0 = ((f.b - g.pad) % g.st + g.st) % g.st;
+    f.Hn = f.h0 < g.H ? (g.H - f.h0 + g.st - 1) / g.st : 0;
+    f.Wn = f.w0 < g.W ? (g.W - f.w0 + g.st - 1) / g.st : 0;
+    f.Rn = f.a < g.R ? (g.R - f.a + g.st - 1) / g.st : 0;
+    f.Sn = f.b < g.S ? (g.S - f.b + g.st - 1) / g.st : 0;
+    f.hb = (f.h0 + g.pad - f.a) / g.st;
+    f.wb = (f.w0 + g.pad - f.b) / g.st;
+    return f;
+}
+
+struct Part {                  // one of the two parts of a gathered element's position
+    int off, a, b;
+};
+
+// Position along (c, r, s) or (k, r, s): its share of the element offset, and the kernel tap (r, s).
+template <int MODE>
+__device__ __forceinline__ Part tap_part(const IgArgs& g, const Phase& ph, int idx, int limit) {
+    Part t;
+    if (idx >= limit) {
+        t.off = 0; t.a = MODE == BWD ? kFar : -kFar; t.b = 0;
+        return t;
+    }
+    const int Sn = MODE == BWD ? ph.Sn : g.S;
+    const int RS = MODE == BWD ? ph.Rn * ph.Sn : g.R * g.S;
+    const int f = idx / RS, rs = idx - f * RS;
+    t.a = rs / Sn;
+    t.b = rs - t.a * Sn;
+    t.off = MODE == BWD ? f * g.P * g.Q : (f * g.H + t.a) * g.W + t.b;
+    return t;
+}
+
+// Position along (n, p, q) (forward, weight gradient: top-left input element of the window) or (n, h, w)
+// (backpropagation: the input element itself, shifted by the padding).
+template <int MODE>
+__device__ __forceinline__ Part pix_part(const IgArgs& g, const Phase& ph, int idx, int limit) {
+    Part t;
+    if (idx >= limit) {
+        t.off = 0; t.a = -kFar; t.b = 0;
+        return t;
+    }
+    if (MODE == BWD) {
+        const int HW = ph.Hn * ph.Wn;
+        const int n = idx / HW, hw = idx - n * HW;
+        const int i = hw / ph.Wn;
+        t.a = ph.hb + i;
+        t.b = ph.wb + (hw - i * ph.Wn);
+        t.off = n * g.K * g.P * g.Q;
+    } else {
+        const int PQ = g.P * g.Q;
+        const int n = idx / PQ, pq = idx - n * PQ;
+        const int p = pq / g.Q;
+        t.a = p * g.st - g.pad;
+        t.b = (pq - p * g.Q) * g.st - g.pad;
+        t.off = (n * g.C * g.H + t.a) * g.W + t.b;
+    }
+    return t;
+}
+
+// Offset of the gathered element, or -1 where it contributes 0.
+template <int MODE>
+__device__ __forceinline__ int gather_offset(const IgArgs& g, const Part& pix, const Part& tap) {
+    if (MODE == BWD) {
+        const int oh = pix.a - tap.a, ow = pix.b - tap.b;
+        const bool ok = (unsigned)oh < (unsigned)g.P && (unsigned)ow < (unsigned)g.Q;
+        return ok ? pix.off + tap.off + oh * g.Q + ow : -1;
+    }
+    const int h = pix.a + tap.a, w = pix.b + tap.b;
+    const bool ok = (unsigned)h < (unsigned)g.H && (unsigned)w < (unsigned)g.W;
+    return ok ? pix.off + tap.off : -1;
+}
+
+// First operand, element (row m, contraction index kk): offset = m * row_stride + k_part(kk).
+template <int MODE>
+__device__ __forceinline__ int a_row_stride(const IgArgs& g) {
+    return MODE == FWD ? g.Kd : MODE == BWD ? g.R * g.S : g.P * g.Q;
+}
+template <int MODE>
+__device__ __forceinline__ int a_k_part(const IgArgs& g, const Phase& ph, int kk) {
+    if (MODE == FWD) return kk;
+    if (MODE == BWD) {
+        const int RS = ph.Rn * ph.Sn, k = kk / RS, rs = kk - k * RS;
+        const int r = rs / ph.Sn, s = rs - r * ph.Sn;
+        return (k * g.C * g.R + ph.a + g.st * r) * g.S + ph.b + g.st * s;
+    }
+    const int PQ = g.P * g.Q, n = kk / PQ;
+    return n * g.K * PQ + (kk - n * PQ);
+}
+
+template <int MODE, int WMT, int WNT>
+__global__ void __launch_bounds__(256, 2)
+k_conv_igemm(IgArgs g, const float* __restrict__ Asrc, const float* __restrict__ Bsrc, const float* __restrict__ act,
+             GradSink sink) {
+    constexpr int TM = 64 * WMT, TN = 64 * WNT;
+    constexpr bool BKM = MODE != WGR;                       // second operand in LDS as [k][TN] (else [TN][KC+1])
+    constexpr int A_LDS = TM * (KC + 1);
+    constexpr int B_LDS = BKM ? KC * TN : TN * (KC + 1);
+    constexpr int BUF = A_LDS + B_LDS;
+    constexpr int NA = TM * KC / 256, NB = TN * KC / 256;   // elements per thread and chunk
+    constexpr int NTAB = BKM ? 2 * KC : TN;                 // table entries (two chunk tables, or one per column)
+    extern __shared__ __attribute__((aligned(16))) float lds[];     // two operand buffers, then the table
+    int* const tab_off = reinterpret_cast<int*>(lds + 2 * BUF);
+    int* const tab_a = tab_off + NTAB;
+    int* const tab_b = tab_a + NTAB;
+
+    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+    const int half = lane >> 5, l32 = lane & 31;
+    const int wm = wave & 1, wn = wave >> 1;
+    const int n0 = blockIdx.x * TN, m0 = blockIdx.y * TM;
+    // backpropagation: blockIdx.z is the stride phase, with its own column and contraction counts
+    Phase ph = {};
+    int Nn = g.Nn, k_begin = 0, k_end = g.Kd;
+    if (MODE == BWD) {
+        ph = make_phase(g, blockIdx.z);
+        Nn = g.N * ph.Hn * ph.Wn;
+        k_end = g.K * ph.Rn * ph.Sn;
+        if (n0 >= Nn) return;                               // the whole workgroup: no barrier has been reached
+    } else {
+        k_begin = blockIdx.z * g.k_per_split;
+        k_end = min(k_begin + g.k_per_split, g.Kd);
+    }
+    const int nchunks = (k_end - k_begin + KC - 1) / KC;
+
+    f32x16 acc[WMT][WNT];
+#pragma unroll
+    for (int i = 0; i < WMT; ++i)
+#pragma unroll
+        for (int j = 0; j < WNT; ++j)
+#pragma unroll
+            for (int v = 0; v < 16; ++v) acc[i][j][v] = 0.f;
+
+    // ---- staging: who fetches what
+    const int kq = tid & 31, rbase = tid >> 5;              // operands stored [row][KC+1]: fixed k, rows rbase + 8 i
+    const int a_rs = a_row_stride<MODE>(g);
+    const int bn = tid % TN, bk = tid / TN;                 // BKM: fixed column, k = bk + (256 / TN) i
+    Part fix;                                               // the thread's fixed part of the second operand
+    if (BKM) fix = pix_part<MODE>(g, ph, n0 + bn, Nn);
+
+    auto build_ktab = [&](int c) {                          // chunk c's table of contraction positions (BKM only)
+        if (BKM && tid < KC) {
+            const Part t = tap_part<MODE>(g, ph, k_begin + c * KC + tid, k_end);
+            const int e = (c & 1) * KC + tid;
+            tab_off[e] = t.off; tab_a[e] = t.a; tab_b[e] = t.b;
+        }
+    };
+    float ra[NA], rb[NB];
+    auto fetch = [&](int c) {
+        const int k0 = k_begin + c * KC;
+        {
+            const int kk = k0 + kq;
+            const bool kok = kk < k_end;
+            const int kp = a_k_part<MODE>(g, ph, kok ? kk : k_begin);
+#pragma unroll
+            for (int i = 0; i < NA; ++i) {
+                const int m = m0 + rbase + 8 * i;
+                const bool ok = kok && m < g.M;
+                const float v = Asrc[ok ? (size_t)(m * a_rs + kp) : 0];
+                ra[i] = ok ? v : 0.f;
+            }
+        }
+        if (BKM) {
+#pragma unroll
+            for (int i = 0; i < NB; ++i) {
+                const int e = (c & 1) * KC + bk + (256 / TN) * i;
+                Part t;
+                t.off = tab_off[e]; t.a = tab_a[e]; t.b = tab_b[e];
+                const int o = gather_offset<MODE>(g, fix, t);
+                const float v = Bsrc[o >= 0 ? (size_t)o : 0];
+                rb[i] = o >= 0 ? v : 0.f;
+            }
+        } else {
+            const Part px = pix_part<MODE>(g, ph, k0 + kq, k_end);
+#pragma unroll
+            for (int i = 0; i < NB; ++i) {
+                const int e = rbase + 8 * i;
+                Part t;
+                t.off = tab_off[e]; t.a = tab_a[e]; t.b = tab_b[e];
+                const int o = gather_offset<MODE>(g, px, t);
+                const float v = Bsrc[o >= 0 ? (size_t)o : 0];
+                rb[i] = o >= 0 ? v : 0.f;
+            }
+        }
+    };
+    auto stage = [&](int buf) {
+        float* la = lds + buf * BUF;
+        float* lb = la + A_LDS;
+#pragma unroll
+        for (int i = 0; i < NA; ++i) la[(rbase + 8 * i) * (KC + 1) + kq] = ra[i];
+        if (BKM) {
+#pragma unroll
+            for (int i = 0; i < NB; ++i) lb[(bk + (256 / TN) * i) * TN + bn] = rb[i];
+        } else {
+#pragma unroll
+            for (int i = 0; i < NB; ++i) lb[(rbase + 8 * i) * (KC + 1) + kq] = rb[i];
+        }
+    };
+
+    if (nchunks > 0) {
+        if (BKM) {
+            build_ktab(0);
+            if (nchunks > 1) build_ktab(1);
+        } else if (tid < TN) {
+            const Part t = tap_part<MODE>(g, ph, n0 + tid, Nn);
+            tab_off[tid] = t.off; tab_a[tid] = t.a; tab_b[tid] = t.b;
+        }
+        __syncthreads();
+        fetch(0);
+        stage(0);
+        __syncthreads();
+        constexpr int b_sr = BKM ? 1 : KC + 1, b_sk = BKM ? TN : 1;
+        for (int c = 0; c < nchunks; ++c) {
+            const bool more = c + 1 < nchunks;
+            if (more) fetch(c + 1);
+            const float* ap = lds + (c & 1) * BUF + (wm * WMT * 32 + l32) * (KC + 1) + half * (KC / 2);
+            const float* bp = lds + (c & 1) * BUF + A_LDS + (wn * WNT * 32 + l32) * b_sr + half * (KC / 2) * b_sk;
+#pragma unroll
+            for (int kk = 0; kk < KC / 2; ++kk) {
+                float a[WMT], b[WNT];
+#pragma unroll
+                for (int i = 0; i < WMT; ++i) a[i] = ap[i * 32 * (KC + 1) + kk];
+#pragma unroll
+                for (int j = 0; j < WNT; ++j) b[j] = bp[j * 32 * b_sr + kk * b_sk];
+#pragma unroll
+                for (int i = 0; i < WMT; ++i)
+#pragma unroll
+                    for (int j = 0; j < WNT; ++j)
+                        acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x2f32(a[i], b[j], acc[i][j], 0, 0, 0);
+            }
+            if (more) stage((c + 1) & 1);
+            if (c + 2 < nchunks) build_ktab(c + 2);
+            __syncthreads();
+        }
+    }
+
+    // ---- epilogue: lane = output column (contiguous in memory for all three passes)
+#pragma unroll
+    for (int j = 0; j < WNT; ++j) {
+        const int n = n0 + (wn * WNT + j) * 32 + l32;
+        const bool nok = n < Nn;
+        int col, rs_out;
+        if (MODE == WGR) {
+            col = n; rs_out = g.Nn;
+        } else if (MODE == FWD) {
+            const int plane = g.P * g.Q;
+            const int img = (nok ? n : 0) / plane;
+            col = img * g.M * plane + ((nok ? n : 0) - img * plane);
+            rs_out = plane;
+        } else {
+            const int plane = ph.Hn * ph.Wn;                // > 0: the workgroup has columns
+            const int img = (nok ? n : 0) / plane, hw = (nok ? n : 0) - img * plane;
+            const int i = hw / ph.Wn;
+            rs_out = g.H * g.W;
+            col = img * g.M * rs_out + (ph.h0 + g.st * i) * g.W + ph.w0 + g.st * (hw - i * ph.Wn);
+        }
+#pragma unroll
+        for (int i = 0; i < WMT; ++i) {
+            float mask[16];
+            if (MODE == BWD && act) {      // ReLU derivative of the layer below: all reads before the first store
+#pragma unroll
+                for (int v = 0; v < 16; ++v) {
+                    const int m = m0 + (wm * WMT + i) * 32 + 8 * (v / 4) + 4 * half + (v % 4);
+                    mask[v] = act[(nok && m < g.M) ? (size_t)(col + m * rs_out) : 0];
+                }
+            }
+#pragma unroll
+            for (int v = 0; v < 16; ++v) {
+                const int m = m0 + (wm * WMT + i) * 32 + 8 * (v / 4) + 4 * half + (v % 4);
+                if (!nok || m >= g.M) continue;
+                float r = acc[i][j][v];
+                if (MODE == FWD && g.relu) r = fmaxf(r, 0.f);
+                if (MODE == BWD && act) r = mask[v] > 0.f ? r : 0.f;
+                const size_t e = (size_t)(col + m * rs_out);
+                if (MODE == WGR) sink_store(sink, (size_t)blockIdx.z * g.M * g.Nn + e, r);
+                else sink.dw[e] = r;
+            }
+        }
+    }
+}
+
+// out (or the SGD step, sink) = sum over splits of partial[split][i], in split order
+__global__ void __launch_bounds__(256) k_igemm_reduce(int nsplit, size_t MN, const float* __restrict__ partial, GradSink sink) {
+    for (size_t i = blockIdx.x * (size_t)256 + threadIdx.x; i < MN; i += (size_t)gridDim.x * 256) {
+        float s0 = 0.f, s1 = 0.f;
+        int s = 0;
+        for (; s + 1 < nsplit; s += 2) {
+            s0 += partial[(size_t)s * MN + i];
+            s1 += partial[(size_t)(s + 1) * MN + i];
+        }
+        if (s < nsplit) s0 += partial[(size_t)s * MN + i];
+        sink_store(sink, i, s0 + s1);
+    }
+}
+
+struct IgPlan {
+    bool ok;
+    IgArgs a;
+    int tm, nsplit;
+    size_t ws_bytes;
+};
+
+IgPlan plan(int mode, const ConvShape& s) {
+    IgPlan p{};
+    p.ok = false;
+    const size_t lim = 0x7fff0000u;        // element offsets and column indices are 32-bit
+    const size_t nx = (size_t)s.N * s.C * s.H * s.W, ny = (size_t)s.N * s.K * s.P * s.Q, nw = (size_t)s.K * s.C * s.R * s.S;
+    if (nx == 0 || ny == 0 || nw == 0 || nx >= lim || ny >= lim || nw >= lim) return p;
+    // coordinates stay far below the marker for "outside"; one grid layer per stride phase
+    if (s.H + s.pad + s.R >= 65536 || s.W + s.pad + s.S >= 65536 || s.stride > 128) return p;
+    if ((size_t)s.P * s.stride + s.R >= 65536 || (size_t)s.Q * s.stride + s.S >= 65536) return p;
+    IgArgs& a = p.a;
+    a.N = s.N; a.C = s.C; a.H = s.H; a.W = s.W; a.K = s.K; a.R = s.R; a.S = s.S; a.st = s.stride; a.pad = s.pad;
+    a.P = s.P; a.Q = s.Q;
+    a.relu = 0;
+    size_t M, Nn, Kd;
+    if (mode == FWD) { M = s.K; Nn = (size_t)s.N * s.P * s.Q; Kd = (size_t)s.C * s.R * s.S; }
+    else if (mode == BWD) { M = s.C; Nn = (size_t)s.N * s.H * s.W; Kd = (size_t)s.K * s.R * s.S; }
+    else { M = s.K; Nn = (size_t)s.C * s.R * s.S; Kd = (size_t)s.N * s.P * s.Q; }
+    a.M = (int)M; a.Nn = (int)Nn; a.Kd = (int)Kd;
+    p.tm = M <= 64 ? 64 : 128;
+    const size_t tiles = ((M + p.tm - 1) / p.tm) * ((Nn + 127) / 128);
+    if ((Nn + 127) / 128 > 0x7fffffffu / 2) return p;
+    int want = 1;
+    if (mode == WGR && tiles < 256) want = (int)((512 + tiles - 1) / tiles);
+    const int chunks = (int)((Kd + KC - 1) / KC);
+    int max_split = chunks / 4;
+    if (max_split < 1) max_split = 1;
+    if (want > max_split) want = max_split;
+    const int cps = (chunks + want - 1) / want;
+    a.k_per_split = cps * KC;
+    p.nsplit = (int)((Kd + a.k_per_split - 1) / a.k_per_split);
+    p.ws_bytes = p.nsplit > 1 ? (size_t)p.nsplit * M * Nn * sizeof(float) : 0;
+    p.ok = true;
+    return p;
+}
+
+template <int MODE, int WMT>
+int launch(cnn_ctx* ctx, const IgPlan& p, const ConvShape& s, const float* A, const float* B, const float* act,
+           const GradSink& sink) {
+    constexpr int TM = 64 * WMT, TN = 128;
+    const IgArgs& a = p.a;
+    const GradSink first = p.nsplit > 1 ? sink_dw(reinterpret_cast<float*>(ctx->ws)) : sink;
+    // backpropagation: a layer of the grid per stride phase, each with at most ceil(H / st) x ceil(W / st) columns per image
+    const int hn = (s.H + s.stride - 1) / s.stride, wn = (s.W + s.stride - 1) / s.stride;
+    const size_t cols = MODE == BWD ? (size_t)s.N * hn * wn : (size_t)a.Nn;
+    dim3 grid((unsigned)((cols + TN - 1) / TN), (unsigned)((a.M + TM - 1) / TM),
+              (unsigned)(MODE == BWD ? s.stride * s.stride : p.nsplit));
+    constexpr int lds_bytes = (2 * (TM * (KC + 1) + (MODE != WGR ? KC * TN : TN * (KC + 1))) + 3 * (MODE != WGR ? 2 * KC : TN)) *
+                              (int)sizeof(float);
+    static bool attr_done = false;
+    if (!attr_done && lds_bytes > 48 * 1024) {
+        hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(&k_conv_igemm<MODE, WMT, 2>),
+                                           hipFuncAttributeMaxDynamicSharedMemorySize, lds_bytes);
+        if (e != hipSuccess) return cnn::hip_check(ctx, e, "hipFuncSetAttribute(conv_igemm)");
+        attr_done = true;
+    }
+    static char name[64] = "";
+    if (!name[0])
+        snprintf(name, sizeof(name), "k_conv_igemm<%s %dx%d>", MODE == FWD ? "fwd" : MODE == BWD ? "bwd" : "wgrad", TM, TN);
+    {
+        cnn::ProfScope ps(ctx, name, cnn::conv_flops(s));
+        hipLaunchKernelGGL((k_conv_igemm<MODE, WMT, 2>), grid, dim3(256), lds_bytes, ctx->stream, a, A, B, act, first);
+    }
+    int st = cnn::launch_check(ctx, "conv_igemm");
+    if (st != CNN_OK || p.nsplit == 1) return st;
+    const size_t MN = (size_t)a.M * a.Nn;
+    size_t gsz = (MN + 255) / 256;
+    if (gsz > 4096) gsz = 4096;
+    {
+        cnn::ProfScope ps(ctx, sink.w ? "k_igemm_reduce<sgd>" : "k_igemm_reduce", 0.0);
+        hipLaunchKernelGGL(k_igemm_reduce, dim3((unsigned)gsz), dim3(256), 0, ctx->stream, p.nsplit, MN, first.dw, sink);
+    }
+    return cnn::launch_check(ctx, "igemm_reduce");
+}
+
+}  // namespace
+
+namespace cnn {
+
+int igemm_conv_fwd(cnn_ctx* ctx, const ConvShape& s, const float* x, const float* w, float* y, int relu) {
+    IgPlan p = plan(FWD, s);
+    if (!p.ok) return CNN_EUNSUPPORTED;
+    p.a.relu = relu;
+    if (p.tm == 64) return launch<FWD, 1>(ctx, p, s, w, x, nullptr, sink_dw(y));
+    return launch<FWD, 2>(ctx, p, s, w, x, nullptr, sink_dw(y));
+}
+
+int igemm_conv_bwd_data(cnn_ctx* ctx, const ConvShape& s, const float* dy, const float* w, float* dx, const float* act) {
+    const IgPlan p = plan(BWD, s);
+    if (!p.ok) return CNN_EUNSUPPORTED;
+    if (p.tm == 64) return launch<BWD, 1>(ctx, p, s, w, dy, act, sink_dw(dx));
+    return launch<BWD, 2>(ctx, p, s, w, dy, act, sink_dw(dx));
+}
+
+size_t igemm_conv_bwd_weight_ws(const ConvShape& s) {
+    const IgPlan p = plan(WGR, s);
+    return p.ok ? p.ws_bytes : 0;
+}
+
+int igemm_conv_bwd_weight(cnn_ctx* ctx, const ConvShape& s, const float* x, const float* dy, const GradSink& sink) {
+    const IgPlan p = plan(WGR, s);
+    if (!p.ok) return CNN_EUNSUPPORTED;
+    if (p.ws_bytes && (!ctx->ws || ctx->ws_bytes < p.ws_bytes)) return CNN_EWORKSPACE;
+    if (p.tm == 64) return launch<WGR, 1>(ctx, p, s, dy, x, nullptr, sink);
+    return launch<WGR, 2>(ctx, p, s, dy, x, nullptr, sink);
+}
+
+}  // namespace cnn

@@ -147,8 +147,18 @@ def test_first_layer_7x7(cnn, ctx, case):
     P.check_contraction("dx", P.np_(dx), *oracle.conv_bwd_data(dy, w, H, H, stride, pad, with_abs=True))
 
 
-def test_conv_generic_shapes_fall_back_and_match(cnn, ctx):
-    # strides, rectangular images, 11x11/4 and 1x1: served by whichever kernel applies
+@pytest.mark.parametrize("force_direct", [0, 1])
+def test_conv_generic_shapes_fall_back_and_match(cnn, ctx, force_direct):
+    # strides, rectangular images, 11x11/4 and 1x1: served by whichever kernel applies; with force_direct by the
+    # plain one-thread-per-output kernels
+    ctx.set_option(cnn.OPT_FORCE_DIRECT, force_direct)
+    try:
+        _generic_shapes(cnn, ctx)
+    finally:
+        ctx.set_option(cnn.OPT_FORCE_DIRECT, 0)
+
+
+def _generic_shapes(cnn, ctx):
     for (N, C, H, W, K, R, S, st, pad) in [(2, 3, 39, 39, 8, 11, 11, 4, 0), (1, 5, 9, 13, 7, 3, 2, 2, 1),
                                            (2, 4, 6, 6, 4, 1, 1, 1, 0), (1, 3, 224, 224, 8, 3, 3, 1, 1),
                                            (2, 3, 224, 224, 64, 3, 3, 1, 1), (3, 3, 231, 231, 96, 11, 11, 4, 0),
@@ -165,6 +175,43 @@ def test_conv_generic_shapes_fall_back_and_match(cnn, ctx):
         P.check_contraction("y", P.np_(y), *oracle.conv_fwd(x, w, st, pad, with_abs=True))
         P.check_contraction("dx", P.np_(dx), *oracle.conv_bwd_data(dy, w, H, W, st, pad, with_abs=True))
         P.check_contraction("dw", P.np_(dw), *oracle.conv_bwd_weight(x, dy, R, S, st, pad, with_abs=True))
+
+
+# (N, C, H, W, K, R, S, stride, pad): what only the implicit GEMM serves on the matrix cores. 1x1 (plain and strided),
+# 3x3 / 5x5 strided with many input features (backpropagation and weight gradient), rectangular and even-sized
+# kernels, 9x9, stride 3 and 4 with padding, tiles ragged in every dimension, a contraction shorter than one chunk
+IGEMM_CASES = [(2, 256, 28, 28, 512, 1, 1, 1, 0), (3, 64, 56, 56, 128, 3, 3, 2, 1), (2, 96, 27, 27, 40, 1, 1, 2, 0),
+               (2, 32, 30, 22, 72, 1, 7, 1, 3), (2, 24, 22, 30, 136, 7, 1, 1, 0), (2, 16, 20, 20, 33, 9, 9, 1, 4),
+               (3, 20, 17, 23, 70, 2, 2, 2, 0), (2, 40, 33, 31, 64, 4, 4, 4, 2), (1, 130, 19, 19, 200, 3, 3, 3, 1),
+               (2, 128, 28, 28, 256, 5, 5, 2, 2), (1, 5, 6, 6, 3, 2, 3, 1, 1), (65, 8, 9, 9, 16, 3, 2, 2, 1)]
+
+
+@pytest.mark.parametrize("case", IGEMM_CASES)
+def test_conv_implicit_gemm_shapes(cnn, ctx, case):
+    # the three passes, the ReLU forms of forward and backpropagation (bit-identical to the unfused sequence), and the
+    # weight gradient with the SGD step folded in (bit-identical to gradient + update)
+    N, C, H, W, K, R, S, st, pad = case
+    say("implicit GEMM case", case)
+    x = np.maximum(synth.randn(84, 1, (N, C, H, W)), 0).astype(np.float32)
+    w = synth.randn(84, 2, (K, C, R, S), 0.2)
+    y = cnn.cnn_conv_fwd(ctx, dev(x), dev(w), st, pad)
+    dy = synth.randn(84, 3, tuple(y.shape))
+    dx = cnn.cnn_conv_bwd_data(ctx, dev(dy), dev(w), H, W, st, pad)
+    dw = cnn.cnn_conv_bwd_weight(ctx, dev(x), dev(dy), R, S, st, pad)
+    a = cnn.cnn_conv_fwd_relu(ctx, dev(x), dev(w), st, pad)
+    dz = cnn.cnn_conv_bwd_data_relu(ctx, dev(dy), dev(w), dev(x), st, pad)
+    w0 = synth.randn(84, 4, (K, C, R, S), 0.05); v0 = synth.randn(84, 5, (K, C, R, S), 0.5)
+    w1, v1 = dev(w0), dev(v0)
+    assert cnn.cnn_conv_bwd_weight_sgd(ctx, dev(x), dev(dy), w1, v1, st, pad, 0.02, 0.9) is not None
+    w2, v2 = dev(w0), dev(v0)
+    cnn.cnn_sgd_update(ctx, w2.view(-1), dw.view(-1), v2.view(-1), 0.02, 0.9)
+    torch.cuda.synchronize()
+    P.check_contraction("y", P.np_(y), *oracle.conv_fwd(x, w, st, pad, with_abs=True))
+    P.check_contraction("dx", P.np_(dx), *oracle.conv_bwd_data(dy, w, H, W, st, pad, with_abs=True))
+    P.check_contraction("dw", P.np_(dw), *oracle.conv_bwd_weight(x, dy, R, S, st, pad, with_abs=True))
+    assert torch.equal(a, cnn.cnn_relu_fwd(ctx, y))
+    assert torch.equal(dz, cnn.cnn_relu_bwd(ctx, dev(x), dx))
+    assert torch.equal(w1, w2) and torch.equal(v1, v2)
 
 
 def test_conv_degenerate_shapes(cnn, ctx):
@@ -314,7 +361,11 @@ def test_conv_weight_gradient_with_the_sgd_step_folded_in(cnn, ctx, case):
 def test_folded_sgd_refuses_what_only_the_plain_kernels_serve(cnn, ctx):
     x = dev(synth.randn(95, 5, (2, 5, 9, 9))); dy = dev(synth.randn(95, 6, (2, 7, 9, 9)))
     w0 = synth.randn(95, 7, (7, 5, 3, 3)); w = dev(w0)
-    assert cnn.cnn_conv_bwd_weight_sgd(ctx, x, dy, w, None, 1, 1, 0.1, 0.0) is None
+    ctx.set_option(cnn.OPT_FORCE_DIRECT, 1)
+    try:
+        assert cnn.cnn_conv_bwd_weight_sgd(ctx, x, dy, w, None, 1, 1, 0.1, 0.0) is None
+    finally:
+        ctx.set_option(cnn.OPT_FORCE_DIRECT, 0)
     xf = dev(synth.randn(95, 8, (5, 6))); dyf = dev(synth.randn(95, 9, (5, 10)))     # I % 4 != 0
     wf0 = synth.randn(95, 10, (10, 6)); wf = dev(wf0)
     dxf = torch.full((5, 6), 7.0, device="cuda")
