@@ -50,11 +50,13 @@ def test_validation_rejects_before_any_launch(L):
         assert L.cnn_fc_bwd(h, 4, 8, 8, p, p, None, p, p) == -1
         assert L.cnn_fc_bwd(h, 4, 8, 8, None, p, p, None, p) == -1          # dw asked for without x
         assert L.cnn_sgd_update(h, 0, p, p, None, 0.1, 0.0) == -1
-        # weight gradient folded into the update: null w, bad dims; shapes only the plain kernels serve are refused
+        # weight gradient folded into the update: null w, bad dims; with the plain kernels forced the call is refused
         # (-2) before anything is launched; a tiled shape without a workspace is -3
         assert L.cnn_conv_bwd_weight_sgd(h, 1, 1, 4, 4, 1, 3, 3, 1, 1, p, p, None, None, 0.1, 0.0) == -1
         assert L.cnn_conv_bwd_weight_sgd(h, 1, 1, 4, 4, 1, 3, 3, 0, 1, p, p, p, None, 0.1, 0.0) == -1
+        assert L.cnn_set_option(h, 0, 1) == 0
         assert L.cnn_conv_bwd_weight_sgd(h, 2, 5, 9, 9, 7, 3, 3, 1, 1, p, p, p, None, 0.1, 0.0) == -2
+        assert L.cnn_set_option(h, 0, 0) == 0
         assert L.cnn_conv_bwd_weight_sgd(h, 4, 64, 56, 56, 64, 3, 3, 1, 1, p, p, p, p, 0.1, 0.9) == -3
         assert L.cnn_fc_bwd_sgd(h, 4, 8, 8, None, p, p, p, None, 0.1, 0.0) == -1
         assert L.cnn_fc_bwd_sgd(h, 4, 8, 0, p, p, p, p, None, 0.1, 0.0) == -1
