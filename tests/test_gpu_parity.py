@@ -214,6 +214,36 @@ def test_conv_implicit_gemm_shapes(cnn, ctx, case):
     assert torch.equal(w1, w2) and torch.equal(v1, v2)
 
 
+def test_conv_tensors_beyond_two_gib(cnn, ctx):
+    # an input of 2^29 + elements (byte offsets past 2^31): element offsets inside the kernels are 32-bit, byte
+    # offsets must not be; a 3x3 layer (small output) and a 1x1 layer whose output is as large as its input;
+    # sampled outputs, the first and the last element always among them
+    N, C, H, W = 1, 32, 4100, 4100
+    say("large tensor: generating", (N, C, H, W))
+    x = synth.randn(83, 1, (N, C, H, W))
+    xd = dev(x)
+    for (K, R, pad) in [(8, 3, 1), (32, 1, 0)]:
+        say("large tensor case", (N, C, H, W, K, R, pad))
+        w = synth.randn(83, 2, (K, C, R, R), 0.2)
+        dy = synth.randn(83, 3, (N, K, H, W))
+        dyd, wd = dev(dy), dev(w)
+        y = cnn.cnn_conv_fwd(ctx, xd, wd, 1, pad)
+        dx = cnn.cnn_conv_bwd_data(ctx, dyd, wd, H, W, 1, pad)
+        dw = cnn.cnn_conv_bwd_weight(ctx, xd, dyd, R, R, 1, pad)
+        torch.cuda.synchronize()
+        say("  checking")
+        idx = np.unique(np.concatenate([P.sample(83, 10, y.numel(), 20000), [0, y.numel() - 1]]))
+        ref, sabs = oracle.conv_fwd_at(x, w, idx, 1, pad)
+        P.check_contraction("y", P.np_(y).ravel()[idx], ref, sabs)
+        idx = np.unique(np.concatenate([P.sample(83, 11, dx.numel(), 20000), [0, dx.numel() - 1]]))
+        ref, sabs = oracle.conv_bwd_data_at(dy, w, H, W, idx, 1, pad)
+        P.check_contraction("dx", P.np_(dx).ravel()[idx], ref, sabs)
+        idx = P.sample(83, 12, dw.numel(), 48)
+        ref, sabs = oracle.conv_bwd_weight_at(x, dy, R, R, idx, 1, pad)
+        P.check_contraction("dw", P.np_(dw).ravel()[idx], ref, sabs)
+        del y, dx, dw, dyd
+
+
 def test_conv_degenerate_shapes(cnn, ctx):
     # images of one pixel / one row / smaller than the kernel's reach, a single feature on either side, padding
     # beyond the kernel (outputs that see only zeros), a ragged 513-feature layer, one image
