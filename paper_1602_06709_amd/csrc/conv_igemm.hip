@@ -107,11 +107,11 @@ template <int MODE>
 __device__ __forceinline__ int gather_offset(const IgArgs& g, const Part& pix, const Part& tap) {
     if (MODE == BWD) {
         const int oh = pix.a - tap.a, ow = pix.b - tap.b;
-        const bool ok = (unsigned)oh < (unsigned)g.P && (unsigned)ow < (unsigned)g.Q;
+        const bool ok = ((unsigned)oh < (unsigned)g.P) & ((unsigned)ow < (unsigned)g.Q);
         return ok ? pix.off + tap.off + oh * g.Q + ow : -1;
     }
     const int h = pix.a + tap.a, w = pix.b + tap.b;
-    const bool ok = (unsigned)h < (unsigned)g.H && (unsigned)w < (unsigned)g.W;
+    const bool ok = ((unsigned)h < (unsigned)g.H) & ((unsigned)w < (unsigned)g.W);
     return ok ? pix.off + tap.off : -1;
 }
 
@@ -144,9 +144,7 @@ k_conv_igemm(IgArgs g, const float* __restrict__ Asrc, const float* __restrict__
     constexpr int NA = TM * KC / 256, NB = TN * KC / 256;   // elements per thread and chunk
     constexpr int NTAB = BKM ? 2 * KC : TN;                 // table entries (two chunk tables, or one per column)
     extern __shared__ __attribute__((aligned(16))) float lds[];     // two operand buffers, then the table
-    int* const tab_off = reinterpret_cast<int*>(lds + 2 * BUF);
-    int* const tab_a = tab_off + NTAB;
-    int* const tab_b = tab_a + NTAB;
+    int4* const tab = reinterpret_cast<int4*>(lds + 2 * BUF);       // (off, a, b, -) per entry: one 16-byte read
 
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
     const int half = lane >> 5, l32 = lane & 31;
@@ -184,12 +182,15 @@ k_conv_igemm(IgArgs g, const float* __restrict__ Asrc, const float* __restrict__
     auto build_ktab = [&](int c) {                          // chunk c's table of contraction positions (BKM only)
         if (BKM && tid < KC) {
             const Part t = tap_part<MODE>(g, ph, k_begin + c * KC + tid, k_end);
-            const int e = (c & 1) * KC + tid;
-            tab_off[e] = t.off; tab_a[e] = t.a; tab_b[e] = t.b;
+            tab[(c & 1) * KC + tid] = make_int4(t.off, t.a, t.b, 0);
         }
     };
+    // fetched elements and, one bit each, whether they count: the selection happens when they go to LDS, so that no
+    // load has a consumer before the chunk's MFMAs (a select right behind each load makes the compiler wait for it)
     float ra[NA], rb[NB];
+    unsigned oka = 0, okb = 0;
     auto fetch = [&](int c) {
+        oka = 0; okb = 0;
         const int k0 = k_begin + c * KC;
         {
             const int kk = k0 + kq;
@@ -198,31 +199,28 @@ k_conv_igemm(IgArgs g, const float* __restrict__ Asrc, const float* __restrict__
 #pragma unroll
             for (int i = 0; i < NA; ++i) {
                 const int m = m0 + rbase + 8 * i;
-                const bool ok = kok && m < g.M;
-                const float v = Asrc[ok ? (size_t)(m * a_rs + kp) : 0];
-                ra[i] = ok ? v : 0.f;
+                const bool ok = kok & (m < g.M);
+                ra[i] = Asrc[ok ? (size_t)(m * a_rs + kp) : 0];
+                oka |= (unsigned)ok << i;
             }
         }
-        if (BKM) {
+        // table entries four at a time, every read issued before its first use (a read behind a comparison would
+        // expose the LDS latency once per element)
+        Part px = fix;
+        if (!BKM) px = pix_part<MODE>(g, ph, k0 + kq, k_end);
 #pragma unroll
-            for (int i = 0; i < NB; ++i) {
-                const int e = (c & 1) * KC + bk + (256 / TN) * i;
-                Part t;
-                t.off = tab_off[e]; t.a = tab_a[e]; t.b = tab_b[e];
-                const int o = gather_offset<MODE>(g, fix, t);
-                const float v = Bsrc[o >= 0 ? (size_t)o : 0];
-                rb[i] = o >= 0 ? v : 0.f;
-            }
-        } else {
-            const Part px = pix_part<MODE>(g, ph, k0 + kq, k_end);
+        for (int i0 = 0; i0 < NB; i0 += 4) {
+            int4 t4[4];
 #pragma unroll
-            for (int i = 0; i < NB; ++i) {
-                const int e = rbase + 8 * i;
+            for (int u = 0; u < 4; ++u)
+                t4[u] = tab[BKM ? (c & 1) * KC + bk + (256 / TN) * (i0 + u) : rbase + 8 * (i0 + u)];
+#pragma unroll
+            for (int u = 0; u < 4; ++u) {
                 Part t;
-                t.off = tab_off[e]; t.a = tab_a[e]; t.b = tab_b[e];
+                t.off = t4[u].x; t.a = t4[u].y; t.b = t4[u].z;
                 const int o = gather_offset<MODE>(g, px, t);
-                const float v = Bsrc[o >= 0 ? (size_t)o : 0];
-                rb[i] = o >= 0 ? v : 0.f;
+                rb[i0 + u] = Bsrc[o >= 0 ? (size_t)o : 0];
+                okb |= (unsigned)(o >= 0) << (i0 + u);
             }
         }
     };
@@ -230,13 +228,13 @@ k_conv_igemm(IgArgs g, const float* __restrict__ Asrc, const float* __restrict__
         float* la = lds + buf * BUF;
         float* lb = la + A_LDS;
 #pragma unroll
-        for (int i = 0; i < NA; ++i) la[(rbase + 8 * i) * (KC + 1) + kq] = ra[i];
+        for (int i = 0; i < NA; ++i) la[(rbase + 8 * i) * (KC + 1) + kq] = (oka >> i) & 1 ? ra[i] : 0.f;
         if (BKM) {
 #pragma unroll
-            for (int i = 0; i < NB; ++i) lb[(bk + (256 / TN) * i) * TN + bn] = rb[i];
+            for (int i = 0; i < NB; ++i) lb[(bk + (256 / TN) * i) * TN + bn] = (okb >> i) & 1 ? rb[i] : 0.f;
         } else {
 #pragma unroll
-            for (int i = 0; i < NB; ++i) lb[(rbase + 8 * i) * (KC + 1) + kq] = rb[i];
+            for (int i = 0; i < NB; ++i) lb[(rbase + 8 * i) * (KC + 1) + kq] = (okb >> i) & 1 ? rb[i] : 0.f;
         }
     };
 
@@ -246,7 +244,7 @@ k_conv_igemm(IgArgs g, const float* __restrict__ Asrc, const float* __restrict__
             if (nchunks > 1) build_ktab(1);
         } else if (tid < TN) {
             const Part t = tap_part<MODE>(g, ph, n0 + tid, Nn);
-            tab_off[tid] = t.off; tab_a[tid] = t.a; tab_b[tid] = t.b;
+            tab[tid] = make_int4(t.off, t.a, t.b, 0);
         }
         __syncthreads();
         fetch(0);
@@ -389,7 +387,7 @@ int launch(cnn_ctx* ctx, const IgPlan& p, const ConvShape& s, const float* A, co
     const size_t cols = MODE == BWD ? (size_t)s.N * hn * wn : (size_t)a.Nn;
     dim3 grid((unsigned)((cols + TN - 1) / TN), (unsigned)((a.M + TM - 1) / TM),
               (unsigned)(MODE == BWD ? s.stride * s.stride : p.nsplit));
-    constexpr int lds_bytes = (2 * (TM * (KC + 1) + (MODE != WGR ? KC * TN : TN * (KC + 1))) + 3 * (MODE != WGR ? 2 * KC : TN)) *
+    constexpr int lds_bytes = (2 * (TM * (KC + 1) + (MODE != WGR ? KC * TN : TN * (KC + 1))) + 4 * (MODE != WGR ? 2 * KC : TN)) *
                               (int)sizeof(float);
     static bool attr_done = false;
     if (!attr_done && lds_bytes > 48 * 1024) {
