@@ -679,6 +679,9 @@ const Variant kVariants[] = {
     // 3x3, any strides: 128-feature tiles (4 waves) and 64-feature tiles (2 waves), 7 / 8 / 9 pixel blocks per wave
     V(3, 3, 4, 4, 1, 7, 4, 2, 3, 0, 0), V(3, 3, 4, 4, 1, 8, 4, 2, 1, 0, 0), V(3, 3, 4, 4, 1, 9, 4, 2, 1, 0, 0),
     V(3, 3, 4, 2, 1, 7, 4, 4, 3, 0, 0), V(3, 3, 4, 2, 1, 8, 4, 4, 1, 0, 0),
+    // 64 features x two wave columns: four waves for grids of at most one workgroup per compute unit, where a
+    // two-wave workgroup leaves half the SIMDs idle (small minibatches)
+    V(3, 3, 4, 2, 2, 4, 4, 4, 3, 0, 0),
     // 3x3 with fewer than 4 contraction channels (first layers)
     V(3, 3, 4, 2, 2, 7, 1, 4, 1, 0, 0),
     // 5x5: 64-feature tiles, two wave columns
@@ -755,6 +758,8 @@ bool make_plan(int R, int S, int pad, int stride, int N, int J, int M, int HI, i
                 double score = eff * (lds_bytes <= 78 * 1024 ? 1.0 : 0.9) * (padded || stride != 1 ? 1.0 : 0.97);
                 score *= 1.0 - 0.3 * (double)(THI - TR * stride) / THI;
                 if (v.wldp) score *= 1.03;                          // operand offsets are immediates
+                // a two-wave workgroup alone on its compute unit (grid within one round) uses two of the four SIMDs
+                if (v.threads == 128 && (long)ptiles * ((M + v.mb - 1) / v.mb) <= 256) score *= 0.55;
                 {
                     // a grid that cannot fill the chip even with every unit sliced as far as allowed takes as long
                     // as one of its workgroups: then the smaller pixel tile wins, not the better filled one
