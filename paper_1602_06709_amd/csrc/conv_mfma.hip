@@ -68,6 +68,11 @@ struct ConvGeo {
     // blockIdx.x is slice blockIdx.x % nsl of unit blockIdx.x / nsl, units numbered (pixel tile, feature tile); the
     // hardware's round-robin then spreads them over all XCDs instead of leaving some without work.
     int flat;
+    // sk_share != 0 (a grid within one round that uniform slices cannot spread evenly, e.g. 224 units on 256 compute
+    // units): the chunks of all units, laid end to end, are dealt out in equal runs of sk_share chunks, one run per
+    // workgroup.  A run may end one unit and begin the next; every piece goes to the scratch buffer (at most sk_pmax
+    // pieces per unit, numbered by the workgroups that touch it) and k_tile_reduce adds them in that order.
+    int sk_share, sk_pmax, sk_nchunks;
     int epi;
     int lds_buf;                   // elements of one (filter tile, input tile) buffer
 };
@@ -99,7 +104,7 @@ struct ConvCfg {
 constexpr int kOutOfRange = (int)0x80000000;   // buffer-load byte offset beyond any descriptor used here -> reads 0
 constexpr int kRsrcWord3 = 0x00020000;         // raw buffer descriptor of 32-bit elements
 
-template <class G>
+template <class G, bool SK>
 __global__ void __launch_bounds__(G::T, 2)
 k_conv_tiled(ConvGeo g, const float* __restrict__ in, const float* __restrict__ wt, const float* __restrict__ aux,
              float* __restrict__ out_base, float* __restrict__ partial, unsigned char* arg_out) {
@@ -119,9 +124,31 @@ k_conv_tiled(ConvGeo g, const float* __restrict__ in, const float* __restrict__ 
     // Workgroups are handed to the 8 XCDs round-robin by linear id.  Give each XCD (its own L2) a contiguous range
     // of pixel tiles and run the output-feature tiles of one pixel tile back to back on it, so the input tile, and
     // the halo rows it shares with the next tile, come from HBM once instead of once per feature tile.
+    // SK: this workgroup's run of chunks [sk_c0, sk_c1) of the end-to-end numbering, spanning `parts` units
+    const int nchunks = (J + CB - 1) / CB;
+    int sk_c0 = 0, sk_c1 = 0, sk_first = 0, parts = 1;
+    if (SK) {
+        const int total = g.ptiles * g.mtiles * nchunks;
+        sk_c0 = blockIdx.x * g.sk_share;
+        if (sk_c0 >= total) return;
+        sk_c1 = min(sk_c0 + g.sk_share, total);
+        sk_first = sk_c0 / nchunks;
+        parts = (sk_c1 - 1) / nchunks - sk_first + 1;
+    }
+    for (int part = 0; part < parts; ++part) {
     int ptile, m0, slice = -1;
     size_t tix;                          // index of a sliced unit's partial tiles in the scratch buffer
-    if (g.flat) {
+    int ch_begin = 0, ch_end = nchunks;
+    if (SK) {
+        const int ul = sk_first + part;
+        ptile = ul / g.mtiles;
+        m0 = (ul % g.mtiles) * G::MB;
+        tix = ul;
+        ch_begin = part == 0 ? sk_c0 - ul * nchunks : 0;
+        ch_end = min(sk_c1 - ul * nchunks, nchunks);
+        slice = blockIdx.x - (ul * nchunks) / g.sk_share;      // this piece's number among the unit's pieces
+        if (part) __syncthreads();                               // the previous unit's operands are no longer read
+    } else if (g.flat) {
         const int ul = blockIdx.x / g.nsl;
         if (g.nsl > 1) slice = blockIdx.x % g.nsl;
         ptile = ul / g.mtiles;
@@ -280,9 +307,10 @@ k_conv_tiled(ConvGeo g, const float* __restrict__ in, const float* __restrict__ 
     // behind it while those MFMAs run.  The last iterations stage and fetch a clamped chunk again instead of
     // branching (harmless: that buffer is never read for results), which keeps the chunk body one basic block.
     // A tail workgroup (slice >= 0) covers only its slice of the contraction and writes a partial tile.
-    const int nchunks = (J + CB - 1) / CB;
-    const int ch_begin = slice < 0 ? 0 : slice * g.chunks_per_slice;
-    const int ch_end = slice < 0 ? nchunks : min(ch_begin + g.chunks_per_slice, nchunks);
+    if (!SK && slice >= 0) {
+        ch_begin = slice * g.chunks_per_slice;
+        ch_end = min(ch_begin + g.chunks_per_slice, nchunks);
+    }
     const size_t out_plane = (size_t)g.HO * g.WO;
     constexpr int NSEG = G::NSEG, IPS = (NITEMS + NSEG - 1) / NSEG;
     // fewer channels than one chunk (VEC == 1: first layers): the whole contraction is this one chunk, nothing is
@@ -370,10 +398,10 @@ k_conv_tiled(ConvGeo g, const float* __restrict__ in, const float* __restrict__ 
     }
 
     // ---- epilogue: lane = pixel (coalesced along the row), register v = output feature
-    if (slice >= 0) {
+    if (SK || slice >= 0) {              // (SK: every piece is partial; the other epilogues are compiled out)
         // partial tile [MB][NPIXB] of tail unit (xcd, unit - full_per_xcd), slice `slice`; no guards: the scratch
         // buffer holds whole tiles and the reduction skips what lies outside the tensor
-        float* po = partial + (tix * g.nsl + slice) * (size_t)(G::MB * G::NPIXB);
+        float* po = partial + (tix * (SK ? g.sk_pmax : g.nsl) + slice) * (size_t)(G::MB * G::NPIXB);
 #pragma unroll
         for (int j = 0; j < NT; ++j) {
             const int i = (wn * NT + j) * 32 + l32;
@@ -383,6 +411,7 @@ k_conv_tiled(ConvGeo g, const float* __restrict__ in, const float* __restrict__ 
                 po[(size_t)m * G::NPIXB + i] = acc[j][v];
             }
         }
+        if (SK) continue;                // on to the piece of the next unit
         return;
     }
     if (g.epi == EPI_POOL) {
@@ -524,6 +553,7 @@ k_conv_tiled(ConvGeo g, const float* __restrict__ in, const float* __restrict__ 
             }
         }
     }
+    }   // pieces (one pass unless SK; an SK piece never gets here: it leaves through the partial-tile store)
 }
 
 // wT[c][k][r][s] = w[k][c][R-1-r][S-1-s]: the "transpose-weights" of Section 2.3 with the taps mirrored, so that
@@ -579,6 +609,13 @@ __global__ void __launch_bounds__(256) k_tile_reduce(ConvGeo g, int MB, int cap,
     const int row0 = ptile * g.TR, nrows = g.N * g.HO;
     const size_t out_plane = (size_t)g.HO * g.WO, tile = (size_t)MB * cap;
     const float* pt = partial + (size_t)blockIdx.x * g.nsl * tile;
+    int nsl = g.nsl;
+    if (g.sk_share) {
+        // the pieces of unit blockIdx.x: one per workgroup whose run of chunks touches it
+        const int u = blockIdx.x;
+        nsl = ((u + 1) * g.sk_nchunks - 1) / g.sk_share - (u * g.sk_nchunks) / g.sk_share + 1;
+        pt = partial + (size_t)u * g.sk_pmax * tile;
+    }
     if (g.epi == EPI_POOL) {
         // ReLU + 2x2 max-pool of the summed tile: one thread per pooled element (window order: row-major, first
         // maximum wins, as in the stand-alone pooling kernel)
@@ -591,7 +628,7 @@ __global__ void __launch_bounds__(256) k_tile_reduce(ConvGeo g, int MB, int cap,
             int idx = 0;
             for (int w4 = 0; w4 < 4; ++w4) {
                 const int i = (2 * pr + w4 / 2) * g.WO + 2 * pq + (w4 & 1);
-                float r = slice_sum(pt + (size_t)ml * cap + i, tile, g.nsl);
+                float r = slice_sum(pt + (size_t)ml * cap + i, tile, nsl);
                 r = r > 0.f ? r : 0.f;
                 if (w4 == 0 || r > best) { best = r; idx = w4; }
             }
@@ -601,11 +638,57 @@ __global__ void __launch_bounds__(256) k_tile_reduce(ConvGeo g, int MB, int cap,
         }
         return;
     }
+    if (out_plane % 4 == 0 && g.NPIX % 4 == 0) {
+        // four consecutive pixels of a tile are four consecutive, 16-byte aligned elements of one output plane
+        // (tiles and images start at multiples of four pixels): everything moves as float4; same order of additions
+        typedef float f4 __attribute__((ext_vector_type(4)));
+        const int c4 = cap / 4;
+        const size_t lin0 = (size_t)row0 * g.WO, lin_end = (size_t)nrows * g.WO;
+        for (int e = threadIdx.x; e < 8 * c4; e += 256) {
+            const int ml = blockIdx.y * 8 + e / c4, i = (e % c4) * 4;
+            if (i >= g.NPIX || lin0 + i >= lin_end || m0 + ml >= g.M) continue;
+            const float* ps = pt + (size_t)ml * cap + i;
+            f4 r = *reinterpret_cast<const f4*>(ps);
+            if (nsl == 2) {
+                r += *reinterpret_cast<const f4*>(ps + tile);
+            } else if (nsl == 3) {
+                const f4 a1 = *reinterpret_cast<const f4*>(ps + tile), a2 = *reinterpret_cast<const f4*>(ps + 2 * tile);
+                r = (r + a1) + a2;
+            } else {
+                for (int sl = 1; sl < nsl; ++sl) r += *reinterpret_cast<const f4*>(ps + (size_t)sl * tile);
+            }
+            const size_t lin = lin0 + i, plane = (lin / out_plane) * g.M + m0 + ml, rem = lin % out_plane;
+            const size_t o = plane * out_plane + rem;
+            if (g.epi == EPI_UNPOOL) {
+                const f4 a = *reinterpret_cast<const f4*>(aux + o);
+                const int ps4[4] = {arg_out[o], arg_out[o + 1], arg_out[o + 2], arg_out[o + 3]};
+#pragma unroll
+                for (int t = 0; t < 4; ++t) {
+                    const float v = a[t] > 0.f ? r[t] : 0.f;
+                    const size_t q = rem + t;
+                    float* d = out + plane * 4 * out_plane + (q / g.WO) * (size_t)(4 * g.WO) + 2 * (q % g.WO);
+                    d[0] = ps4[t] == 0 ? v : 0.f; d[1] = ps4[t] == 1 ? v : 0.f;
+                    d[2 * g.WO] = ps4[t] == 2 ? v : 0.f; d[2 * g.WO + 1] = ps4[t] == 3 ? v : 0.f;
+                }
+                continue;
+            }
+            if (g.epi == EPI_RELU) {
+#pragma unroll
+                for (int t = 0; t < 4; ++t) r[t] = r[t] > 0.f ? r[t] : 0.f;
+            } else if (g.epi == EPI_MASK) {
+                const f4 a = *reinterpret_cast<const f4*>(aux + o);
+#pragma unroll
+                for (int t = 0; t < 4; ++t) r[t] = a[t] > 0.f ? r[t] : 0.f;
+            }
+            *reinterpret_cast<f4*>(out + o) = r;
+        }
+        return;
+    }
     for (int e = threadIdx.x; e < 8 * cap; e += 256) {
         const int ml = blockIdx.y * 8 + e / cap, i = e % cap;
         const int orow = row0 + i / g.WO;
         if (i >= g.NPIX || orow >= nrows || m0 + ml >= g.M) continue;
-        float r = slice_sum(pt + (size_t)ml * cap + i, tile, g.nsl);
+        float r = slice_sum(pt + (size_t)ml * cap + i, tile, nsl);
         if (g.epi == EPI_UNPOOL) {
             const size_t plane = (size_t)(orow / g.HO) * g.M + m0 + ml;
             const size_t o = plane * out_plane + (size_t)(orow % g.HO) * g.WO + i % g.WO;
@@ -634,14 +717,23 @@ typedef int (*LaunchFn)(cnn_ctx*, const LaunchArgs&);
 
 template <class G>
 int launch(cnn_ctx* ctx, const LaunchArgs& a) {
+    constexpr bool kHasSK = G::R == 3 && G::VEC == 4 && G::WM == 4;      // instantiations the planner may run this way
     static size_t attr_bytes = 48 * 1024;
     if (a.lds_bytes > attr_bytes) {
-        hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(&k_conv_tiled<G>),
+        hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(&k_conv_tiled<G, false>),
                                            hipFuncAttributeMaxDynamicSharedMemorySize, (int)a.lds_bytes);
+        if (e == hipSuccess && kHasSK)
+            e = hipFuncSetAttribute(reinterpret_cast<const void*>(&k_conv_tiled<G, kHasSK>),
+                                    hipFuncAttributeMaxDynamicSharedMemorySize, (int)a.lds_bytes);
         if (e != hipSuccess) return cnn::hip_check(ctx, e, "hipFuncSetAttribute(conv_tiled)");
         attr_bytes = a.lds_bytes;
     }
     dim3 grid((unsigned)(a.g.flat ? a.g.ptiles * a.g.mtiles * a.g.nsl : 8 * (a.g.full_per_xcd + a.g.tail_per_xcd * a.g.nsl)));
+    if (a.g.sk_share) {
+        if (!kHasSK) return CNN_EUNSUPPORTED;
+        const long total = (long)a.g.ptiles * a.g.mtiles * a.g.sk_nchunks;
+        grid = dim3((unsigned)((total + a.g.sk_share - 1) / a.g.sk_share));
+    }
     static char name[96] = "";
     if (!name[0] && G::WLDP_CT)
         snprintf(name, sizeof(name), "k_conv_tiled<%dx%d CB%d WM%d WN%d NT%d ld%d/%d>", G::R, G::S, G::CB, G::WM, G::WN,
@@ -649,10 +741,16 @@ int launch(cnn_ctx* ctx, const LaunchArgs& a) {
     if (!name[0])
         snprintf(name, sizeof(name), "k_conv_tiled<%dx%d CB%d WM%d WN%d NT%d%s>", G::R, G::S, G::CB, G::WM, G::WN, G::NT,
                  G::VEC == 1 ? " v1" : "");
+    static char name_sk[104] = "";
+    if (!name_sk[0]) snprintf(name_sk, sizeof(name_sk), "%s runs", name);
     {
-        cnn::ProfScope ps(ctx, name, 2.0 * a.g.N * a.g.J * a.g.M * G::RS * a.g.HO * a.g.WO);
-        hipLaunchKernelGGL(k_conv_tiled<G>, grid, dim3(G::T), a.lds_bytes, ctx->stream, a.g, a.in, a.wt, a.aux, a.out,
-                           a.partial, a.arg);
+        cnn::ProfScope ps(ctx, a.g.sk_share ? name_sk : name, 2.0 * a.g.N * a.g.J * a.g.M * G::RS * a.g.HO * a.g.WO);
+        if (kHasSK && a.g.sk_share)
+            hipLaunchKernelGGL((k_conv_tiled<G, kHasSK>), grid, dim3(G::T), a.lds_bytes, ctx->stream, a.g, a.in, a.wt, a.aux,
+                               a.out, a.partial, a.arg);
+        else
+            hipLaunchKernelGGL((k_conv_tiled<G, false>), grid, dim3(G::T), a.lds_bytes, ctx->stream, a.g, a.in, a.wt, a.aux,
+                               a.out, a.partial, a.arg);
     }
     return cnn::launch_check(ctx, "conv_tiled");
 }
@@ -828,8 +926,28 @@ bool make_plan(int R, int S, int pad, int stride, int N, int J, int M, int HI, i
     g.nsl = best_tail ? best_nsl : 1;
     g.chunks_per_slice = (nchunks + g.nsl - 1) / g.nsl;
     g.flat = rounds == 0 && g.ptiles % 8 != 0;
-    const long sliced_units = g.flat ? (g.nsl > 1 ? (long)g.ptiles * g.mtiles : 0) : best_tail;
-    p->partial_bytes = (size_t)sliced_units * g.nsl * v.mb * (v.nt * v.wn * 32) * sizeof(float);
+    long sliced_units = g.flat ? (g.nsl > 1 ? (long)g.ptiles * g.mtiles : 0) : best_tail;
+    int pieces = g.nsl;
+    // Equal runs of chunks instead of equal slices of units, where that spreads a one-round grid better: the busiest
+    // compute unit works through share / nchunks of a unit instead of 1 / nsl.  The pieces cost a partial tile each
+    // (two or three per unit) and the reduction pass, so the saving must be worth tens of microseconds when the
+    // uniform plan needs no reduction at all.
+    g.sk_share = g.sk_pmax = 0;
+    g.sk_nchunks = nchunks;
+    if (rounds == 0 && v.vec == 4 && R == 3 && v.mb == 128 && !getenv("CNN_NO_RUNS")) {
+        const long total = live * nchunks;
+        const int share = (int)((total + slots - 1) / slots);
+        const double unit_us = 2.0 * J * R * S * v.mb * (v.nt * v.wn * 32) / 0.55e12 * 1e6;     // one unit on one compute unit
+        const double saving_us = unit_us * (1.0 / g.nsl - (double)share / nchunks);
+        if (share >= 8 && share < nchunks && saving_us > (g.nsl > 1 ? 5.0 : 40.0)) {
+            g.sk_share = share;
+            g.sk_pmax = (nchunks + share - 1) / share + 1;
+            g.flat = 1;
+            sliced_units = live;
+            pieces = g.sk_pmax;
+        }
+    }
+    p->partial_bytes = (size_t)sliced_units * pieces * v.mb * (v.nt * v.wn * 32) * sizeof(float);
     p->reduce_units = (int)sliced_units;
     return true;
 }

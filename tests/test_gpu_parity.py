@@ -103,6 +103,42 @@ def test_conv_three_passes_tiled_geometries(cnn, ctx, case):
     P.check_contraction("dw", P.np_(dw), *oracle.conv_bwd_weight(x, dy, R, R, 1, pad, with_abs=True))
 
 
+# (N, C, H, K): 3x3 / pad 1 layers whose grid is within one round and spreads better in equal runs of chunks than
+# in equal slices of units (54, 112 and 56 units on 256 compute units); a run ends one unit and begins the next
+RUNS_CASES = [(20, 256, 14, 384), (32, 128, 14, 512), (8, 256, 28, 256)]
+
+
+@pytest.mark.parametrize("case", RUNS_CASES)
+def test_conv_units_dealt_out_in_runs_of_chunks(cnn, ctx, case):
+    N, C, H, K = case
+    say("runs-of-chunks case", case)
+    x = np.maximum(synth.randn(82, 1, (N, C, H, H)), 0).astype(np.float32)
+    w = synth.randn(82, 2, (K, C, 3, 3), 0.1)
+    dy = synth.randn(82, 3, (N, K, H, H))
+    ctx.profile_reset(); ctx.profile(True)
+    y = cnn.cnn_conv_fwd(ctx, dev(x), dev(w), 1, 1)
+    dx = cnn.cnn_conv_bwd_data(ctx, dev(dy), dev(w), H, H, 1, 1)
+    torch.cuda.synchronize(); ctx.profile(False)
+    names = [e[0] for e in ctx.profile_entries()]
+    assert sum(" runs" in n for n in names) == 2, names
+    P.check_contraction("y", P.np_(y), *oracle.conv_fwd(x, w, 1, 1, with_abs=True))
+    P.check_contraction("dx", P.np_(dx), *oracle.conv_bwd_data(dy, w, H, H, 1, 1, with_abs=True))
+    # every epilogue runs in the reduction pass then: bit for bit the unfused sequences
+    a = cnn.cnn_conv_fwd_relu(ctx, dev(x), dev(w), 1, 1)
+    assert torch.equal(a, cnn.cnn_relu_fwd(ctx, y))
+    ap, arg = cnn.cnn_conv_fwd_relu_pool(ctx, dev(x), dev(w), 1, 1)
+    ap2, arg2 = cnn.cnn_maxpool2_fwd(ctx, a)
+    assert torch.equal(ap, ap2) and torch.equal(arg, arg2)
+    dz = cnn.cnn_conv_bwd_data_relu(ctx, dev(dy), dev(w), dev(x), 1, 1)
+    assert torch.equal(dz, cnn.cnn_relu_bwd(ctx, dev(x), dx))
+    xp, xarg = cnn.cnn_maxpool2_fwd(ctx, dev(np.maximum(synth.randn(82, 4, (N, C, 2 * H, 2 * H)), 0).astype(np.float32)))
+    du = cnn.cnn_conv_bwd_data_unpool_relu(ctx, dev(dy), dev(w), xarg, xp, 1, 1)
+    assert du is not None
+    ref = cnn.cnn_maxpool2_bwd(ctx, cnn.cnn_relu_bwd(ctx, xp, cnn.cnn_conv_bwd_data(ctx, dev(dy), dev(w), H, H, 1, 1)), xarg, 2 * H, 2 * H)
+    torch.cuda.synchronize()
+    assert torch.equal(du, ref)
+
+
 # (N, C, H, W, K, R, S, stride, pad): images that are not square, through every kernel family
 RECT_CASES = [(2, 16, 20, 36, 40, 3, 3, 1, 1), (3, 8, 30, 14, 72, 3, 3, 1, 1), (2, 32, 12, 56, 130, 3, 3, 1, 1),
               (2, 16, 24, 40, 48, 5, 5, 1, 2), (2, 16, 18, 26, 40, 7, 7, 1, 3), (2, 3, 40, 64, 64, 3, 3, 1, 1),
