@@ -638,7 +638,7 @@ __global__ void __launch_bounds__(256) k_tile_reduce(ConvGeo g, int MB, int cap,
         }
         return;
     }
-    if (out_plane % 4 == 0 && g.NPIX % 4 == 0) {
+    if (out_plane % 4 == 0 && g.NPIX % 4 == 0 && (g.epi != EPI_UNPOOL || g.WO % 2 == 0)) {
         // four consecutive pixels of a tile are four consecutive, 16-byte aligned elements of one output plane
         // (tiles and images start at multiples of four pixels): everything moves as float4; same order of additions
         typedef float f4 __attribute__((ext_vector_type(4)));
@@ -662,13 +662,19 @@ __global__ void __launch_bounds__(256) k_tile_reduce(ConvGeo g, int MB, int cap,
             if (g.epi == EPI_UNPOOL) {
                 const f4 a = *reinterpret_cast<const f4*>(aux + o);
                 const int ps4[4] = {arg_out[o], arg_out[o + 1], arg_out[o + 2], arg_out[o + 3]};
+                // two pixel pairs, each inside one row (even width): a pair's two windows are eight consecutive
+                // floats, four in each of two rows of the full-size gradient
 #pragma unroll
-                for (int t = 0; t < 4; ++t) {
-                    const float v = a[t] > 0.f ? r[t] : 0.f;
-                    const size_t q = rem + t;
+                for (int h = 0; h < 2; ++h) {
+                    const size_t q = rem + 2 * h;
+                    const float v0 = a[2 * h] > 0.f ? r[2 * h] : 0.f, v1 = a[2 * h + 1] > 0.f ? r[2 * h + 1] : 0.f;
+                    const int p0 = ps4[2 * h], p1 = ps4[2 * h + 1];
                     float* d = out + plane * 4 * out_plane + (q / g.WO) * (size_t)(4 * g.WO) + 2 * (q % g.WO);
-                    d[0] = ps4[t] == 0 ? v : 0.f; d[1] = ps4[t] == 1 ? v : 0.f;
-                    d[2 * g.WO] = ps4[t] == 2 ? v : 0.f; d[2 * g.WO + 1] = ps4[t] == 3 ? v : 0.f;
+                    f4 top, bot;
+                    top[0] = p0 == 0 ? v0 : 0.f; top[1] = p0 == 1 ? v0 : 0.f; top[2] = p1 == 0 ? v1 : 0.f; top[3] = p1 == 1 ? v1 : 0.f;
+                    bot[0] = p0 == 2 ? v0 : 0.f; bot[1] = p0 == 3 ? v0 : 0.f; bot[2] = p1 == 2 ? v1 : 0.f; bot[3] = p1 == 3 ? v1 : 0.f;
+                    *reinterpret_cast<f4*>(d) = top;
+                    *reinterpret_cast<f4*>(d + 2 * g.WO) = bot;
                 }
                 continue;
             }
