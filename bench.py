@@ -100,6 +100,11 @@ def main():
     ctx.profile(False)
     ms_per_step = dt / args.steps * 1e3
     loss = float(net.loss_per_sample.mean().item()) if wl.loss else None
+    # a run whose numbers have left the finite range has timed something else (zeros and NaNs also change the clocks)
+    finite = all(bool(torch.isfinite(w).all()) for w in net.w) and (loss is None or np.isfinite(loss))
+    if not finite:
+        print("bench.py: non-finite weights or loss after the timed steps: the measurement is void", file=sys.stderr)
+        sys.exit(1)
 
     # ---- the stand-alone SGD update (the default step folds it into the weight gradients): timed on its own after
     # the timed region, on the same arenas, so that its HBM rate is reported either way

@@ -77,7 +77,7 @@ def workload(config_id: int, N: int = None) -> Workload:
     if config_id == 3:
         n = N or 64
         return Workload(3, "vgg_a_full", list(VGG_A_CONV) + list(VGG_A_FC), (n, 3, 224, 224), True,
-                        n_classes=1000, lr=0.01, momentum=0.9, sgd=True, init="he")
+                        n_classes=1000, lr=0.001, momentum=0.9, sgd=True, init="he")   # 0.01 diverges from a He start
     if config_id == 4:
         n = N or 64
         return Workload(4, "overfeat_fast", list(OVERFEAT_FAST), (n, 3, 231, 231), True,
