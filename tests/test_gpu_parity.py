@@ -692,6 +692,22 @@ def test_pooled_weight_gradient_refuses_other_shapes(cnn, ctx):
         assert cnn.cnn_conv_bwd_weight_unpool(ctx, x, dp, arg, R, R, st, pad) is None
 
 
+@pytest.mark.parametrize("cfg,n", [(3, 16), (5, 256)])
+def test_training_stays_finite_and_the_loss_falls(cnn, ctx, cfg, n):
+    # twelve steps on the one synthetic batch: what the benchmark times must be a training run, not NaNs
+    from paper_1602_06709_amd.net import Net
+    wl = synth.workload(cfg, n)
+    net = Net(ctx, wl, synth.make_weights(wl))
+    net.set_input(synth.make_input(wl), synth.make_labels(wl))
+    losses = []
+    for _ in range(12):
+        net.step()
+        losses.append(float(net.loss_per_sample.mean()))
+    say("losses", cfg, losses)
+    assert all(np.isfinite(losses)) and all(bool(torch.isfinite(w).all()) for w in net.w)
+    assert losses[-1] < losses[0]
+
+
 def test_config5_dnn7_n1024_sampled(cnn, ctx):
     _run_and_check(cnn, ctx, 5, None, False, n_samples=20000)
 
