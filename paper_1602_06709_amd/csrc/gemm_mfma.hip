@@ -395,11 +395,28 @@ GemmPlan plan_gemm(int M, int Nn, int Kd) {
     }
     p.tn = 128;
     const long tiles = (long)((M + p.tm - 1) / p.tm) * ((Nn + p.tn - 1) / p.tn);
-    int want = tiles >= 256 ? 1 : (int)((512 + tiles - 1) / tiles);
     const int chunks = (Kd + KC - 1) / KC;
     int max_split = chunks / 8;            // at least 8 chunks (256 contraction elements) per split
     if (max_split < 1) max_split = 1;
-    if (want > max_split) want = max_split;
+    if (max_split > 32) max_split = 32;
+    // Splits of the contraction: the busiest compute unit works through ceil(tiles * splits / 256) workgroups of
+    // 1 / splits of a tile each (a lone workgroup per compute unit, although it runs two wave groups, below, reaches
+    // about 0.9 of the rate of two), and the partial products are written, read back and added (about 4 TB/s, plus
+    // the second launch).
+    // 288 tiles are two rounds unsplit and nine eighths of one in eight splits.
+    int want = 1;
+    {
+        const double unit_us = 2.0 * p.tm * p.tn * (double)Kd / 0.55e6;
+        double best_t = 0.0;
+        for (int ns = 1; ns <= max_split; ++ns) {
+            const int c = (chunks + ns - 1) / ns, real = (chunks + c - 1) / c;
+            if (real != ns) continue;
+            const long k = (tiles * ns + 255) / 256;
+            double t = (double)k * c / chunks * unit_us / (k >= 2 ? 1.0 : 0.9);
+            if (ns > 1) t += (double)(ns + 1) * M * Nn * 4.0 / 4.0e6 + 6.0;
+            if (ns == 1 || t < best_t * 0.97) { best_t = t; want = ns; }
+        }
+    }
     const int cps = (chunks + want - 1) / want;
     p.k_per_split = cps * KC;
     p.nsplit = (Kd + p.k_per_split - 1) / p.k_per_split;
