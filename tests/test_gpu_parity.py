@@ -629,10 +629,10 @@ def test_training_steps_with_folded_sgd_equal_the_separate_update(cnn, ctx, cfg)
             assert torch.equal(nets[0].v_arena, nets[1].v_arena), f"velocity differs after iteration {it}"
 
 
-@pytest.mark.parametrize("case", [(28, 224), (56, 100), (40, 158)])
+@pytest.mark.parametrize("case", [(28, 224), (56, 100), (40, 158), (14, 224)])
 def test_first_layer_band_kernel_with_pool(cnn, ctx, case):
     # 3 -> 64 features, 3x3 / pad 1, 224 columns, conv -> ReLU -> 2x2 max-pool in one kernel that walks bands of 14
-    # rows (served from 448 bands up): whole bands, a ragged last band (100 = 7 x 14 + 2; 158 = 11 x 14 + 4), all
+    # rows (served from 224 bands up): whole bands, a ragged last band (100 = 7 x 14 + 2; 158 = 11 x 14 + 4), all
     # elements against the oracle; the unfused sequence must agree wherever the window's maximum is not a near-tie
     N, H = case
     say("first-layer band kernel", case)
