@@ -118,8 +118,10 @@ int cnn_conv_bwd_data_relu(cnn_ctx* ctx, int N, int C, int H, int W, int K, int 
  *   arg[n][k][i][j] = 2*di + dj of that maximum (the first one in row-major window order on ties), as
  *   cnn_maxpool2_fwd writes it.  a: N*K*(P/2)*(Q/2) floats out, arg: as many bytes out (both device memory).
  *   The full-size activation is never written: in a conv -> ReLU -> pool chain nothing in the backward pass needs
- *   it (cnn_maxpool2_relu_bwd works from a and arg).  Results equal cnn_maxpool2_fwd(cnn_conv_fwd_relu(x, w)) bit
- *   for bit.  P and Q must be even.  Returns CNN_EUNSUPPORTED (nothing launched, outputs untouched) for shapes the
+ *   it (cnn_maxpool2_relu_bwd works from a and arg).  Results equal cnn_maxpool2_fwd(cnn_conv_fwd_relu(x, w)) up
+ *   to the rounding of the convolution's summation order (pooling wants tiles of whole row pairs, so the two calls
+ *   may cut the contraction differently; where they are tiled alike the results are the same bit for bit), and
+ *   the window positions agree except at such near-ties.  P and Q must be even.  Returns CNN_EUNSUPPORTED (nothing launched, outputs untouched) for shapes the
  *   tiled kernel does not serve: call the two unfused entry points then.  Workspace: cnn_workspace_bytes with
  *   CNN_OP_CONV_FWD_RELU_POOL. */
 int cnn_conv_fwd_relu_pool(cnn_ctx* ctx, int N, int C, int H, int W, int K, int R, int S, int stride, int pad,
