@@ -607,6 +607,22 @@ def test_fused_conv_relu_pool_equals_the_unfused_sequence(cnn, ctx):
     assert L.cnn_conv_fwd_relu_pool(ctx.handle, 1, 1, 5, 5, 1, 3, 3, 1, 1, z.data_ptr(), z.data_ptr(), z.data_ptr(), b.data_ptr()) == -1
 
 
+@pytest.mark.parametrize("case", [(11, 256, 20, 256), (12, 256, 20, 512)])
+def test_fused_pool_where_the_two_calls_cut_the_contraction_differently(cnn, ctx, case):
+    # 20 x 20 images: pooling wants tiles of whole row pairs, the plain call takes 11 rows: the two plans slice the
+    # contraction differently, so the fused result equals the unfused pair only up to rounding (and the window
+    # positions up to near-ties); against the oracle both hold the tolerance
+    N, C, H, K = case
+    say("fused pool, differently planned", case)
+    x = synth.randn(81, 1, (N, C, H, H)); w = synth.randn(81, 2, (K, C, 3, 3), 0.05)
+    a, arg = cnn.cnn_conv_fwd_relu_pool(ctx, dev(x), dev(w), 1, 1)
+    a2, arg2 = cnn.cnn_maxpool2_fwd(ctx, cnn.cnn_conv_fwd_relu(ctx, dev(x), dev(w), 1, 1))
+    torch.cuda.synchronize()
+    assert float((a - a2).abs().max()) <= 2e-5 * float(a2.abs().max())
+    assert float((arg != arg2).float().mean()) < 1e-3
+    P.check_trace_item(("conv_fwd_relu_pool", 0, 0, dev(x), dev(w), a, arg), 0, [("conv", C, K, 3, 3, 1, 1)], True)
+
+
 @pytest.mark.parametrize("cfg", [2, 5, 4, 3])
 def test_training_steps_with_folded_sgd_equal_the_separate_update(cnn, ctx, cfg):
     # two iterations (the second one uses the first one's velocity) of each workload, once with the update inside
