@@ -262,8 +262,9 @@ int cnn_block_search_traversal(cnn_ctx* ctx, int minibatch, int ifm, int ofm, in
  * CNN_OP_CONV_BWD_DATA), and its cnn_bf_block_traversal ratio, for comparison with what the search finds for the
  * machine's limits.  Host only.  tile[0] output features per workgroup (for backpropagation: input features, the
  * pass's outputs), [1] output rows per tile (rows of the whole minibatch numbered through), [2] output columns,
- * [3] contraction features per staged chunk, [4] contraction slices of the tail workgroups (1 = none), [5] LDS
- * bytes per workgroup, [6] workgroups, [7] accumulator capacity in pixels.  For the ratio a tile of whole images
+ * [3] contraction features per staged chunk, [4] contraction slices of the tail workgroups (1 = none; negative:
+ * the tiles' chunks are dealt out in equal runs, one per workgroup, and -[4] is the most pieces a tile is cut
+ * into), [5] LDS bytes per workgroup, [6] tiles (in the runs mode: workgroups), [7] accumulator capacity in pixels.  For the ratio a tile of whole images
  * counts as [1] / out_h images of out_h rows, any other as one image of [1] rows.  CNN_EUNSUPPORTED where the tiled
  * matrix-core kernel does not serve the shape. */
 int cnn_conv_tile_info(int op, int N, int C, int H, int W, int K, int R, int S, int stride, int pad, int32_t* tile,

@@ -1026,9 +1026,10 @@ bool mfma_conv_tile_info(const ConvShape& s, int op, int32_t tile[8]) {
     tile[1] = p.g.TR;
     tile[2] = p.g.WO;
     tile[3] = p.v->CB;
-    tile[4] = p.g.nsl > 0 ? p.g.nsl : 1;
+    tile[4] = p.g.sk_share ? -p.g.sk_pmax : (p.g.nsl > 0 ? p.g.nsl : 1);
     tile[5] = (int32_t)p.lds_bytes;
-    tile[6] = p.g.ptiles * p.g.mtiles;
+    tile[6] = p.g.sk_share ? (int32_t)(((long)p.g.ptiles * p.g.mtiles * p.g.sk_nchunks + p.g.sk_share - 1) / p.g.sk_share)
+                           : p.g.ptiles * p.g.mtiles;
     tile[7] = p.v->wn * p.v->nt * 32;
     return true;
 }

@@ -64,7 +64,7 @@ def main():
         "search (n,f,c,r,c)", "B/F", "1-cache"))
     for r_ in rows:
         def t(d):
-            return ("%dx%dx%d%s" % (d["features"], d["rows"], d["cols"], "" if d["slices"] == 1 else " /%d" % d["slices"]),
+            return ("%dx%dx%d%s" % (d["features"], d["rows"], d["cols"], "" if d["slices"] == 1 else (" runs" if d["slices"] < 0 else " /%d" % d["slices"])),
                     "%.4f" % d["bf"]) if d else ("(other kernel)", "-")
         f, b = t(r_["fwd"]), t(r_["bwd"])
         s_ = r_["search_traversal"]
