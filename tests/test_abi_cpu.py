@@ -155,6 +155,9 @@ def test_tile_report_and_block_search_validation(L):
     # 8 TB/s / 157.3 TFLOP/s = 0.051 bytes per FLOP
     assert OB.bf_layer(64, 128, 256, 56, 56, 3, 3) < bf.value < 0.051 < OB.bf_plane(56, 56, 3, 3)
     # backpropagation: the pass's outputs are the layer's input features
+    # 224 tiles on 256 compute units: chunks dealt out in equal runs, 7/8 of a tile per workgroup, two pieces per tile
+    assert L.cnn_conv_tile_info(0, 64, 512, 14, 14, 512, 3, 3, 1, 1, tp, C.byref(bf)) == 0
+    assert list(tile)[4] == -3 and list(tile)[6] == 256 and list(tile)[1] == 16
     assert L.cnn_conv_tile_info(1, 64, 64, 112, 112, 128, 3, 3, 1, 1, tp, C.byref(bf)) == 0 and tile[0] == 64
     assert L.cnn_conv_tile_info(0, 2, 5, 9, 9, 7, 7, 7, 2, 0, tp, C.byref(bf)) == -2      # no tiled kernel for 7x7 / 2
     assert L.cnn_conv_tile_info(2, 64, 128, 56, 56, 256, 3, 3, 1, 1, tp, C.byref(bf)) == -1
