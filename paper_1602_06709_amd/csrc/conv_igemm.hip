@@ -173,7 +173,8 @@ k_conv_igemm(IgArgs g, const float* __restrict__ Asrc, const float* __restrict__
             for (int v = 0; v < 16; ++v) acc[i][j][v] = 0.f;
 
     // ---- staging: who fetches what
-    const int kq = tid & 31, rbase = tid >> 5;              // operands stored [row][KC+1]: fixed k, rows rbase + 8 i
+    constexpr int RSTEP = 256 / KC;
+    const int kq = tid % KC, rbase = tid / KC;              // operands stored [row][KC+1]: fixed k, rows rbase + RSTEP i
     const int a_rs = a_row_stride<MODE>(g);
     const int bn = tid % TN, bk = tid / TN;                 // BKM: fixed column, k = bk + (256 / TN) i
     Part fix;                                               // the thread's fixed part of the second operand
@@ -198,7 +199,7 @@ k_conv_igemm(IgArgs g, const float* __restrict__ Asrc, const float* __restrict__
             const int kp = a_k_part<MODE>(g, ph, kok ? kk : k_begin);
 #pragma unroll
             for (int i = 0; i < NA; ++i) {
-                const int m = m0 + rbase + 8 * i;
+                const int m = m0 + rbase + RSTEP * i;
                 const bool ok = kok & (m < g.M);
                 ra[i] = Asrc[ok ? (size_t)(m * a_rs + kp) : 0];
                 oka |= (unsigned)ok << i;
@@ -213,7 +214,7 @@ k_conv_igemm(IgArgs g, const float* __restrict__ Asrc, const float* __restrict__
             int4 t4[4];
 #pragma unroll
             for (int u = 0; u < 4; ++u)
-                t4[u] = tab[BKM ? (c & 1) * KC + bk + (256 / TN) * (i0 + u) : rbase + 8 * (i0 + u)];
+                t4[u] = tab[BKM ? (c & 1) * KC + bk + (256 / TN) * (i0 + u) : rbase + RSTEP * (i0 + u)];
 #pragma unroll
             for (int u = 0; u < 4; ++u) {
                 Part t;
@@ -228,13 +229,13 @@ k_conv_igemm(IgArgs g, const float* __restrict__ Asrc, const float* __restrict__
         float* la = lds + buf * BUF;
         float* lb = la + A_LDS;
 #pragma unroll
-        for (int i = 0; i < NA; ++i) la[(rbase + 8 * i) * (KC + 1) + kq] = (oka >> i) & 1 ? ra[i] : 0.f;
+        for (int i = 0; i < NA; ++i) la[(rbase + RSTEP * i) * (KC + 1) + kq] = (oka >> i) & 1 ? ra[i] : 0.f;
         if (BKM) {
 #pragma unroll
             for (int i = 0; i < NB; ++i) lb[(bk + (256 / TN) * i) * TN + bn] = (okb >> i) & 1 ? rb[i] : 0.f;
         } else {
 #pragma unroll
-            for (int i = 0; i < NB; ++i) lb[(rbase + 8 * i) * (KC + 1) + kq] = (okb >> i) & 1 ? rb[i] : 0.f;
+            for (int i = 0; i < NB; ++i) lb[(rbase + RSTEP * i) * (KC + 1) + kq] = (okb >> i) & 1 ? rb[i] : 0.f;
         }
     };
 
