@@ -334,6 +334,37 @@ def test_conv_seeded_random_shapes(cnn, ctx, chunk):
         P.check_contraction("dw", P.np_(dw), *oracle.conv_bwd_weight(x, dy, R, S, st, pad, with_abs=True))
 
 
+def test_conv_seeded_random_large_layers(cnn, ctx):
+    # 30 seeded layers with 64 ... 1024 features at 7 ... 56 pixels and minibatches up to 64 (several rounds of tiles, tail
+    # slices, runs of chunks, split weight gradients), outputs sampled against the oracle
+    rng = np.random.default_rng(2000)
+    done = 0
+    while done < 30:
+        R = int(rng.choice([3, 3, 3, 5, 7])); pad = int(rng.choice([0, (R - 1) // 2]))
+        H = int(rng.choice([7, 12, 14, 24, 28, 56, 30])); W = H if rng.random() < 0.7 else int(rng.choice([14, 28, 40]))
+        C = int(rng.choice([64, 96, 128, 256, 512])); K = int(rng.choice([64, 128, 192, 256, 512, 1024]))
+        N = int(rng.integers(1, 65))
+        if H + 2 * pad < R or W + 2 * pad < R:
+            continue
+        P_, Q_ = H + 2 * pad - R + 1, W + 2 * pad - R + 1
+        while N > 1 and N * C * K * R * R * P_ * Q_ > 4e10:
+            N //= 2
+        say("random large layer", (N, C, H, W, K, R, pad))
+        x = np.maximum(synth.randn(85, 3 * done, (N, C, H, W)), 0).astype(np.float32)
+        w = synth.randn(85, 3 * done + 1, (K, C, R, R), 0.05); dy = synth.randn(85, 3 * done + 2, (N, K, P_, Q_))
+        y = cnn.cnn_conv_fwd(ctx, dev(x), dev(w), 1, pad)
+        dx = cnn.cnn_conv_bwd_data(ctx, dev(dy), dev(w), H, W, 1, pad)
+        dw = cnn.cnn_conv_bwd_weight(ctx, dev(x), dev(dy), R, R, 1, pad)
+        torch.cuda.synchronize()
+        idx = P.sample(85, 1000 + done, y.numel(), 4000)
+        P.check_contraction("y", P.np_(y).ravel()[idx], *oracle.conv_fwd_at(x, w, idx, 1, pad))
+        idx = P.sample(85, 2000 + done, dx.numel(), 4000)
+        P.check_contraction("dx", P.np_(dx).ravel()[idx], *oracle.conv_bwd_data_at(dy, w, H, W, idx, 1, pad))
+        idx = P.sample(85, 3000 + done, dw.numel(), 300)
+        P.check_contraction("dw", P.np_(dw).ravel()[idx], *oracle.conv_bwd_weight_at(x, dy, R, R, idx, 1, pad))
+        done += 1
+
+
 def test_bwd_weight_is_bitwise_repeatable(cnn, ctx):
     x = dev(synth.randn(92, 1, (4, 32, 28, 28))); dy = dev(synth.randn(92, 2, (4, 64, 28, 28)))
     a = cnn.cnn_conv_bwd_weight(ctx, x, dy, 3, 3, 1, 1).clone()
