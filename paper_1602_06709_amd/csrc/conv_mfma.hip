@@ -595,7 +595,7 @@ __device__ __forceinline__ float slice_sum(const float* __restrict__ p, size_t t
     return r;
 }
 
-__global__ void __launch_bounds__(256) k_tile_reduce(ConvGeo g, int MB, int cap, const float* __restrict__ partial,
+__global__ void __launch_bounds__(256) k_tile_reduce(ConvGeo g, int MB, int cap, int kRedF, const float* __restrict__ partial,
                                                     const float* __restrict__ aux, float* __restrict__ out,
                                                     unsigned char* arg_out) {
     int ptile, m0;
@@ -622,8 +622,8 @@ __global__ void __launch_bounds__(256) k_tile_reduce(ConvGeo g, int MB, int cap,
         // ReLU + 2x2 max-pool of the summed tile: one thread per pooled element (window order: row-major, first
         // maximum wins, as in the stand-alone pooling kernel)
         const int pw = g.WO / 2, per_m = (g.TR / 2) * pw, php = g.HO / 2;
-        for (int e = threadIdx.x; e < 8 * per_m; e += 256) {
-            const int ml = blockIdx.y * 8 + e / per_m, rem = e % per_m, pr = rem / pw, pq = rem % pw;
+        for (int e = threadIdx.x; e < kRedF * per_m; e += 256) {
+            const int ml = blockIdx.y * kRedF + e / per_m, rem = e % per_m, pr = rem / pw, pq = rem % pw;
             const int orow = row0 + 2 * pr;
             if (orow >= nrows || m0 + ml >= g.M) continue;
             float best = 0.f;
@@ -646,8 +646,8 @@ __global__ void __launch_bounds__(256) k_tile_reduce(ConvGeo g, int MB, int cap,
         typedef float f4 __attribute__((ext_vector_type(4)));
         const int c4 = cap / 4;
         const size_t lin0 = (size_t)row0 * g.WO, lin_end = (size_t)nrows * g.WO;
-        for (int e = threadIdx.x; e < 8 * c4; e += 256) {
-            const int ml = blockIdx.y * 8 + e / c4, i = (e % c4) * 4;
+        for (int e = threadIdx.x; e < kRedF * c4; e += 256) {
+            const int ml = blockIdx.y * kRedF + e / c4, i = (e % c4) * 4;
             if (i >= g.NPIX || lin0 + i >= lin_end || m0 + ml >= g.M) continue;
             const float* ps = pt + (size_t)ml * cap + i;
             f4 r = *reinterpret_cast<const f4*>(ps);
@@ -692,8 +692,8 @@ __global__ void __launch_bounds__(256) k_tile_reduce(ConvGeo g, int MB, int cap,
         }
         return;
     }
-    for (int e = threadIdx.x; e < 8 * cap; e += 256) {
-        const int ml = blockIdx.y * 8 + e / cap, i = e % cap;
+    for (int e = threadIdx.x; e < kRedF * cap; e += 256) {
+        const int ml = blockIdx.y * kRedF + e / cap, i = e % cap;
         const int orow = row0 + i / g.WO;
         if (i >= g.NPIX || orow >= nrows || m0 + ml >= g.M) continue;
         float r = slice_sum(pt + (size_t)ml * cap + i, tile, nsl);
@@ -969,8 +969,10 @@ int run_plan(cnn_ctx* ctx, ConvPlan& p, const float* in, const float* wt, float*
     if (st != CNN_OK || p.reduce_units == 0) return st;
     {
         cnn::ProfScope ps(ctx, "k_tile_reduce", 0.0);
-        hipLaunchKernelGGL(k_tile_reduce, dim3((unsigned)p.reduce_units, (unsigned)(p.v->mb / 8)), dim3(256), 0,
-                           ctx->stream, p.g, p.v->mb, p.v->nt * p.v->wn * 32, ws, aux, out, arg);
+        // features of a tile per reduction workgroup: 16 where that still leaves thousands of workgroups, else 8
+        const int fpb = (long)p.reduce_units * (p.v->mb / 16) >= 2048 ? 16 : 8;
+        hipLaunchKernelGGL(k_tile_reduce, dim3((unsigned)p.reduce_units, (unsigned)(p.v->mb / fpb)), dim3(256), 0,
+                           ctx->stream, p.g, p.v->mb, p.v->nt * p.v->wn * 32, fpb, ws, aux, out, arg);
     }
     return cnn::launch_check(ctx, "tile_reduce");
 }
