@@ -383,7 +383,7 @@ struct GemmPlan {
 
 GemmPlan plan_gemm(int M, int Nn, int Kd) {
     GemmPlan p;
-    p.tm = M <= 64 ? 64 : 128;
+    p.tm = M <= 32 ? 32 : M <= 64 ? 64 : 128;      // a minibatch of 32 or fewer rows: half the padded MFMA work of a 64-row tile
     // too few 128-row tiles to fill the chip and a short contraction: 64-row tiles (twice as many workgroups) beat
     // splitting the contraction, which needs the partial products written, read back and added
     if (p.tm == 128 && (long)((M + 127) / 128) * ((Nn + 127) / 128) < 256 && Kd <= 4096) p.tm = 64;
@@ -422,7 +422,7 @@ GemmPlan plan_gemm(int M, int Nn, int Kd) {
     p.nsplit = (Kd + p.k_per_split - 1) / p.k_per_split;
     p.ws_bytes = p.nsplit > 1 ? (size_t)p.nsplit * M * Nn * sizeof(float) : 0;
     // a grid of at most one workgroup per compute unit: two wave groups per tile
-    p.ks = tiles * p.nsplit <= 256 ? 2 : 1;
+    p.ks = tiles * p.nsplit <= 256 && p.tm != 32 ? 2 : 1;      // (the 32-row tile has too few staging slots for 512 threads)
     return p;
 }
 
@@ -489,6 +489,7 @@ int mfma_gemm(cnn_ctx* ctx, int M, int Nn, int Kd, const float* A, int akm, cons
         if (akm && bkm) return launch<GemmCfg<MT, NT, WGM, WGN, true, true, KS>>(ctx, p, M, Nn, Kd, A, B, C);     \
         return launch<GemmCfg<MT, NT, WGM, WGN, true, false, KS>>(ctx, p, M, Nn, Kd, A, B, C);                    \
     } while (0)
+    if (p.tm == 32) GO(1, 1, 1, 4, 1);
     if (p.tm == 64 && p.ks == 2) GO(2, 1, 1, 4, 2);
     if (p.tm == 64) GO(2, 1, 1, 4, 1);
     if (p.ks == 2) GO(2, 2, 2, 2, 2);
