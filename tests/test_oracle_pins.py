@@ -119,11 +119,26 @@ def test_conv_three_passes_vs_torch_fp64(case):
     y, s = oracle.conv_fwd(x, w, st, pad, with_abs=True)
     assert y.shape == tuple(yt.shape)
     np.testing.assert_allclose(y, yt.detach().numpy(), rtol=1e-13, atol=1e-13)
-    np.testing.assert_allclose(oracle.conv_bwd_data(g, w, H, W, st, pad), xt.grad.numpy(), rtol=1e-13, atol=1e-13)
-    np.testing.assert_allclose(oracle.conv_bwd_weight(x, g, R, S, st, pad), wt.grad.numpy(), rtol=1e-13, atol=1e-13)
-    # S = sum |a*b| is the same contraction on absolute values
-    sa = torch.nn.functional.conv2d(xt.detach().abs(), wt.detach().abs(), stride=st, padding=pad)
-    np.testing.assert_allclose(s, sa.numpy(), rtol=1e-13, atol=1e-13)
+    dx, sdx = oracle.conv_bwd_data(g, w, H, W, st, pad, with_abs=True)
+    dw, sdw = oracle.conv_bwd_weight(x, g, R, S, st, pad, with_abs=True)
+    np.testing.assert_allclose(dx, xt.grad.numpy(), rtol=1e-13, atol=1e-13)
+    np.testing.assert_allclose(dw, wt.grad.numpy(), rtol=1e-13, atol=1e-13)
+    # S = sum |a*b| is the same contraction on absolute values: torch's forward and its autograd
+    # on |x|, |w|, |g| give the S of all three passes
+    xa = torch.tensor(np.abs(x), dtype=torch.float64, requires_grad=True)
+    wa = torch.tensor(np.abs(w), dtype=torch.float64, requires_grad=True)
+    sa = torch.nn.functional.conv2d(xa, wa, stride=st, padding=pad)
+    sa.backward(torch.tensor(np.abs(g), dtype=torch.float64))
+    np.testing.assert_allclose(s, sa.detach().numpy(), rtol=1e-13, atol=1e-13)
+    np.testing.assert_allclose(sdx, xa.grad.numpy(), rtol=1e-13, atol=1e-13)
+    np.testing.assert_allclose(sdw, wa.grad.numpy(), rtol=1e-13, atol=1e-13)
+    # the sampled forms return the same (value, S) pairs, pinned here against torch directly
+    for (v, sv), ref, sref in (
+            (oracle.conv_fwd_at(x, w, np.arange(y.size), st, pad), yt.detach().numpy(), sa.detach().numpy()),
+            (oracle.conv_bwd_data_at(g, w, H, W, np.arange(dx.size), st, pad), xt.grad.numpy(), xa.grad.numpy()),
+            (oracle.conv_bwd_weight_at(x, g, R, S, np.arange(dw.size), st, pad), wt.grad.numpy(), wa.grad.numpy())):
+        np.testing.assert_allclose(v, ref.ravel(), rtol=1e-13, atol=1e-13)
+        np.testing.assert_allclose(sv, sref.ravel(), rtol=1e-13, atol=1e-13)
 
 
 def test_conv_vs_scipy_correlate2d():
@@ -202,8 +217,12 @@ def test_fc_is_matmul_and_is_the_1x1_special_case():
     y, s = oracle.fc_fwd(x, w, with_abs=True)
     np.testing.assert_allclose(y, x64 @ w64.T, rtol=1e-13, atol=1e-13)
     np.testing.assert_allclose(s, np.abs(x64) @ np.abs(w64).T, rtol=1e-13, atol=1e-13)
-    np.testing.assert_allclose(oracle.fc_bwd_data(g, w), g64 @ w64, rtol=1e-13, atol=1e-13)
-    np.testing.assert_allclose(oracle.fc_bwd_weight(x, g), g64.T @ x64, rtol=1e-13, atol=1e-13)
+    dx, sdx = oracle.fc_bwd_data(g, w, with_abs=True)
+    dw, sdw = oracle.fc_bwd_weight(x, g, with_abs=True)
+    np.testing.assert_allclose(dx, g64 @ w64, rtol=1e-13, atol=1e-13)
+    np.testing.assert_allclose(dw, g64.T @ x64, rtol=1e-13, atol=1e-13)
+    np.testing.assert_allclose(sdx, np.abs(g64) @ np.abs(w64), rtol=1e-13, atol=1e-13)
+    np.testing.assert_allclose(sdw, np.abs(g64).T @ np.abs(x64), rtol=1e-13, atol=1e-13)
     # Section 2.1: FC is the conv loop nest with k_h = k_w = out_h = out_w = 1
     yc = oracle.conv_fwd(x.reshape(N, I, 1, 1), w.reshape(O, I, 1, 1), 1, 0)
     np.testing.assert_allclose(yc.reshape(N, O), y, rtol=1e-14, atol=1e-14)
@@ -211,11 +230,13 @@ def test_fc_is_matmul_and_is_the_1x1_special_case():
                                .reshape(O, I), oracle.fc_bwd_weight(x, g), rtol=1e-14, atol=1e-14)
     np.testing.assert_allclose(oracle.conv_bwd_data(g.reshape(N, O, 1, 1), w.reshape(O, I, 1, 1), 1, 1, 1, 0)
                                .reshape(N, I), oracle.fc_bwd_data(g, w), rtol=1e-14, atol=1e-14)
-    for full, fn in ((y, lambda i: oracle.fc_fwd_at(x, w, i)),
-                     (oracle.fc_bwd_data(g, w), lambda i: oracle.fc_bwd_data_at(g, w, i)),
-                     (oracle.fc_bwd_weight(x, g), lambda i: oracle.fc_bwd_weight_at(x, g, i))):
-        v, _ = fn(np.arange(full.size))
-        np.testing.assert_allclose(v, full.ravel(), rtol=1e-14, atol=1e-14)
+    # sampled forms: value and S against numpy matmul (not against the full forms)
+    for ref, sref, fn in ((x64 @ w64.T, np.abs(x64) @ np.abs(w64).T, lambda i: oracle.fc_fwd_at(x, w, i)),
+                          (g64 @ w64, np.abs(g64) @ np.abs(w64), lambda i: oracle.fc_bwd_data_at(g, w, i)),
+                          (g64.T @ x64, np.abs(g64).T @ np.abs(x64), lambda i: oracle.fc_bwd_weight_at(x, g, i))):
+        v, sv = fn(np.arange(ref.size))
+        np.testing.assert_allclose(v, ref.ravel(), rtol=1e-13, atol=1e-13)
+        np.testing.assert_allclose(sv, sref.ravel(), rtol=1e-13, atol=1e-13)
 
 
 # ---------------------------------------------------------------- SGD
