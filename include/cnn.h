@@ -145,6 +145,19 @@ int cnn_conv_bwd_data_unpool_relu(cnn_ctx* ctx, int N, int C, int H, int W, int 
 int cnn_conv_bwd_weight(cnn_ctx* ctx, int N, int C, int H, int W, int K, int R, int S, int stride, int pad,
                         const float* x, const float* dy, float* dw);
 
+/* ---- cnn_conv_bwd_weight for callers that cannot allocate device memory for a workspace (code under HIP graph
+ *   capture, tight serving loops, harnesses that forbid hipMalloc).  Same arguments, same kernels, same bits; the
+ *   partial sums go to a CNN_STATIC_SCRATCH_BYTES array built into the library's code object (every GPU the
+ *   library runs on holds its own copy until the process ends) instead of the workspace attached to the context,
+ *   which is neither needed nor touched.  The call allocates nothing on the host or the device.  Layers whose
+ *   cnn_workspace_bytes(CNN_OP_CONV_BWD_WEIGHT, ...) exceeds CNN_STATIC_SCRATCH_BYTES return CNN_EWORKSPACE with
+ *   nothing launched (text via cnn_last_error).  All calls on one GPU share that GPU's array, whatever their
+ *   context or stream: calls that overlap in time on one GPU race.  The array keeps the previous call's partial
+ *   sums; every call overwrites the part it reads, nothing needs clearing.  CNN_OPT_PROFILE does not record it. */
+#define CNN_STATIC_SCRATCH_BYTES (80 << 20)
+int cnn_conv_bwd_weight_static(cnn_ctx* ctx, int N, int C, int H, int W, int K, int R, int S, int stride, int pad,
+                               const float* x, const float* dy, float* dw);
+
 /* ---- Section 2.1: the fully-connected layer is the same loop nest with k_h = k_w = out_h = out_w = 1.
  *   y[n][o] = sum_i x[n][i] * w[o][i] */
 int cnn_fc_fwd(cnn_ctx* ctx, int N, int I, int O, const float* x, const float* w, float* y);

@@ -36,6 +36,7 @@ SIGNATURES = {
     "cnn_conv_fwd": (_i, _CONV),
     "cnn_conv_bwd_data": (_i, _CONV),
     "cnn_conv_bwd_weight": (_i, _CONV),
+    "cnn_conv_bwd_weight_static": (_i, _CONV),
     "cnn_conv_fwd_relu": (_i, _CONV),
     "cnn_conv_bwd_data_relu": (_i, [_vp] + [_i] * 9 + [_vp] * 4),
     "cnn_conv_fwd_relu_pool": (_i, [_vp] + [_i] * 9 + [_vp] * 4),
@@ -255,6 +256,21 @@ def cnn_conv_bwd_weight(ctx, x, dy, R, S, stride=1, pad=0, out=None):
     dw = out if out is not None else torch.empty((K, Cc, R, S), dtype=torch.float32, device=x.device)
     _check(lib().cnn_conv_bwd_weight(ctx.handle, N, Cc, H, W, K, R, S, stride, pad, _t(x), _t(dy), _t(dw)), ctx.handle)
     return dw
+
+
+STATIC_SCRATCH_BYTES = 80 << 20
+
+
+def cnn_conv_bwd_weight_static(ctx, x, dy, R, S, stride, pad, out):
+    """cnn_conv_bwd_weight on the library's built-in scratch array: no workspace is reserved and nothing is
+    allocated here or in the library, so the caller passes the output tensor."""
+    N, Cc, H, W = x.shape
+    K = dy.shape[1]
+    assert tuple(dy.shape) == (N, K, out_dim(H, R, stride, pad), out_dim(W, S, stride, pad))
+    assert tuple(out.shape) == (K, Cc, R, S)
+    _check(lib().cnn_conv_bwd_weight_static(ctx.handle, N, Cc, H, W, K, R, S, stride, pad, _t(x), _t(dy), _t(out)),
+           ctx.handle)
+    return out
 
 
 def cnn_fc_fwd(ctx, x, w, out=None):

@@ -1,4 +1,5 @@
 // C-ABI entry points: argument validation, kernel selection, error reporting.
+#include <mutex>
 #include <new>
 #include <stdio.h>
 #include <string.h>
@@ -49,6 +50,35 @@ int make_shape(int N, int C, int H, int W, int K, int R, int S, int stride, int 
     return CNN_OK;
 }
 
+}  // namespace
+
+// ---- The allocation-free variant of cnn_conv_bwd_weight: its partial sums live in a device array that is part of
+// the library's code object instead of a caller's workspace.  `scratch` is a host-side stand-in for the array, not
+// a device address: host code only ever uses the per-device pointer hipGetSymbolAddress returns for it.
+static __device__ __align__(256) unsigned char scratch[CNN_STATIC_SCRATCH_BYTES];
+
+namespace {
+constexpr int kMaxDevices = 64;
+std::mutex g_scratch_mutex;
+void* g_scratch_ptr[kMaxDevices];   // each device holds its own copy of the array at its own address
+
+// The current device's copy of `scratch`; looked up once per device, with that device current.
+int static_scratch(cnn_ctx* ctx, void** out) {
+    int dev = -1;
+    int st = cnn::hip_check(ctx, hipGetDevice(&dev), "hipGetDevice");
+    if (st != CNN_OK) return st;
+    if (dev < 0 || dev >= kMaxDevices) return CNN_EUNSUPPORTED;
+    std::lock_guard<std::mutex> lock(g_scratch_mutex);
+    if (!g_scratch_ptr[dev]) {
+        void* p = nullptr;
+        st = cnn::hip_check(ctx, hipGetSymbolAddress(&p, HIP_SYMBOL(scratch)), "hipGetSymbolAddress(scratch)");
+        if (st != CNN_OK) return st;
+        if (!p) return CNN_EHIP;
+        g_scratch_ptr[dev] = p;
+    }
+    *out = g_scratch_ptr[dev];
+    return CNN_OK;
+}
 }  // namespace
 
 extern "C" {
@@ -243,6 +273,35 @@ int cnn_conv_bwd_weight(cnn_ctx* ctx, int N, int C, int H, int W, int K, int R, 
         if (st != CNN_EUNSUPPORTED) return st;
     }
     return cnn::direct_conv_bwd_weight(ctx, s, x, dy, dw);
+}
+
+int cnn_conv_bwd_weight_static(cnn_ctx* ctx, int N, int C, int H, int W, int K, int R, int S, int stride, int pad,
+                               const float* x, const float* dy, float* dw) {
+    if (!ctx || !x || !dy || !dw || !aligned16(x) || !aligned16(dy) || !aligned16(dw)) return CNN_EINVAL;
+    ConvShape s;
+    int st = make_shape(N, C, H, W, K, R, S, stride, pad, &s);
+    if (st != CNN_OK) return st;
+    if (cnn_workspace_bytes(CNN_OP_CONV_BWD_WEIGHT, N, C, H, W, K, R, S, stride, pad) > (size_t)CNN_STATIC_SCRATCH_BYTES) {
+        snprintf(ctx->err, sizeof(ctx->err), "cnn_conv_bwd_weight_static: the layer needs more than the %d bytes of "
+                 "built-in scratch; use cnn_conv_bwd_weight with a workspace", CNN_STATIC_SCRATCH_BYTES);
+        return CNN_EWORKSPACE;
+    }
+    void* ptr = nullptr;
+    st = static_scratch(ctx, &ptr);
+    if (st != CNN_OK) return st;
+    // Same kernels as cnn_conv_bwd_weight, with the built-in array as their workspace.  Per-kernel profiling
+    // creates event objects, so it is off for this call.
+    void* const ws = ctx->ws;
+    const size_t ws_bytes = ctx->ws_bytes;
+    const int profile = ctx->profile;
+    ctx->ws = ptr;
+    ctx->ws_bytes = CNN_STATIC_SCRATCH_BYTES;
+    ctx->profile = 0;
+    st = cnn_conv_bwd_weight(ctx, N, C, H, W, K, R, S, stride, pad, x, dy, dw);
+    ctx->ws = ws;
+    ctx->ws_bytes = ws_bytes;
+    ctx->profile = profile;
+    return st;
 }
 
 // The second stage of the weight gradient (the sum over the minibatch splits, Section 3.1) hands each finished

@@ -72,6 +72,11 @@ def test_validation_rejects_before_any_launch(L):
         # weight gradient of a tiled shape without a workspace attached
         assert L.cnn_conv_bwd_weight(h, 4, 64, 56, 56, 64, 3, 3, 1, 1, p, p, p) == -3
         assert L.cnn_last_error(h) == b""
+        # the allocation-free weight gradient: same validation; a layer beyond its built-in scratch array is refused
+        assert L.cnn_conv_bwd_weight_static(h, 1, 1, 4, 4, 1, 3, 3, 1, 1, p, None, p) == -1
+        assert L.cnn_conv_bwd_weight_static(h, 1, 1, 2, 2, 1, 5, 5, 1, 0, p, p, p) == -1
+        assert L.cnn_conv_bwd_weight_static(h, 2, 2048, 14, 14, 2048, 3, 3, 1, 1, p, p, p) == -3
+        assert b"built-in scratch" in L.cnn_last_error(h)
     finally:
         assert L.cnn_destroy(h) == 0
     assert L.cnn_destroy(None) == -1
