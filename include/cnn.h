@@ -219,7 +219,9 @@ int cnn_unpack_wt(cnn_ctx* ctx, int K, int C, int R, int S, int SW, int transpos
  *   row-major window order; backward routes dy to that position, zero elsewhere.
  *   sigmoid: a = 1/(1+exp(-z)); dz = da * a * (1 - a) (uses the forward OUTPUT a).
  *   softmax cross-entropy: loss_per_sample[n] = -log softmax(z[n])[label[n]];
- *   dz[n][o] = (softmax(z[n])[o] - [o == label[n]]) / N.  dz may be NULL. */
+ *   dz[n][o] = (softmax(z[n])[o] - [o == label[n]]) / N.  dz may be NULL.  label is device memory, int32, each
+ *   entry in [0, O): an entry outside that range gives loss_per_sample[n] = NaN and no -1 term in its row of dz
+ *   (nothing is read out of bounds). */
 int cnn_relu_fwd(cnn_ctx* ctx, size_t n, const float* z, float* a);
 int cnn_relu_bwd(cnn_ctx* ctx, size_t n, const float* z, const float* da, float* dz);
 int cnn_maxpool2_fwd(cnn_ctx* ctx, size_t planes, int H, int W, const float* x, float* y, uint8_t* arg);

@@ -76,8 +76,8 @@ class CnnError(RuntimeError):
 
 
 def library_path():
-    """The in-tree library; LIBCNN_PATH points tuning runs at an alternative build of the same sources."""
-    return os.environ.get("LIBCNN_PATH") or _build.LIB
+    """The in-tree library, the only one this binding loads."""
+    return _build.LIB
 
 
 def ensure_built():

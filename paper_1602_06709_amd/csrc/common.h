@@ -6,7 +6,28 @@
 
 #include "../../include/cnn.h"
 
+#include <atomic>
+#include <stdarg.h>
+#include <stdio.h>
+#include <string>
 #include <vector>
+
+// ---- device-side vocabulary shared by the matrix-core kernels
+typedef float f32x16 __attribute__((ext_vector_type(16)));     // accumulator of one v_mfma_f32_32x32x2_f32
+typedef __attribute__((address_space(3))) float lds_float;      // LDS pointers are 32-bit: one VGPR each
+constexpr int kOutOfRange = (int)0x80000000;   // buffer-load byte offset beyond any descriptor used here -> reads 0
+constexpr int kRsrcWord3 = 0x00020000;         // raw buffer descriptor of 32-bit elements
+
+// printf into a std::string.  Each kernel instantiation builds its profile name once in a function-local static
+// (initialised thread-safely by the language), so two contexts on two threads never write one buffer.
+inline std::string strf(const char* fmt, ...) {
+    char buf[160];
+    va_list ap;
+    va_start(ap, fmt);
+    vsnprintf(buf, sizeof(buf), fmt, ap);
+    va_end(ap);
+    return std::string(buf);
+}
 
 struct ProfEntry {
     const char* name;

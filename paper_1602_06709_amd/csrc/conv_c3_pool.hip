@@ -22,13 +22,9 @@
 
 namespace {
 
-typedef float f32x16 __attribute__((ext_vector_type(16)));
 typedef float f32x4 __attribute__((ext_vector_type(4)));
-typedef __attribute__((address_space(3))) float lds_float;      // LDS pointers are 32-bit: one VGPR each
 typedef __attribute__((address_space(3))) f32x4 lds_f32x4;
 
-constexpr int kOutOfRange = (int)0x80000000;   // buffer-load byte offset beyond any descriptor used here -> reads 0
-constexpr int kRsrcWord3 = 0x00020000;         // raw buffer descriptor of 32-bit elements
 
 constexpr int kW = 224, kK = 64;               // columns, output features
 constexpr int kBR = 14;                        // output rows per band
@@ -209,7 +205,7 @@ bool c3_pool_serves(const ConvShape& s) {
 
 int c3_pool_conv_fwd(cnn_ctx* ctx, const ConvShape& s, const float* x, const float* w, float* a, unsigned char* arg) {
     if (!c3_pool_serves(s)) return CNN_EUNSUPPORTED;
-    static bool attr_done = false;
+    static std::atomic<bool> attr_done{false};
     if (!attr_done) {
         hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(&k_conv_c3_pool),
                                            hipFuncAttributeMaxDynamicSharedMemorySize, kLdsBytes);

@@ -22,7 +22,6 @@
 
 namespace {
 
-typedef float f32x16 __attribute__((ext_vector_type(16)));
 
 constexpr int KC = 32;
 constexpr int kFar = 1 << 24;     // a coordinate no image reaches: marks table entries and columns past the end
@@ -390,16 +389,15 @@ int launch(cnn_ctx* ctx, const IgPlan& p, const ConvShape& s, const float* A, co
               (unsigned)(MODE == BWD ? s.stride * s.stride : p.nsplit));
     constexpr int lds_bytes = (2 * (TM * (KC + 1) + (MODE != WGR ? KC * TN : TN * (KC + 1))) + 4 * (MODE != WGR ? 2 * KC : TN)) *
                               (int)sizeof(float);
-    static bool attr_done = false;
+    static std::atomic<bool> attr_done{false};
     if (!attr_done && lds_bytes > 48 * 1024) {
         hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(&k_conv_igemm<MODE, WMT, 2>),
                                            hipFuncAttributeMaxDynamicSharedMemorySize, lds_bytes);
         if (e != hipSuccess) return cnn::hip_check(ctx, e, "hipFuncSetAttribute(conv_igemm)");
         attr_done = true;
     }
-    static char name[64] = "";
-    if (!name[0])
-        snprintf(name, sizeof(name), "k_conv_igemm<%s %dx%d>", MODE == FWD ? "fwd" : MODE == BWD ? "bwd" : "wgrad", TM, TN);
+    static const std::string name_s = strf("k_conv_igemm<%s %dx%d>", MODE == FWD ? "fwd" : MODE == BWD ? "bwd" : "wgrad", TM, TN);
+    const char* const name = name_s.c_str();
     {
         cnn::ProfScope ps(ctx, name, cnn::conv_flops(s));
         hipLaunchKernelGGL((k_conv_igemm<MODE, WMT, 2>), grid, dim3(256), lds_bytes, ctx->stream, a, A, B, act, first);

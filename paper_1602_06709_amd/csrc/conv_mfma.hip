@@ -38,8 +38,6 @@
 
 namespace {
 
-typedef float f32x16 __attribute__((ext_vector_type(16)));
-typedef __attribute__((address_space(3))) float lds_float;      // LDS pointers are 32-bit: one VGPR each
 
 // epilogues: plain store; ReLU of the result; result where aux > 0 else 0 (ReLU derivative, aux = the ReLU's output);
 // ReLU followed by 2x2 / stride-2 max-pooling: only the pooled result and the window position of each maximum are
@@ -101,8 +99,6 @@ struct ConvCfg {
     static_assert(Q4 <= T, "one pass fetches at least one filter row");
 };
 
-constexpr int kOutOfRange = (int)0x80000000;   // buffer-load byte offset beyond any descriptor used here -> reads 0
-constexpr int kRsrcWord3 = 0x00020000;         // raw buffer descriptor of 32-bit elements
 
 template <class G, bool SK>
 __global__ void __launch_bounds__(G::T, 2)
@@ -726,7 +722,7 @@ typedef int (*LaunchFn)(cnn_ctx*, const LaunchArgs&);
 template <class G>
 int launch(cnn_ctx* ctx, const LaunchArgs& a) {
     constexpr bool kHasSK = G::R == 3 && G::VEC == 4 && G::WM == 4;      // instantiations the planner may run this way
-    static size_t attr_bytes = 48 * 1024;
+    static std::atomic<size_t> attr_bytes{48 * 1024};
     if (a.lds_bytes > attr_bytes) {
         hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(&k_conv_tiled<G, false>),
                                            hipFuncAttributeMaxDynamicSharedMemorySize, (int)a.lds_bytes);
@@ -742,15 +738,14 @@ int launch(cnn_ctx* ctx, const LaunchArgs& a) {
         const long total = (long)a.g.ptiles * a.g.mtiles * a.g.sk_nchunks;
         grid = dim3((unsigned)((total + a.g.sk_share - 1) / a.g.sk_share));
     }
-    static char name[96] = "";
-    if (!name[0] && G::WLDP_CT)
-        snprintf(name, sizeof(name), "k_conv_tiled<%dx%d CB%d WM%d WN%d NT%d ld%d/%d>", G::R, G::S, G::CB, G::WM, G::WN,
-                 G::NT, G::WLDP_CT, G::PLANEP_CT);
-    if (!name[0])
-        snprintf(name, sizeof(name), "k_conv_tiled<%dx%d CB%d WM%d WN%d NT%d%s>", G::R, G::S, G::CB, G::WM, G::WN, G::NT,
-                 G::VEC == 1 ? " v1" : "");
-    static char name_sk[104] = "";
-    if (!name_sk[0]) snprintf(name_sk, sizeof(name_sk), "%s runs", name);
+    static const std::string name_s =
+        G::WLDP_CT ? strf("k_conv_tiled<%dx%d CB%d WM%d WN%d NT%d ld%d/%d>", G::R, G::S, G::CB, G::WM, G::WN, G::NT,
+                          G::WLDP_CT, G::PLANEP_CT)
+                   : strf("k_conv_tiled<%dx%d CB%d WM%d WN%d NT%d%s>", G::R, G::S, G::CB, G::WM, G::WN, G::NT,
+                          G::VEC == 1 ? " v1" : "");
+    static const std::string name_sk_s = name_s + " runs";
+    const char* const name = name_s.c_str();
+    const char* const name_sk = name_sk_s.c_str();
     {
         cnn::ProfScope ps(ctx, a.g.sk_share ? name_sk : name, 2.0 * a.g.N * a.g.J * a.g.M * G::RS * a.g.HO * a.g.WO);
         if (kHasSK && a.g.sk_share)
@@ -925,10 +920,6 @@ bool make_plan(int R, int S, int pad, int stride, int N, int J, int M, int HI, i
         }
         if (best_nsl > 1) best_tail = (int)tail;
     }
-    if (getenv("CNN_PLAN_DEBUG"))     // diagnostic aid: the chosen plan, one line per planning call, on stderr
-        fprintf(stderr, "plan %dx%d N%d J%d M%d %dx%d: mb%d nt%d TR%d THI%d WLDP%d PLANEP%d%s ptiles%d mtiles%d units%ld lds%zu tail%d nsl%d\n",
-                R, S, N, J, M, HI, WI, v.mb, v.nt, g.TR, g.THI, g.WLDP, g.PLANEP, v.wldp ? " fixed" : "", g.ptiles, g.mtiles, units,
-                p->lds_bytes, best_tail, best_nsl);
     g.tail_per_xcd = best_tail / 8;
     g.full_per_xcd = upx - g.tail_per_xcd;
     g.nsl = best_tail ? best_nsl : 1;
@@ -942,7 +933,7 @@ bool make_plan(int R, int S, int pad, int stride, int N, int J, int M, int HI, i
     // uniform plan needs no reduction at all.
     g.sk_share = g.sk_pmax = 0;
     g.sk_nchunks = nchunks;
-    if (rounds == 0 && v.vec == 4 && R == 3 && v.mb == 128 && !getenv("CNN_NO_RUNS")) {
+    if (rounds == 0 && v.vec == 4 && R == 3 && v.mb == 128) {
         const long total = live * nchunks;
         const int share = (int)((total + slots - 1) / slots);
         const double unit_us = 2.0 * J * R * S * v.mb * (v.nt * v.wn * 32) / 0.55e12 * 1e6;     // one unit on one compute unit

@@ -20,11 +20,7 @@
 
 namespace {
 
-typedef float f32x16 __attribute__((ext_vector_type(16)));
-typedef __attribute__((address_space(3))) float lds_float;      // LDS pointers are 32-bit: one VGPR each
 
-constexpr int kOutOfRange = (int)0x80000000;   // buffer-load byte offset beyond any descriptor used here -> reads 0
-constexpr int kRsrcWord3 = 0x00020000;         // raw buffer descriptor of 32-bit elements
 
 template <int R_, int S_, int ST_, int TH_, int WI_, int KBK_, int NT_>
 struct C3Cfg {
@@ -199,7 +195,7 @@ int c3_strided_conv_fwd(cnn_ctx* ctx, const ConvShape& s, const float* x, const 
     if (s.C != 3 || s.R != G::R || s.S != G::S || s.stride != G::ST || s.pad != 0 || s.W != G::WI || s.H != s.W ||
         s.K > G::KROWS)
         return CNN_EUNSUPPORTED;
-    static bool attr_done = false;
+    static std::atomic<bool> attr_done{false};
     if (!attr_done) {
         hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(&k_conv_c3_strided<G>),
                                            hipFuncAttributeMaxDynamicSharedMemorySize, G::LDS_BYTES);

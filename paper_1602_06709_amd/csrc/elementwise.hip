@@ -201,8 +201,11 @@ __global__ void __launch_bounds__(kBlock) k_softmax_xent(int N, int O, const flo
         __syncthreads();
     }
     sum = red[0];
+    // labels live in device memory, so the host cannot validate them: a label outside [0, O) reads nothing, gives
+    // this sample a NaN loss and leaves its row of dz as the plain softmax / N
     const int lab = label[n];
-    if (threadIdx.x == 0 && loss) loss[n] = -((zr[lab] - m) - logf(sum));
+    const bool lab_ok = (unsigned)lab < (unsigned)O;
+    if (threadIdx.x == 0 && loss) loss[n] = lab_ok ? -((zr[lab] - m) - logf(sum)) : __builtin_nanf("");
     if (dz) {
         const float inv = 1.0f / sum, invN = 1.0f / (float)N;
         for (int o = threadIdx.x; o < O; o += kBlock)

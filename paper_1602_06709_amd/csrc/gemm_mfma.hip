@@ -22,14 +22,10 @@
 
 namespace {
 
-typedef float f32x16 __attribute__((ext_vector_type(16)));
-typedef __attribute__((address_space(3))) float lds_float;      // LDS pointers are 32-bit: one VGPR each
 typedef float f32x4 __attribute__((ext_vector_type(4)));
 typedef __attribute__((address_space(3))) f32x4 lds_f32x4;
 
 constexpr int KC = 32;   // contraction elements per LDS chunk
-constexpr int kOutOfRange = (int)0x80000000;   // buffer-load byte offset beyond any descriptor used here -> reads 0
-constexpr int kRsrcWord3 = 0x00020000;         // raw buffer descriptor of 32-bit elements
 
 // KS: wave groups that share a tile and split every chunk's contraction steps between them (their accumulators are
 // added through LDS at the end).  With one workgroup per compute unit it doubles the waves per SIMD, which is what
@@ -430,7 +426,7 @@ template <class G>
 int launch(cnn_ctx* ctx, const GemmPlan& p, int M, int Nn, int Kd, const float* A, const float* B, const GradSink& sink) {
     const GradSink first = p.nsplit > 1 ? sink_dw(reinterpret_cast<float*>(ctx->ws)) : sink;
     constexpr int lds_bytes = 2 * G::BUF * (int)sizeof(float);
-    static bool attr_done = false;
+    static std::atomic<bool> attr_done{false};
     if (!attr_done && lds_bytes > 48 * 1024) {
         hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(&k_gemm<G>),
                                            hipFuncAttributeMaxDynamicSharedMemorySize, lds_bytes);
@@ -438,12 +434,11 @@ int launch(cnn_ctx* ctx, const GemmPlan& p, int M, int Nn, int Kd, const float* 
         attr_done = true;
     }
     dim3 grid((unsigned)((Nn + G::TN - 1) / G::TN), (unsigned)((M + G::TM - 1) / G::TM), (unsigned)p.nsplit);
-    static char name[96] = "";
-    if (!name[0])
-        snprintf(name, sizeof(name), "k_gemm<%dx%d %s%s%s>", G::TM, G::TN, G::AKM ? "At" : "A", G::BKM ? "B" : "Bt",
-                 G::KS == 2 ? " x2" : "");
-    static char name_sgd[96] = "";
-    if (!name_sgd[0]) snprintf(name_sgd, sizeof(name_sgd), "%s+sgd", name);
+    static const std::string name_s = strf("k_gemm<%dx%d %s%s%s>", G::TM, G::TN, G::AKM ? "At" : "A", G::BKM ? "B" : "Bt",
+                                           G::KS == 2 ? " x2" : "");
+    static const std::string name_sgd_s = name_s + "+sgd";
+    const char* const name = name_s.c_str();
+    const char* const name_sgd = name_sgd_s.c_str();
     {
         cnn::ProfScope ps(ctx, first.w ? name_sgd : name, 2.0 * M * Nn * Kd);
         hipLaunchKernelGGL(k_gemm<G>, grid, dim3(G::T), lds_bytes, ctx->stream, M, Nn, Kd, p.k_per_split, A, B, first);

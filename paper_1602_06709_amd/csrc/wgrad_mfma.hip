@@ -21,11 +21,7 @@
 
 namespace {
 
-typedef float f32x16 __attribute__((ext_vector_type(16)));
-typedef __attribute__((address_space(3))) float lds_float;      // LDS pointers are 32-bit: one VGPR each
 
-constexpr int kOutOfRange = (int)0x80000000;   // buffer-load byte offset beyond any descriptor used here -> reads 0
-constexpr int kRsrcWord3 = 0x00020000;         // raw buffer descriptor of 32-bit elements
 
 struct WgGeo {
     int N, C, K, HI, WI, HO, WO, pad;
@@ -423,6 +419,9 @@ bool make_plan(const ConvShape& s, Plan* p) {
         }
     }
     if (!best_tw) return false;
+    // widths without a usable divisor (primes such as 37) would run a handful of pixels per 32-wide MFMA step over
+    // dozens of column tiles, each with its own copy of dw: the implicit-GEMM weight gradient serves those
+    if (best_nbi * best_tw < 16 && s.Q / best_tw > 4) return false;
     WgGeo& g = p->g;
     g.N = s.N; g.C = s.C; g.K = s.K; g.HI = s.H; g.WI = s.W; g.HO = s.P; g.WO = s.Q; g.pad = s.pad;
     g.TW = best_tw; g.NBI = best_nbi; g.WLD = best_tw + G::S - 1;
@@ -459,7 +458,7 @@ bool make_plan(const ConvShape& s, Plan* p) {
 template <class G>
 int launch(cnn_ctx* ctx, const Plan& p, const ConvShape& s, const float* x, const float* dy, const GradSink& sink) {
     if (ctx->ws_bytes < p.ws_bytes || !ctx->ws) return CNN_EWORKSPACE;
-    static size_t attr_bytes = 48 * 1024;
+    static std::atomic<size_t> attr_bytes{48 * 1024};
     if (p.lds_bytes > attr_bytes) {
         hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(&k_wgrad<G>),
                                            hipFuncAttributeMaxDynamicSharedMemorySize, (int)p.lds_bytes);
@@ -468,11 +467,10 @@ int launch(cnn_ctx* ctx, const Plan& p, const ConvShape& s, const float* x, cons
     }
     float* partial = reinterpret_cast<float*>(ctx->ws);
     dim3 grid((unsigned)(p.nsplit * p.g.col_tiles), (unsigned)p.ctiles, (unsigned)p.ktiles);
-    static char name[96] = "";
-    if (!name[0] && G::FIXED)
-        snprintf(name, sizeof(name), "k_wgrad<%dx%d KW%d CW%d RW%d tw%dx%d>", G::R, G::S, G::KW, G::CW, G::RW, G::TW_CT,
-                 G::NBI_CT);
-    if (!name[0]) snprintf(name, sizeof(name), "k_wgrad<%dx%d KW%d CW%d RW%d>", G::R, G::S, G::KW, G::CW, G::RW);
+    static const std::string name_s =
+        G::FIXED ? strf("k_wgrad<%dx%d KW%d CW%d RW%d tw%dx%d>", G::R, G::S, G::KW, G::CW, G::RW, G::TW_CT, G::NBI_CT)
+                 : strf("k_wgrad<%dx%d KW%d CW%d RW%d>", G::R, G::S, G::KW, G::CW, G::RW);
+    const char* const name = name_s.c_str();
     {
         cnn::ProfScope ps(ctx, name, cnn::conv_flops(s));
         hipLaunchKernelGGL(k_wgrad<G>, grid, dim3(G::T), p.lds_bytes, ctx->stream, p.g, x, dy, partial);

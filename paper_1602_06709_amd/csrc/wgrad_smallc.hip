@@ -16,7 +16,6 @@
 
 namespace {
 
-typedef float f32x16 __attribute__((ext_vector_type(16)));
 
 struct SmallcArgs {
     int N, C, H, W, K, R, S, stride, pad, P, Q;
@@ -355,7 +354,7 @@ template <int KBK, int JB, int JW, int PW, int CC, int ST, int NPASS, bool POOL 
 int launch(cnn_ctx* ctx, const SmallcPlan& p, const ConvShape& s, const float* x, const float* dy, const GradSink& sink,
            const unsigned char* parg = nullptr) {
     auto kern = &k_wgrad_smallc<KBK, JB, JW, PW, CC, ST, NPASS, POOL>;
-    static bool attr_done = false;
+    static std::atomic<bool> attr_done{false};
     if (!attr_done) {
         hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(kern), hipFuncAttributeMaxDynamicSharedMemorySize,
                                            150 * 1024);
@@ -363,8 +362,8 @@ int launch(cnn_ctx* ctx, const SmallcPlan& p, const ConvShape& s, const float* x
         attr_done = true;
     }
     float* partial = reinterpret_cast<float*>(ctx->ws);
-    static char name[64] = "";
-    if (!name[0]) snprintf(name, sizeof(name), "k_wgrad_smallc<KB%d JB%d JW%d PW%d ST%d%s>", KBK, JB, JW, PW, ST, POOL ? " unpool" : "");
+    static const std::string name_s = strf("k_wgrad_smallc<KB%d JB%d JW%d PW%d ST%d%s>", KBK, JB, JW, PW, ST, POOL ? " unpool" : "");
+    const char* const name = name_s.c_str();
     {
         cnn::ProfScope ps(ctx, name, cnn::conv_flops(s));
         hipLaunchKernelGGL(kern, dim3((unsigned)(p.nsplit * p.a.col_tiles)), dim3(256), p.lds_bytes, ctx->stream, p.a, x, dy,

@@ -39,20 +39,89 @@ def check_elementwise(name, got, ref, atol_scale=None, rel_l2=REL_L2, ulps=4):
 
 
 def np_(t):
-    return t.detach().cpu().numpy()
+    return t if isinstance(t, np.ndarray) else t.detach().cpu().numpy()
+
+
+def check_fused_update(name, w0, v0, g_ref, sabs, w_got, v_got, lr, mu):
+    """w_got / v_got against the oracle's SGD step on the oracle's gradient: the gradient's contraction bound,
+    carried through the update, plus a few ulp of the update's own operands."""
+    wo, vo = oracle.sgd_update(w0, g_ref, v0, lr, mu)
+    sabs = np.asarray(sabs, np.float64).ravel()
+    ulp = 4 * 2.0 ** -23
+    vel = vo if vo is not None else np.asarray(g_ref, np.float64).ravel()
+    if vo is not None:
+        dv = np.abs(np_(v_got).astype(np.float64).ravel() - vo)
+        assert np.all(dv <= PER_ELEM * sabs + ulp * (mu * np.abs(v0.ravel()) + np.abs(vel))), name + ": v"
+        assert np.linalg.norm(np_(v_got).astype(np.float64).ravel() - vo) <= REL_L2 * np.linalg.norm(vo), name + ": v rel-L2"
+    dw_ = np.abs(np_(w_got).astype(np.float64).ravel() - wo)
+    assert np.all(dw_ <= lr * PER_ELEM * sabs + ulp * (np.abs(w0.ravel()) + lr * np.abs(vel))), name + ": w"
+    # the step actually taken, w0 - w, against lr * velocity (not drowned by |w|)
+    step_got = w0.astype(np.float64).ravel() - np_(w_got).astype(np.float64).ravel()
+    step_ref = w0.astype(np.float64).ravel() - wo
+    slack = 2.0 ** -23 * np.linalg.norm(w0)      # rounding of w itself
+    assert np.linalg.norm(step_got - step_ref) <= REL_L2 * np.linalg.norm(step_ref) + slack, name + ": step rel-L2"
 
 
 def sample(cfg, tid, total, count):
     return synth.sample_indices(cfg, tid, total, count)
 
 
-def check_trace_item(item, cfg, layers, full, n_samples=20000, n_samples_wgrad=1500):
+def _check_folded(name, cfg, i, wi, g_full, g_at, size, w_got, v_got, pre, lr, momentum, full, count):
+    """A weight gradient that went straight into the SGD step: the oracle's gradient (whole tensor, or at a seeded
+    sample of elements) pushed through the oracle's update from the weights and velocity held before the call."""
+    w0, v0 = pre[0][wi], pre[1][wi]
+    if full:
+        g_ref, sabs = g_full()
+        idx = slice(None)
+    else:
+        idx = sample(cfg, 7000 + i, size, count)
+        g_ref, sabs = g_at(idx)
+    pick = lambda a: None if a is None else np.ascontiguousarray(a.ravel()[idx])
+    check_fused_update(name, pick(w0), pick(v0), g_ref.ravel(), sabs, pick(np_(w_got)),
+                       pick(np_(v_got)) if v_got is not None else None, lr, momentum)
+    return 0.0
+
+
+def check_trace_item(item, cfg, layers, full, n_samples=20000, n_samples_wgrad=1500, pre=None, lr=None, momentum=None):
     """Re-evaluate one recorded libcnn call with the oracle on the very tensors it consumed.
-    full=True compares whole tensors; otherwise a seeded sample of output elements."""
+    full=True compares whole tensors; otherwise a seeded sample of output elements.
+    pre = (weights, velocities) per weighted layer as they were before the step: needed by the calls that fold the
+    SGD update into the weight gradient (their w, v are updated in place), with the step's lr and momentum."""
     op = item[0]
     i = item[1]
     L = layers[i]
     name = f"cfg{cfg}:{op}@layer{i}"
+    if op == "conv_bwd_weight_sgd":
+        _, _, wi, x, dy, w, v = item
+        x, dy = np_(x), np_(dy)
+        return _check_folded(name, cfg, i, wi,
+                             lambda: oracle.conv_bwd_weight(x, dy, L[3], L[4], L[5], L[6], with_abs=True),
+                             lambda idx: oracle.conv_bwd_weight_at(x, dy, L[3], L[4], idx, L[5], L[6]),
+                             w.numel(), w, v, pre, lr, momentum, full, n_samples_wgrad)
+    if op == "conv_bwd_weight_unpool_sgd":
+        _, _, wi, x, dpool, arg, w, v = item
+        x, dpool, arg = np_(x), np_(dpool), np_(arg)
+        dy = oracle.maxpool2_bwd(dpool, arg, 2 * dpool.shape[2], 2 * dpool.shape[3]).astype(np.float32)
+        return _check_folded(name, cfg, i, wi,
+                             lambda: oracle.conv_bwd_weight(x, dy, L[3], L[4], L[5], L[6], with_abs=True),
+                             lambda idx: oracle.conv_bwd_weight_at(x, dy, L[3], L[4], idx, L[5], L[6]),
+                             w.numel(), w, v, pre, lr, momentum, full, n_samples_wgrad)
+    if op == "fc_bwd_sgd":
+        _, _, wi, x, w, dy, dx, v = item
+        x, dy = np_(x), np_(dy)
+        r = 0.0
+        if dx is not None:       # backpropagation must have read the weights as they were before the update
+            w_before, dxn = pre[0][wi], np_(dx)
+            if full:
+                ref, s = oracle.fc_bwd_data(dy, w_before, with_abs=True)
+                r = check_contraction(name + ":dx", dxn, ref, s)
+            else:
+                idx = sample(cfg, 6000 + i, dxn.size, n_samples)
+                ref, s = oracle.fc_bwd_data_at(dy, w_before, idx)
+                r = check_contraction(name + ":dx", dxn.ravel()[idx], ref, s)
+        _check_folded(name, cfg, i, wi, lambda: oracle.fc_bwd_weight(x, dy, with_abs=True),
+                      lambda idx: oracle.fc_bwd_weight_at(x, dy, idx), w.numel(), w, v, pre, lr, momentum, full, n_samples)
+        return r
     if op == "conv_fwd":
         _, _, wi, x, w, y = item
         x, w, y = np_(x), np_(w), np_(y)

@@ -219,7 +219,9 @@ def _generic_shapes(cnn, ctx):
 IGEMM_CASES = [(2, 256, 28, 28, 512, 1, 1, 1, 0), (3, 64, 56, 56, 128, 3, 3, 2, 1), (2, 96, 27, 27, 40, 1, 1, 2, 0),
                (2, 32, 30, 22, 72, 1, 7, 1, 3), (2, 24, 22, 30, 136, 7, 1, 1, 0), (2, 16, 20, 20, 33, 9, 9, 1, 4),
                (3, 20, 17, 23, 70, 2, 2, 2, 0), (2, 40, 33, 31, 64, 4, 4, 4, 2), (1, 130, 19, 19, 200, 3, 3, 3, 1),
-               (2, 128, 28, 28, 256, 5, 5, 2, 2), (1, 5, 6, 6, 3, 2, 3, 1, 1), (65, 8, 9, 9, 16, 3, 2, 2, 1)]
+               (2, 128, 28, 28, 256, 5, 5, 2, 2), (1, 5, 6, 6, 3, 2, 3, 1, 1), (65, 8, 9, 9, 16, 3, 2, 2, 1),
+               # stride-1 3x3 with a prime width: the ring-buffer weight gradient has no column tile for it
+               (2, 32, 20, 37, 48, 3, 3, 1, 1), (1, 24, 12, 67, 40, 3, 3, 1, 1)]
 
 
 @pytest.mark.parametrize("case", IGEMM_CASES)
@@ -409,26 +411,6 @@ def test_sgd_update(cnn, ctx, n):
     P.check_elementwise("w0", P.np_(w2), wo, atol_scale=np.abs(w) + 0.01 * np.abs(g))
 
 
-def _check_fused_update(name, w0, v0, g_ref, sabs, w_got, v_got, lr, mu):
-    """w_got / v_got against the oracle's SGD step on the oracle's gradient: the gradient's contraction bound,
-    carried through the update, plus a few ulp of the update's own operands."""
-    wo, vo = oracle.sgd_update(w0, g_ref, v0, lr, mu)
-    sabs = np.asarray(sabs, np.float64).ravel()
-    ulp = 4 * 2.0 ** -23
-    vel = vo if vo is not None else np.asarray(g_ref, np.float64).ravel()
-    if vo is not None:
-        dv = np.abs(P.np_(v_got).astype(np.float64).ravel() - vo)
-        assert np.all(dv <= P.PER_ELEM * sabs + ulp * (mu * np.abs(v0.ravel()) + np.abs(vel))), name + ": v"
-        assert np.linalg.norm(P.np_(v_got).astype(np.float64).ravel() - vo) <= P.REL_L2 * np.linalg.norm(vo), name + ": v rel-L2"
-    dw_ = np.abs(P.np_(w_got).astype(np.float64).ravel() - wo)
-    assert np.all(dw_ <= lr * P.PER_ELEM * sabs + ulp * (np.abs(w0.ravel()) + lr * np.abs(vel))), name + ": w"
-    # the step actually taken, w0 - w, against lr * velocity (not drowned by |w|)
-    step_got = w0.astype(np.float64).ravel() - P.np_(w_got).astype(np.float64).ravel()
-    step_ref = w0.astype(np.float64).ravel() - wo
-    slack = 2.0 ** -23 * np.linalg.norm(w0)      # rounding of w itself
-    assert np.linalg.norm(step_got - step_ref) <= P.REL_L2 * np.linalg.norm(step_ref) + slack, name + ": step rel-L2"
-
-
 # (N, C, H, K, R, stride, pad): whole-tile and ragged 3x3, 5x5, the two first-layer kernels, one split / many splits
 WSGD_CASES = [(4, 64, 28, 128, 3, 1, 1), (3, 16, 28, 72, 3, 1, 1), (2, 32, 12, 64, 5, 1, 2), (2, 3, 32, 64, 3, 1, 1),
               (2, 3, 63, 96, 11, 4, 0), (8, 128, 14, 256, 3, 1, 1), (1, 64, 56, 128, 3, 1, 1)]
@@ -452,7 +434,7 @@ def test_conv_weight_gradient_with_the_sgd_step_folded_in(cnn, ctx, case):
         assert torch.equal(w, w2), "folded update differs from gradient + cnn_sgd_update"
         if use_v:
             assert torch.equal(v, v2)
-        _check_fused_update(f"wsgd{case}", w0, v0 if use_v else None, g_ref, sabs, w, v, lr, mu)
+        P.check_fused_update(f"wsgd{case}", w0, v0 if use_v else None, g_ref, sabs, w, v, lr, mu)
 
 
 def test_folded_sgd_refuses_what_only_the_plain_kernels_serve(cnn, ctx):
@@ -490,7 +472,7 @@ def test_fc_backward_with_the_sgd_step_folded_in(cnn, ctx, case):
         torch.cuda.synchronize()
         assert torch.equal(r[0], dx_u), "dx must come from the weights before the update"
         assert torch.equal(w, w2) and (not use_v or torch.equal(v, v2))
-        _check_fused_update(f"fcsgd{case}", w0, v0 if use_v else None, g_ref, sabs, w, v, lr, mu)
+        P.check_fused_update(f"fcsgd{case}", w0, v0 if use_v else None, g_ref, sabs, w, v, lr, mu)
     # first layer: no dx
     w = dev(w0)
     r = cnn.cnn_fc_bwd_sgd(ctx, dev(x), w, dev(dy), None, False, None, 0.05, 0.0)
@@ -654,12 +636,13 @@ def test_fused_pool_where_the_two_calls_cut_the_contraction_differently(cnn, ctx
     P.check_trace_item(("conv_fwd_relu_pool", 0, 0, dev(x), dev(w), a, arg), 0, [("conv", C, K, 3, 3, 1, 1)], True)
 
 
-@pytest.mark.parametrize("cfg", [2, 5, 4, 3])
-def test_training_steps_with_folded_sgd_equal_the_separate_update(cnn, ctx, cfg):
+@pytest.mark.parametrize("cfg,n", [(2, None), (5, None), (4, 8), (3, 8), (4, None), (3, None)])
+def test_training_steps_with_folded_sgd_equal_the_separate_update(cnn, ctx, cfg, n):
     # two iterations (the second one uses the first one's velocity) of each workload, once with the update inside
     # the weight gradients and once as gradient arena + one cnn_sgd_update: same weights and velocity, bit for bit
+    # (n = None: the workload's own minibatch -- 64 for VGG-A and OverFeat-FAST, what the benchmark times)
     from paper_1602_06709_amd.net import Net
-    wl = synth.workload(cfg, 8 if cfg in (3, 4) else None)
+    wl = synth.workload(cfg, n)
     if not wl.sgd:       # workloads defined without an update take one here
         wl = dataclasses.replace(wl, sgd=True, lr=0.01, momentum=0.9)
     say(f"folded-sgd steps cfg{cfg} N={wl.input_shape[0]}")
@@ -755,12 +738,50 @@ def test_training_stays_finite_and_the_loss_falls(cnn, ctx, cfg, n):
     assert losses[-1] < losses[0]
 
 
-def test_config5_dnn7_n1024_sampled(cnn, ctx):
-    _run_and_check(cnn, ctx, 5, None, False, n_samples=20000)
+def _run_folded_step_and_check(cnn, ctx, cfg, full, **kw):
+    """The sequence the benchmark times -- Net.step() with the SGD update inside every weight gradient, a layer's
+    backpropagation issued before it -- at the workload's own minibatch, every call against the oracle.  One step
+    first, so that the checked step starts from a non-zero velocity."""
+    from paper_1602_06709_amd.net import Net
+    wl = synth.workload(cfg)
+    say(f"folded step cfg{cfg} N={wl.input_shape[0]} full={full}")
+    net = Net(ctx, wl, synth.make_weights(wl), record=True)
+    assert net.fuse_sgd and wl.sgd
+    net.set_input(synth.make_input(wl), synth.make_labels(wl))
+    net.step()
+    torch.cuda.synchronize()
+    w0 = [P.np_(w).copy() for w in net.w]
+    v0 = [P.np_(v).copy() if v is not None else None for v in net.v]
+    net.step()
+    torch.cuda.synchronize()
+    ops = [item[0] for item in net.trace]
+    n_weighted = sum(1 for L in wl.layers if L[0] in ("conv", "fc"))
+    assert sum(op.endswith("_sgd") for op in ops) == n_weighted, ops      # every update went through a folded call
+    assert not any(op in ("conv_bwd_weight", "fc_bwd", "conv_bwd_weight_unpool") for op in ops), ops
+    for item in net.trace:
+        if not item[0].endswith("_sgd"):
+            # the call read this step's weights, which the folded update has since overwritten in place
+            wi = item[2] if item[0].startswith(("conv_", "fc_")) else None
+            item = tuple(w0[wi] if (wi is not None and isinstance(t, torch.Tensor) and t.data_ptr() == net.w[wi].data_ptr())
+                         else t for t in item)
+        r = P.check_trace_item(item, cfg, wl.layers, full, pre=(w0, v0), lr=wl.lr, momentum=wl.momentum, **kw)
+        say(f"  {item[0]}@{item[1]} rel-L2 {r:.2e}")
+
+
+def test_config5_dnn7_n1024_full_tensors(cnn, ctx):
+    _run_and_check(cnn, ctx, 5, None, True)
+
+
+def test_config5_dnn7_n1024_folded_step_full_tensors(cnn, ctx):
+    _run_folded_step_and_check(cnn, ctx, 5, True)
 
 
 def test_config3_vgg_a_full_n64_sampled(cnn, ctx):
     _run_and_check(cnn, ctx, 3, None, False, n_samples=8000, n_samples_wgrad=400)
+
+
+def test_config3_vgg_a_full_n64_folded_step_sampled(cnn, ctx):
+    _run_folded_step_and_check(cnn, ctx, 3, False, n_samples=8000, n_samples_wgrad=400)
 
 
 def test_config4_overfeat_fast_n64_sampled(cnn, ctx):
