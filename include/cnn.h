@@ -90,6 +90,19 @@ int cnn_profile_count(const cnn_ctx* ctx);
 int cnn_profile_get(cnn_ctx* ctx, int index, const char** kernel_name, double* flops, float* ms);
 int cnn_profile_reset(cnn_ctx* ctx);
 
+/* ---- What this GPU sustains on the two resources the kernels are bound by (measurement aids; results are read
+ *   through CNN_OPT_PROFILE timings or events of the caller's own around the call).
+ *   cnn_probe_mfma: 512 workgroups of four waves issue iters * 8 register-only fp32 matrix-core instructions
+ *     (v_mfma_f32_32x32x2_f32, the one every contraction kernel here is built on) per wave; *flops (host, may be
+ *     NULL) receives the FLOPs of the launch.  sink: device memory, CNN_PROBE_SINK_FLOATS floats, overwritten.
+ *   cnn_probe_stream: one pass over n floats (n a multiple of 4) in the launch shape of cnn_sgd_update:
+ *     CNN_STREAM_READ reads src (dst needs one float and is not written), CNN_STREAM_WRITE fills dst (src may be
+ *     NULL), CNN_STREAM_COPY dst <- src.  4*n bytes read and / or written. */
+enum { CNN_STREAM_READ = 0, CNN_STREAM_WRITE = 1, CNN_STREAM_COPY = 2 };
+#define CNN_PROBE_SINK_FLOATS (512 * 256)
+int cnn_probe_mfma(cnn_ctx* ctx, int iters, float* sink, double* flops);
+int cnn_probe_stream(cnn_ctx* ctx, int mode, size_t n, const float* src, float* dst);
+
 /* ---- Section 2.1, Algorithm 1 "Forward Propagation":
  *   y[n][k][p][q] = sum_{c,r,s} x[n][c][p*stride + r - pad][q*stride + s - pad] * w[k][c][r][s]
  *   (cross-correlation; positions outside the input contribute 0).

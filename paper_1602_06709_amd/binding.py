@@ -33,6 +33,8 @@ SIGNATURES = {
     "cnn_profile_count": (_i, [_vp]),
     "cnn_profile_get": (_i, [_vp, _i, C.POINTER(C.c_char_p), C.POINTER(C.c_double), C.POINTER(C.c_float)]),
     "cnn_profile_reset": (_i, [_vp]),
+    "cnn_probe_mfma": (_i, [_vp, _i, _vp, C.POINTER(C.c_double)]),
+    "cnn_probe_stream": (_i, [_vp, _i, _sz, _vp, _vp]),
     "cnn_conv_fwd": (_i, _CONV),
     "cnn_conv_bwd_data": (_i, _CONV),
     "cnn_conv_bwd_weight": (_i, _CONV),
@@ -176,6 +178,25 @@ class Context:
 
     def reserve_for(self, op, N, Cc, H, W, K, R, S, stride, pad):
         self.reserve(lib().cnn_workspace_bytes(op, N, Cc, H, W, K, R, S, stride, pad))
+
+
+# ---------------------------------------------------------------- measurement aids
+STREAM_READ, STREAM_WRITE, STREAM_COPY = 0, 1, 2
+PROBE_SINK_FLOATS = 512 * 256
+
+
+def cnn_probe_mfma(ctx, iters, sink):
+    """Register-only fp32 matrix-core loop; returns the FLOPs of the launch."""
+    assert sink.numel() >= PROBE_SINK_FLOATS
+    fl = C.c_double()
+    _check(lib().cnn_probe_mfma(ctx.handle, int(iters), _t(sink), C.byref(fl)), ctx.handle)
+    return fl.value
+
+
+def cnn_probe_stream(ctx, mode, src, dst):
+    """One read / write / copy pass over dst.numel() floats (src.numel() for a read)."""
+    n = src.numel() if mode == STREAM_READ else dst.numel()
+    _check(lib().cnn_probe_stream(ctx.handle, mode, n, _t(src) if src is not None else None, _t(dst)), ctx.handle)
 
 
 # ---------------------------------------------------------------- contractions

@@ -92,7 +92,17 @@ class Net:
         if self.record:
             self.trace.append(item)
         if self.marks is not None:
-            self.marks.append((item[0], item[1], self.ctx.profile_count()))
+            # bytes the call must move at least: every tensor it reads or writes once; the weights and velocity a
+            # folded update rewrites in place count twice
+            seen, nbytes = set(), 0
+            for t in item[2:]:
+                if isinstance(t, torch.Tensor) and t.data_ptr() not in seen:
+                    seen.add(t.data_ptr())
+                    nbytes += t.numel() * t.element_size()
+            if item[0].endswith("_sgd"):
+                wi = item[2]
+                nbytes += sum(t.numel() * 4 for t in (self.w[wi], self.v[wi]) if t is not None)
+            self.marks.append((item[0], item[1], self.ctx.profile_count(), nbytes))
 
     def _input_of(self, i):
         j = i - 1
@@ -185,7 +195,7 @@ class Net:
         v = self.v[wi].view(-1) if self.v[wi] is not None else None
         B.cnn_sgd_update(self.ctx, self.w[wi].view(-1), self.dw[wi].view(-1), v, self.wl.lr, self.wl.momentum)
         if self.marks is not None:
-            self.marks.append(("sgd_update", -1, self.ctx.profile_count()))
+            self.marks.append(("sgd_update", -1, self.ctx.profile_count(), 0))
 
     def backward(self, update=False):
         """Expects gact[-1] to hold the gradient of the last activation (from loss() or set_upstream()).
@@ -269,7 +279,7 @@ class Net:
     def sgd(self):
         B.cnn_sgd_update(self.ctx, self.w_arena, self.dw_arena, self.v_arena, self.wl.lr, self.wl.momentum)
         if self.marks is not None:
-            self.marks.append(("sgd_update", -1, self.ctx.profile_count()))
+            self.marks.append(("sgd_update", -1, self.ctx.profile_count(), 0))
 
     # ------------------------------------------------------------ helpers
     def set_input(self, x_np, labels_np=None):

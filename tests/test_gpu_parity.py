@@ -411,6 +411,26 @@ def test_sgd_update(cnn, ctx, n):
     P.check_elementwise("w0", P.np_(w2), wo, atol_scale=np.abs(w) + 0.01 * np.abs(g))
 
 
+def test_measurement_probes(cnn, ctx):
+    # the stream probes move what they say they move; the MFMA probe reports its FLOPs and leaves finite numbers
+    for n in (4, 2048 + 4, (1 << 20) + 12):
+        src = torch.arange(n, dtype=torch.float32, device="cuda"); dst = torch.full((n + 4,), -1.0, device="cuda")
+        cnn.cnn_probe_stream(ctx, cnn.STREAM_COPY, src, dst[:n])
+        torch.cuda.synchronize()
+        assert torch.equal(dst[:n], src) and bool((dst[n:] == -1.0).all())
+        cnn.cnn_probe_stream(ctx, cnn.STREAM_WRITE, None, dst[:n])
+        cnn.cnn_probe_stream(ctx, cnn.STREAM_READ, src, dst[:n])
+        torch.cuda.synchronize()
+        assert torch.equal(dst[:n].view(-1, 4), torch.tensor([1.0, 2.0, 3.0, 4.0], device="cuda").expand(n // 4, 4))
+        assert bool((dst[n:] == -1.0).all())
+    sink = torch.zeros(cnn.PROBE_SINK_FLOATS, device="cuda")
+    fl = cnn.cnn_probe_mfma(ctx, 10, sink)
+    torch.cuda.synchronize()
+    assert fl == 512 * 4 * 10 * 8 * 4096.0 and bool(torch.isfinite(sink).all()) and float(sink.abs().sum()) > 0
+    assert cnn.lib().cnn_probe_stream(ctx.handle, 3, 8, src.data_ptr(), dst.data_ptr()) == -1
+    assert cnn.lib().cnn_probe_stream(ctx.handle, 2, 6, src.data_ptr(), dst.data_ptr()) == -1
+
+
 # (N, C, H, K, R, stride, pad): whole-tile and ragged 3x3, 5x5, the two first-layer kernels, one split / many splits
 WSGD_CASES = [(4, 64, 28, 128, 3, 1, 1), (3, 16, 28, 72, 3, 1, 1), (2, 32, 12, 64, 5, 1, 2), (2, 3, 32, 64, 3, 1, 1),
               (2, 3, 63, 96, 11, 4, 0), (8, 128, 14, 256, 3, 1, 1), (1, 64, 56, 128, 3, 1, 1)]
