@@ -12,8 +12,9 @@ Prints ONE JSON line.  Inputs are resident in HBM before the timed region starts
 
 Timing: `value` = images of the K timed steps / wall-clock between two device synchronisations.  Beside it,
 `step_ms` gives mean / median / best of the K per-step durations (HIP events between the steps, on the stream the
-library launches on), and `clocks` the engine / memory clocks sampled from sysfs by a host thread during the timed
-region.
+library launches on), and `clocks` the engine / memory clocks read from sysfs before the warm-up (idle) and right
+after the timed region (the GPU has just been busy); no read sits between warm-up and timed region or inside it: one
+takes milliseconds, during which an idle GPU drops its clocks.
 `roofline` describes the dominant kernel (largest share of the timed region): achieved = algorithmic FLOPs of its
 launches / their summed duration, measured with HIP events that the library records on its own stream around every
 kernel launch, inside the timed region, on every 5th timed step (`--profile-every`, `profiled_steps` in the
@@ -33,7 +34,6 @@ import os
 import re
 import statistics
 import sys
-import threading
 import time
 
 ROOT = os.path.dirname(os.path.abspath(__file__))
@@ -55,13 +55,11 @@ def csrc_sha():
     return h.hexdigest()[:16]
 
 
-class ClockSampler(threading.Thread):
-    """Reads the current engine (sclk) and memory (mclk) clock levels from sysfs every few milliseconds while the
-    timed region runs: host-side file reads only, nothing is sent to the GPU."""
+class Clocks:
+    """The current engine (sclk) and memory (mclk) clock levels from sysfs: host-side file reads that go through the
+    driver to the power controller and take milliseconds, so none sits inside the timed region or just before it."""
 
-    def __init__(self, pci_bus_id=None, period=0.01):
-        super().__init__(daemon=True)
-        self.period, self.samples, self._stop_evt = period, {"sclk": [], "mclk": []}, threading.Event()
+    def __init__(self, pci_bus_id=None):
         self.files = {}
         devs = sorted(glob.glob("/sys/class/drm/card*/device"))
         if pci_bus_id:
@@ -73,34 +71,18 @@ class ClockSampler(threading.Thread):
                 if key not in self.files and os.access(p, os.R_OK):
                     self.files[key] = p
 
-    @staticmethod
-    def read(path):
-        try:
-            for line in open(path):
-                if line.rstrip().endswith("*"):
-                    m = re.search(r"(\d+)\s*mhz", line, re.I)
-                    if m:
-                        return int(m.group(1))
-        except OSError:
-            pass
-        return None
-
-    def run(self):
-        while not self._stop_evt.is_set():
-            for key, p in self.files.items():
-                v = self.read(p)
-                if v is not None:
-                    self.samples[key].append(v)
-            self._stop_evt.wait(self.period)
-
-    def stop(self):
-        self._stop_evt.set()
-        self.join(timeout=1.0)
+    def read(self):
         out = {}
-        for key, vals in self.samples.items():
-            out[key + "_mhz"] = ({"min": min(vals), "median": statistics.median(vals), "max": max(vals), "samples": len(vals)}
-                                 if vals else None)
-        out["source"] = self.files or "no readable pp_dpm_sclk / pp_dpm_mclk under /sys/class/drm"
+        for key, path in self.files.items():
+            out[key + "_mhz"] = None
+            try:
+                for line in open(path):
+                    if line.rstrip().endswith("*"):
+                        m = re.search(r"(\d+)\s*mhz", line, re.I)
+                        if m:
+                            out[key + "_mhz"] = int(m.group(1))
+            except OSError:
+                pass
         return out
 
 
@@ -212,8 +194,15 @@ def main():
             net.gact[-1].copy_(upstream)     # device-to-device; the gradient buffer is overwritten by backward
         net.step()
 
-    for _ in range(args.warmup):
+    bus = getattr(torch.cuda.get_device_properties(0), "pci_bus_id", None)
+    clocks = Clocks("%02x:00.0" % bus if isinstance(bus, int) else None)
+    clock_report = {"idle_before_warmup": clocks.read()}
+    for i in range(args.warmup):
+        # the last warm-up step runs with the per-kernel events on: the library creates its event objects the first
+        # time a launch is recorded, and that must not happen inside the timed region
+        ctx.profile(not args.no_profile and i == args.warmup - 1)
         step()
+    ctx.profile(False)
     torch.cuda.synchronize()
     prof_steps = [] if args.no_profile else [i for i in range(args.steps) if i % max(1, args.profile_every) == 0]
     ctx.profile_reset()
@@ -221,9 +210,6 @@ def main():
     # per-step events on the stream the library launches on (its context was bound to torch's current stream)
     assert ctx.stream.cuda_stream == torch.cuda.current_stream().cuda_stream
     ev = [torch.cuda.Event(enable_timing=True) for _ in range(args.steps + 1)]
-    bus = getattr(torch.cuda.get_device_properties(0), "pci_bus_id", None)
-    clocks = ClockSampler("%02x:00.0" % bus if isinstance(bus, int) else None)
-    clocks.start()
     t0 = time.perf_counter()
     for i in range(args.steps):
         ev[i].record()
@@ -233,14 +219,16 @@ def main():
     ev[args.steps].record()
     torch.cuda.synchronize()
     dt = time.perf_counter() - t0
-    clock_report = clocks.stop()
+    clock_report["right_after_timed_region"] = clocks.read()
+    clock_report["source"] = clocks.files or "no readable pp_dpm_sclk / pp_dpm_mclk under /sys/class/drm"
     ctx.profile(False)
     net.marks = None
     ms_per_step = dt / args.steps * 1e3
     per_step = [ev[i].elapsed_time(ev[i + 1]) for i in range(args.steps)]
     plain = [t for i, t in enumerate(per_step) if i not in prof_steps] or per_step
     step_ms = {"mean": sum(per_step) / len(per_step), "median": statistics.median(per_step), "best": min(per_step),
-               "worst": max(per_step), "median_of_steps_without_kernel_events": statistics.median(plain)}
+               "worst": max(per_step), "median_of_steps_without_kernel_events": statistics.median(plain),
+               "all": [round(t, 4) for t in per_step]}
     loss = float(net.loss_per_sample.mean().item()) if wl.loss else None
     # a run whose numbers have left the finite range has timed something else (zeros and NaNs also change the clocks)
     finite = all(bool(torch.isfinite(w).all()) for w in net.w) and (loss is None or np.isfinite(loss))

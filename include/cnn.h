@@ -179,6 +179,23 @@ int cnn_fc_fwd(cnn_ctx* ctx, int N, int I, int O, const float* x, const float* w
 int cnn_fc_bwd(cnn_ctx* ctx, int N, int I, int O, const float* x, const float* w, const float* dy,
                float* dx, float* dw);
 
+/* ---- Fully-connected layers with the neighbouring element-wise activation folded into the GEMM's store (one pass
+ *   over the activation tensor less per layer and direction; Section 2.1's loop nest is unchanged):
+ *     cnn_fc_fwd_act:      a = act(x W^T)
+ *     cnn_fc_bwd_act, cnn_fc_bwd_sgd_act: as cnn_fc_bwd / cnn_fc_bwd_sgd for a layer whose input x IS the output of
+ *       `act_in` (the activation behind the previous layer): dz receives the gradient in FRONT of that activation,
+ *       dz = (dy W) * act_in'(.) with ReLU' = 1 where x > 0 (else 0) and sigmoid' = x * (1 - x).
+ *   act / act_in: CNN_ACT_NONE (the plain call), CNN_ACT_RELU, CNN_ACT_SIGMOID.  Same bits as the plain call followed
+ *   by cnn_relu_fwd / cnn_sigmoid_fwd, resp. cnn_relu_bwd(x, .) / cnn_sigmoid_bwd(x, .).  Workspace as the plain
+ *   calls.  CNN_EUNSUPPORTED (nothing launched) for shapes only the plain fallback kernels serve (I or O not a
+ *   multiple of 4): call the unfused pair there. */
+enum { CNN_ACT_NONE = 0, CNN_ACT_RELU = 1, CNN_ACT_SIGMOID = 2 };
+int cnn_fc_fwd_act(cnn_ctx* ctx, int N, int I, int O, const float* x, const float* w, float* a, int act);
+int cnn_fc_bwd_act(cnn_ctx* ctx, int N, int I, int O, const float* x, const float* w, const float* dy, float* dz,
+                   float* dw, int act_in);
+int cnn_fc_bwd_sgd_act(cnn_ctx* ctx, int N, int I, int O, const float* x, float* w, const float* dy, float* dz, float* v,
+                       float lr, float momentum, int act_in);
+
 /* ---- SGD step (the paper's "vanilla SGD", Sections 1 and 3.4; no weight decay, no Nesterov):
  *   v <- momentum * v + dw ;  w <- w - lr * v         (v == NULL: w <- w - lr * dw, momentum ignored)
  *   n elements; w and v updated in place.  One launch over the whole (flat) parameter arena. */

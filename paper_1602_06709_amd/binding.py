@@ -49,6 +49,9 @@ SIGNATURES = {
     "cnn_sgd_update": (_i, [_vp, _sz, _vp, _vp, _vp, _f, _f]),
     "cnn_conv_bwd_weight_sgd": (_i, [_vp] + [_i] * 9 + [_vp] * 4 + [_f, _f]),
     "cnn_fc_bwd_sgd": (_i, [_vp, _i, _i, _i, _vp, _vp, _vp, _vp, _vp, _f, _f]),
+    "cnn_fc_fwd_act": (_i, [_vp, _i, _i, _i, _vp, _vp, _vp, _i]),
+    "cnn_fc_bwd_act": (_i, [_vp, _i, _i, _i, _vp, _vp, _vp, _vp, _vp, _i]),
+    "cnn_fc_bwd_sgd_act": (_i, [_vp, _i, _i, _i, _vp, _vp, _vp, _vp, _vp, _f, _f, _i]),
     "cnn_conv_bwd_weight_unpool": (_i, [_vp] + [_i] * 9 + [_vp] * 4),
     "cnn_conv_bwd_weight_unpool_sgd": (_i, [_vp] + [_i] * 9 + [_vp] * 5 + [_f, _f]),
     "cnn_bf_plane": (C.c_double, [_i] * 5),
@@ -317,6 +320,56 @@ def cnn_fc_bwd(ctx, x, w, dy, need_dx=True, need_dw=True, dx_out=None, dw_out=No
                             _t(dy), _t(dx) if dx is not None else None, _t(dw) if dw is not None else None),
            ctx.handle)
     return dx, dw
+
+
+ACT = {None: 0, "none": 0, "relu": 1, "sigmoid": 2}
+
+
+def cnn_fc_fwd_act(ctx, x, w, act, out=None):
+    """act(x W^T) in one call; returns None (nothing launched) where the library does not serve the shape this way."""
+    N, I = x.shape
+    O, I2 = w.shape
+    assert I == I2
+    ctx.reserve_for(OP_FC_FWD, N, I, 1, 1, O, 1, 1, 1, 0)
+    a = out if out is not None else torch.empty((N, O), dtype=torch.float32, device=x.device)
+    st = lib().cnn_fc_fwd_act(ctx.handle, N, I, O, _t(x), _t(w), _t(a), ACT[act])
+    if st == EUNSUPPORTED:
+        return None
+    _check(st, ctx.handle)
+    return a
+
+
+def cnn_fc_bwd_act(ctx, x, w, dy, act_in, need_dw=True, dz_out=None, dw_out=None):
+    """cnn_fc_bwd for a layer whose input x is the output of `act_in`: dz is the gradient in front of that activation.
+    Returns None (nothing launched) where the library does not serve the shape this way, else (dz, dw)."""
+    N, O = dy.shape
+    I = w.shape[1]
+    ctx.reserve_for(OP_FC_BWD, N, I, 1, 1, O, 1, 1, 1, 0)
+    dz = dz_out if dz_out is not None else torch.empty((N, I), dtype=torch.float32, device=dy.device)
+    dw = None
+    if need_dw:
+        dw = dw_out if dw_out is not None else torch.empty((O, I), dtype=torch.float32, device=dy.device)
+    st = lib().cnn_fc_bwd_act(ctx.handle, N, I, O, _t(x), _t(w), _t(dy), _t(dz), _t(dw) if dw is not None else None,
+                              ACT[act_in])
+    if st == EUNSUPPORTED:
+        return None
+    _check(st, ctx.handle)
+    return dz, dw
+
+
+def cnn_fc_bwd_sgd_act(ctx, x, w, dy, act_in, v=None, dz_out=None, lr=0.01, momentum=0.0):
+    """cnn_fc_bwd_sgd with the derivative of the activation that produced x folded into dz.  None where unsupported."""
+    N, O = dy.shape
+    I = w.shape[1]
+    assert tuple(x.shape) == (N, I) and w.shape[0] == O and (v is None or tuple(v.shape) == tuple(w.shape))
+    ctx.reserve_for(OP_FC_BWD, N, I, 1, 1, O, 1, 1, 1, 0)
+    dz = dz_out if dz_out is not None else torch.empty((N, I), dtype=torch.float32, device=dy.device)
+    st = lib().cnn_fc_bwd_sgd_act(ctx.handle, N, I, O, _t(x), _t(w), _t(dy), _t(dz), _t(v) if v is not None else None,
+                                  lr, momentum, ACT[act_in])
+    if st == EUNSUPPORTED:
+        return None
+    _check(st, ctx.handle)
+    return dz, w
 
 
 def cnn_sgd_update(ctx, w, dw, v=None, lr=0.01, momentum=0.0):

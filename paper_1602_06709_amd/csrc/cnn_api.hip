@@ -400,16 +400,63 @@ int cnn_fc_bwd(cnn_ctx* ctx, int N, int I, int O, const float* x, const float* w
 
 int cnn_fc_bwd_sgd(cnn_ctx* ctx, int N, int I, int O, const float* x, float* w, const float* dy, float* dx, float* v,
                    float lr, float momentum) {
+    return cnn_fc_bwd_sgd_act(ctx, N, I, O, x, w, dy, dx, v, lr, momentum, CNN_ACT_NONE);
+}
+
+// ---- fully-connected layers with the neighbouring activation folded into the GEMM's store
+static bool act_ok(int act) { return act == CNN_ACT_NONE || act == CNN_ACT_RELU || act == CNN_ACT_SIGMOID; }
+
+int cnn_fc_fwd_act(cnn_ctx* ctx, int N, int I, int O, const float* x, const float* w, float* a, int act) {
+    if (!act_ok(act)) return CNN_EINVAL;
+    if (act == CNN_ACT_NONE) return cnn_fc_fwd(ctx, N, I, O, x, w, a);
+    if (!ctx || !x || !w || !a || !aligned16(x) || !aligned16(w) || !aligned16(a)) return CNN_EINVAL;
+    ConvShape s;
+    int st = make_shape(N, I, 1, 1, O, 1, 1, 1, 0, &s);
+    if (st != CNN_OK) return st;
+    if (ctx->force_direct || !cnn::mfma_gemm_serves(N, O, I, 0, 0)) return CNN_EUNSUPPORTED;
+    const GradSink sink = sink_act(a, act == CNN_ACT_RELU ? ACT_RELU : ACT_SIGMOID, nullptr);
+    return cnn::mfma_gemm(ctx, N, O, I, x, 0, w, 0, nullptr, &sink);
+}
+
+int cnn_fc_bwd_act(cnn_ctx* ctx, int N, int I, int O, const float* x, const float* w, const float* dy, float* dz,
+                   float* dw, int act_in) {
+    if (!act_ok(act_in)) return CNN_EINVAL;
+    if (act_in == CNN_ACT_NONE || !dz) return cnn_fc_bwd(ctx, N, I, O, x, w, dy, dz, dw);
+    if (!ctx || !dy || !x || !w || !aligned16(dy) || !aligned16(x) || !aligned16(w) || !aligned16(dz) ||
+        (dw && !aligned16(dw)))
+        return CNN_EINVAL;
+    ConvShape s;
+    int st = make_shape(N, I, 1, 1, O, 1, 1, 1, 0, &s);
+    if (st != CNN_OK) return st;
+    if (ctx->force_direct || !cnn::mfma_gemm_serves(N, I, O, 0, 1)) return CNN_EUNSUPPORTED;
+    if (dw) {
+        st = cnn_fc_bwd(ctx, N, I, O, x, w, dy, nullptr, dw);
+        if (st != CNN_OK) return st;
+    }
+    const GradSink sink = sink_act(dz, act_in == CNN_ACT_RELU ? ACT_RELU_BWD : ACT_SIGMOID_BWD, x);
+    return cnn::mfma_gemm(ctx, N, I, O, dy, 0, w, 1, nullptr, &sink);
+}
+
+int cnn_fc_bwd_sgd_act(cnn_ctx* ctx, int N, int I, int O, const float* x, float* w, const float* dy, float* dz, float* v,
+                       float lr, float momentum, int act_in) {
+    if (!act_ok(act_in)) return CNN_EINVAL;
     if (!ctx || !dy || !x || !w || !aligned16(dy) || !aligned16(x) || !aligned16(w) || (v && !aligned16(v)) ||
-        (dx && !aligned16(dx)))
+        (dz && !aligned16(dz)))
         return CNN_EINVAL;
     ConvShape s;
     int st = make_shape(N, I, 1, 1, O, 1, 1, 1, 0, &s);
     if (st != CNN_OK) return st;
     if (ctx->force_direct || !cnn::mfma_gemm_serves(O, I, N, 1, 1)) return CNN_EUNSUPPORTED;
-    if (dx) {   // backpropagation reads the weights of this iteration: before they are updated
-        st = cnn::mfma_gemm(ctx, N, I, O, dy, 0, w, 1, dx);
-        if (st == CNN_EUNSUPPORTED) st = cnn::direct_conv_bwd_data(ctx, s, dy, w, dx, nullptr);
+    const bool fold = dz && act_in != CNN_ACT_NONE;
+    if (fold && !cnn::mfma_gemm_serves(N, I, O, 0, 1)) return CNN_EUNSUPPORTED;
+    if (dz) {   // backpropagation reads the weights of this iteration: before they are updated
+        if (fold) {
+            const GradSink dsink = sink_act(dz, act_in == CNN_ACT_RELU ? ACT_RELU_BWD : ACT_SIGMOID_BWD, x);
+            st = cnn::mfma_gemm(ctx, N, I, O, dy, 0, w, 1, nullptr, &dsink);
+        } else {
+            st = cnn::mfma_gemm(ctx, N, I, O, dy, 0, w, 1, dz);
+            if (st == CNN_EUNSUPPORTED) st = cnn::direct_conv_bwd_data(ctx, s, dy, w, dz, nullptr);
+        }
         if (st != CNN_OK) return st;
     }
     const GradSink sink{nullptr, w, v, lr, momentum};

@@ -54,13 +54,32 @@ struct ConvShape {
 // into dw[i], or, when w is set, straight into the SGD step of Section 3.4 without dw ever reaching memory:
 //   v[i] <- mu * v[i] + g (when v is set);  w[i] <- w[i] - lr * v[i]   (v == nullptr: w[i] <- w[i] - lr * g)
 // The arithmetic is the one k_sgd applies to a stored gradient, so both routes give the same bits.
+// An activation folded into the store of a plain output (act == ACT_NONE otherwise).  The expressions are the ones
+// the element-wise kernels use, so the folded and the separate route give the same bits.
+//   ACT_RELU / ACT_SIGMOID: the forward activation of the stored value;
+//   ACT_RELU_BWD / ACT_SIGMOID_BWD: the stored value is a gradient behind an activation whose OUTPUT is aux (same
+//   index): it is multiplied by the activation's derivative (ReLU: 1 where aux > 0; sigmoid: aux * (1 - aux)).
+enum { ACT_NONE = 0, ACT_RELU = 1, ACT_SIGMOID = 2, ACT_RELU_BWD = 3, ACT_SIGMOID_BWD = 4 };
+__device__ __forceinline__ float act_apply(int act, float c, float aux) {
+    switch (act) {
+        case ACT_RELU: return c > 0.f ? c : 0.f;
+        case ACT_SIGMOID: return 1.0f / (1.0f + expf(-c));
+        case ACT_RELU_BWD: return aux > 0.f ? c : 0.f;
+        case ACT_SIGMOID_BWD: return c * aux * (1.0f - aux);
+        default: return c;
+    }
+}
+
 struct GradSink {
     float* dw;
     float* w;
     float* v;
     float lr, mu;
+    int act;             // only with w == nullptr
+    const float* aux;
 };
-inline GradSink sink_dw(float* dw) { return GradSink{dw, nullptr, nullptr, 0.f, 0.f}; }
+inline GradSink sink_dw(float* dw) { return GradSink{dw, nullptr, nullptr, 0.f, 0.f, ACT_NONE, nullptr}; }
+inline GradSink sink_act(float* out, int act, const float* aux) { return GradSink{out, nullptr, nullptr, 0.f, 0.f, act, aux}; }
 
 __device__ __forceinline__ void sink_store(const GradSink& k, size_t i, float g) {
     if (k.w) {
@@ -70,6 +89,8 @@ __device__ __forceinline__ void sink_store(const GradSink& k, size_t i, float g)
             k.v[i] = vel;
         }
         k.w[i] = fmaf(-k.lr, vel, k.w[i]);
+    } else if (k.act != ACT_NONE) {
+        k.dw[i] = act_apply(k.act, g, k.act >= ACT_RELU_BWD ? k.aux[i] : 0.f);
     } else {
         k.dw[i] = g;
     }

@@ -173,15 +173,24 @@ __global__ void __launch_bounds__(kBlock) k_maxpool2_relu_bwd(size_t total, int 
     }
 }
 
-// softmax cross-entropy: one workgroup per sample; max and sum by LDS tree reduction.
+// softmax cross-entropy: one workgroup per sample; max and sum by LDS tree reduction.  ROW_IN_LDS: the row is read
+// from memory once and kept in LDS (first as logits, then as exponentials), so each element costs one read, one
+// exponential and one write; otherwise three passes over memory with the exponential taken twice (same values, same
+// summation order either way).
+template <bool ROW_IN_LDS>
 __global__ void __launch_bounds__(kBlock) k_softmax_xent(int N, int O, const float* __restrict__ z,
                                                         const int32_t* __restrict__ label,
                                                         float* __restrict__ loss, float* __restrict__ dz) {
     __shared__ float red[kBlock];
+    extern __shared__ float row[];              // O floats when ROW_IN_LDS
     const int n = blockIdx.x;
     const float* zr = z + (size_t)n * O;
     float m = -INFINITY;
-    for (int o = threadIdx.x; o < O; o += kBlock) m = fmaxf(m, zr[o]);
+    for (int o = threadIdx.x; o < O; o += kBlock) {
+        const float t = zr[o];
+        if (ROW_IN_LDS) row[o] = t;
+        m = fmaxf(m, t);
+    }
     red[threadIdx.x] = m;
     __syncthreads();
     for (int s = kBlock / 2; s > 0; s >>= 1) {
@@ -190,8 +199,18 @@ __global__ void __launch_bounds__(kBlock) k_softmax_xent(int N, int O, const flo
     }
     m = red[0];
     __syncthreads();
+    // labels live in device memory, so the host cannot validate them: a label outside [0, O) reads nothing, gives
+    // this sample a NaN loss and leaves its row of dz as the plain softmax / N
+    const int lab = label[n];
+    const bool lab_ok = (unsigned)lab < (unsigned)O;
+    const float z_lab = lab_ok ? (ROW_IN_LDS ? row[lab] : zr[lab]) : 0.f;
+    __syncthreads();                            // row[lab] is read before the exponentials overwrite the logits
     float sum = 0.f;
-    for (int o = threadIdx.x; o < O; o += kBlock) sum += expf(zr[o] - m);
+    for (int o = threadIdx.x; o < O; o += kBlock) {
+        const float e = expf((ROW_IN_LDS ? row[o] : zr[o]) - m);
+        if (ROW_IN_LDS) row[o] = e;
+        sum += e;
+    }
     red[threadIdx.x] = sum;
     __syncthreads();
     for (int s = kBlock / 2; s > 0; s >>= 1) {
@@ -199,15 +218,13 @@ __global__ void __launch_bounds__(kBlock) k_softmax_xent(int N, int O, const flo
         __syncthreads();
     }
     sum = red[0];
-    // labels live in device memory, so the host cannot validate them: a label outside [0, O) reads nothing, gives
-    // this sample a NaN loss and leaves its row of dz as the plain softmax / N
-    const int lab = label[n];
-    const bool lab_ok = (unsigned)lab < (unsigned)O;
-    if (threadIdx.x == 0 && loss) loss[n] = lab_ok ? -((zr[lab] - m) - logf(sum)) : __builtin_nanf("");
+    if (threadIdx.x == 0 && loss) loss[n] = lab_ok ? -((z_lab - m) - logf(sum)) : __builtin_nanf("");
     if (dz) {
         const float inv = 1.0f / sum, invN = 1.0f / (float)N;
-        for (int o = threadIdx.x; o < O; o += kBlock)
-            dz[(size_t)n * O + o] = (expf(zr[o] - m) * inv - (o == lab ? 1.0f : 0.0f)) * invN;
+        for (int o = threadIdx.x; o < O; o += kBlock) {
+            const float e = ROW_IN_LDS ? row[o] : expf(zr[o] - m);
+            dz[(size_t)n * O + o] = (e * inv - (o == lab ? 1.0f : 0.0f)) * invN;
+        }
     }
 }
 
@@ -356,7 +373,11 @@ int cnn_maxpool2_relu_bwd(cnn_ctx* ctx, size_t planes, int H, int W, const float
 int cnn_softmax_xent(cnn_ctx* ctx, int N, int O, const float* z, const int32_t* label, float* loss, float* dz) {
     if (!ctx || !z || !label || N <= 0 || O <= 0) return CNN_EINVAL;
     cnn::ProfScope ps_k_softmax_xent(ctx, "k_softmax_xent", 0.0);
-    hipLaunchKernelGGL(k_softmax_xent, dim3(N), dim3(kBlock), 0, ctx->stream, N, O, z, label, loss, dz);
+    if ((size_t)O * sizeof(float) <= 40 * 1024)      // the row fits the default LDS allowance beside the reduction buffer
+        hipLaunchKernelGGL(k_softmax_xent<true>, dim3(N), dim3(kBlock), (size_t)O * sizeof(float), ctx->stream, N, O, z, label,
+                           loss, dz);
+    else
+        hipLaunchKernelGGL(k_softmax_xent<false>, dim3(N), dim3(kBlock), 0, ctx->stream, N, O, z, label, loss, dz);
     return cnn::launch_check(ctx, "softmax_xent");
 }
 

@@ -25,14 +25,15 @@ namespace {
 typedef float f32x4 __attribute__((ext_vector_type(4)));
 typedef __attribute__((address_space(3))) f32x4 lds_f32x4;
 
-constexpr int KC = 32;   // contraction elements per LDS chunk
+constexpr int KCP = 32;   // planning unit of the contraction: every chunk size is a multiple of it
 
 // KS: wave groups that share a tile and split every chunk's contraction steps between them (their accumulators are
 // added through LDS at the end).  With one workgroup per compute unit it doubles the waves per SIMD, which is what
 // hides the LDS and barrier latencies when the grid is a single round.
-template <int MT_, int NT_, int WGM_, int WGN_, bool AKM_, bool BKM_, int KS_>
+template <int MT_, int NT_, int WGM_, int WGN_, bool AKM_, bool BKM_, int KS_, int KC_ = 32>
 struct GemmCfg {
     static constexpr int MT = MT_, NT = NT_, WGM = WGM_, WGN = WGN_, KS = KS_;
+    static constexpr int KC = KC_;      // contraction elements per LDS chunk
     static constexpr bool AKM = AKM_, BKM = BKM_;
     static constexpr int TM = 32 * MT * WGM, TN = 32 * NT * WGN, T = 64 * WGM * WGN * KS;
     static constexpr int A_LDS = AKM ? KC * TM : TM * (KC + 1);
@@ -48,7 +49,7 @@ struct GemmCfg {
 // One operand tile of ROWS x KC elements: per-thread staging slots (float4 each).
 //   KM == false: src[row][Kd], float4 along k;  LDS [row][KC+1]
 //   KM == true:  src[Kd][rows_total], float4 along the row index;  LDS [k][ROWS]
-template <bool KM, int ROWS, int T, int SLOTS>
+template <bool KM, int ROWS, int T, int SLOTS, int KC>
 struct Stager {
     int vo[SLOTS];         // byte offset of the slot's float4 within chunk 0 of the split (or kOutOfRange)
     int kofs[SLOTS];       // first contraction index of the slot within the chunk
@@ -93,21 +94,57 @@ struct Stager {
     }
 };
 
+// Tail slicing: when the tiles fill the chip's workgroup slots one or more times over and leave a short last round,
+// the tiles of that round are cut along the contraction into nsl workgroups each (dispatched after all whole tiles),
+// which store partial tiles [tail tile][slice][TM][TN]; k_gemm_tail_reduce adds them in slice order.  584 tiles of
+// 128 x 128 on 512 slots: 512 whole tiles, then 72 x 7 slices instead of 72 lone workgroups on 72 compute units.
+struct GemmTail {
+    int flat;               // 1: one-dimensional grid of whole tiles followed by tail slices (one contraction split)
+    int tiles_n;            // tiles along Nn
+    int whole_tiles;        // tiles [0, whole_tiles) are computed by one workgroup each
+    int nsl, k_per_slice;   // slices per tail tile, contraction elements per slice (a multiple of KC)
+    float* partial;
+};
+
 template <class G>
 __global__ void __launch_bounds__(G::T, G::KS == 1 ? 2 : 1)
 k_gemm(int M, int Nn, int Kd, int k_per_split, const float* __restrict__ A, const float* __restrict__ B,
-       GradSink sink) {
-    constexpr int MT = G::MT, NT = G::NT, T = G::T;
+       GradSink sink_in, GemmTail tail) {
+    constexpr int MT = G::MT, NT = G::NT, T = G::T, KC = G::KC;
     extern __shared__ __attribute__((aligned(16))) float lds[];      // two (A tile, B tile) buffers
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
     const int half = lane >> 5, l32 = lane & 31;
     const int kg = wave / (G::WGM * G::WGN), wt = wave % (G::WGM * G::WGN);     // wave group, wave within the tile
     const int wm = wt % G::WGM, wn = wt / G::WGM;
-    const int n0 = blockIdx.x * G::TN, m0 = blockIdx.y * G::TM;
-    const int k_begin = blockIdx.z * k_per_split;
-    const int k_end = min(k_begin + k_per_split, Kd);
-    // sink.dw = C, or the split's private copy [blockIdx.z][M][Nn]; sink.w is only set when there is one split
-    const size_t out0 = (size_t)blockIdx.z * M * Nn;
+    int n0, m0, k_begin, k_end;
+    // where the tile goes: element (m, n) at out0 + (m - om0) * ldc + (n - on0) of sink.dw / sink.w / sink.v
+    size_t out0 = 0;
+    int ldc = Nn, om0 = 0, on0 = 0;
+    GradSink sink = sink_in;
+    if (tail.flat) {
+        int t = blockIdx.x;
+        k_begin = 0;
+        k_end = Kd;
+        const bool slice = t >= tail.whole_tiles;
+        if (slice) {
+            const int r = t - tail.whole_tiles, sl = r % tail.nsl;
+            t = tail.whole_tiles + r / tail.nsl;
+            k_begin = sl * tail.k_per_slice;
+            k_end = min(k_begin + tail.k_per_slice, Kd);
+            sink = GradSink{tail.partial + (size_t)r * G::TM * G::TN, nullptr, nullptr, 0.f, 0.f, ACT_NONE, nullptr};     // a partial tile, stored [TM][TN]
+            ldc = G::TN;
+        }
+        n0 = (t % tail.tiles_n) * G::TN;
+        m0 = (t / tail.tiles_n) * G::TM;
+        if (slice) { om0 = m0; on0 = n0; }
+    } else {
+        n0 = blockIdx.x * G::TN;
+        m0 = blockIdx.y * G::TM;
+        k_begin = blockIdx.z * k_per_split;
+        k_end = min(k_begin + k_per_split, Kd);
+        // sink.dw = C, or the split's private copy [blockIdx.z][M][Nn]; sink.w is only set when there is one split
+        out0 = (size_t)blockIdx.z * M * Nn;
+    }
 
     f32x16 acc[MT][NT];
 #pragma unroll
@@ -122,8 +159,8 @@ k_gemm(int M, int Nn, int Kd, int k_per_split, const float* __restrict__ A, cons
             const_cast<float*>(A), 0, (int)((size_t)M * Kd * sizeof(float)), kRsrcWord3);
         const __amdgpu_buffer_rsrc_t rs_b = __builtin_amdgcn_make_buffer_rsrc(
             const_cast<float*>(B), 0, (int)((size_t)Nn * Kd * sizeof(float)), kRsrcWord3);
-        Stager<G::AKM, G::TM, T, G::AS> sa;
-        Stager<G::BKM, G::TN, T, G::BS> sb;
+        Stager<G::AKM, G::TM, T, G::AS, G::KC> sa;
+        Stager<G::BKM, G::TN, T, G::BS, G::KC> sb;
         sa.init(M, Kd, m0, tid, lds);
         sb.init(Nn, Kd, n0, tid, lds + G::A_LDS);
         constexpr int NITEMS = G::AS + G::BS;
@@ -267,7 +304,7 @@ k_gemm(int M, int Nn, int Kd, int k_per_split, const float* __restrict__ A, cons
             const int idx = tid + it * T, row = idx / (TN / 4), c4 = idx % (TN / 4);
             const int m = m0 + row, n = n0 + 4 * c4;
             const bool ok = m < M && n < Nn;
-            *e = ok ? (size_t)m * Nn + n : 0;
+            *e = ok ? (size_t)(m - om0) * ldc + (n - on0) : 0;
             return ok;
         };
         if (sink.w) {
@@ -299,6 +336,28 @@ k_gemm(int M, int Nn, int Kd, int k_per_split, const float* __restrict__ A, cons
             }
         } else {
             float* dst = sink.dw + out0;
+            if (sink.act != ACT_NONE) {
+                // activation folded into the store (never together with contraction splits: out0 == 0)
+                const bool masked = sink.act >= ACT_RELU_BWD;
+                f32x4 ax[ITER];
+#pragma unroll
+                for (int it = 0; it < ITER; ++it) {
+                    size_t e;
+                    where(it, &e);
+                    ax[it] = masked ? *reinterpret_cast<const f32x4*>(sink.aux + e) : f32x4{0.f, 0.f, 0.f, 0.f};
+                }
+#pragma unroll
+                for (int it = 0; it < ITER; ++it) {
+                    size_t e;
+                    if (!where(it, &e)) continue;
+                    const int idx = tid + it * T;
+                    f32x4 c = *(const lds_f32x4*)(lds + (idx / (TN / 4)) * TN + 4 * (idx % (TN / 4)));
+                    c.x = act_apply(sink.act, c.x, ax[it].x); c.y = act_apply(sink.act, c.y, ax[it].y);
+                    c.z = act_apply(sink.act, c.z, ax[it].z); c.w = act_apply(sink.act, c.w, ax[it].w);
+                    *reinterpret_cast<f32x4*>(dst + e) = c;
+                }
+                return;
+            }
 #pragma unroll
             for (int it = 0; it < ITER; ++it) {
                 size_t e;
@@ -324,7 +383,7 @@ k_gemm(int M, int Nn, int Kd, int k_per_split, const float* __restrict__ A, cons
 #pragma unroll
                 for (int v = 0; v < 16; ++v) {
                     const int m = m0 + (wm * MT + i) * 32 + 8 * (v / 4) + 4 * half + (v % 4);
-                    const size_t e = (size_t)(m < M ? m : M - 1) * Nn + n;
+                    const size_t e = (size_t)((m < M ? m : M - 1) - om0) * ldc + (n - on0);
                     wv[v] = sink.w[e];
                     vv[v] = sink.v ? sink.v[e] : 0.f;
                 }
@@ -332,7 +391,7 @@ k_gemm(int M, int Nn, int Kd, int k_per_split, const float* __restrict__ A, cons
                 for (int v = 0; v < 16; ++v) {
                     const int m = m0 + (wm * MT + i) * 32 + 8 * (v / 4) + 4 * half + (v % 4);
                     if (m >= M) continue;
-                    const size_t e = (size_t)m * Nn + n;
+                    const size_t e = (size_t)(m - om0) * ldc + (n - on0);
                     float vel = acc[i][j][v];
                     if (sink.v) {
                         vel = fmaf(sink.mu, vv[v], vel);
@@ -352,7 +411,11 @@ k_gemm(int M, int Nn, int Kd, int k_per_split, const float* __restrict__ A, cons
 #pragma unroll
             for (int v = 0; v < 16; ++v) {
                 const int m = m0 + (wm * MT + i) * 32 + 8 * (v / 4) + 4 * half + (v % 4);
-                if (m < M) sink.dw[out0 + (size_t)m * Nn + n] = acc[i][j][v];
+                if (m < M) {
+                    const size_t e = out0 + (size_t)(m - om0) * ldc + (n - on0);
+                    sink.dw[e] = sink.act == ACT_NONE ? acc[i][j][v]
+                                                      : act_apply(sink.act, acc[i][j][v], sink.act >= ACT_RELU_BWD ? sink.aux[e] : 0.f);
+                }
             }
         }
 }
@@ -372,8 +435,28 @@ __global__ void __launch_bounds__(256) k_splitk_reduce(int nsplit, size_t MN, co
     }
 }
 
+// C (or the SGD step, sink) of the tail tiles = sum over their slices' partial tiles, in slice order.  One thread per
+// element; grid = (TM * TN / 256, tail tiles).
+__global__ void __launch_bounds__(256) k_gemm_tail_reduce(int M, int Nn, int TM, int TN, GemmTail tail, GradSink sink) {
+    const int t = tail.whole_tiles + blockIdx.y;
+    const int e = blockIdx.x * 256 + threadIdx.x;                    // element of the tile, row-major [TM][TN]
+    const int m = (t / tail.tiles_n) * TM + e / TN, n = (t % tail.tiles_n) * TN + e % TN;
+    if (m >= M || n >= Nn) return;
+    const size_t tile = (size_t)TM * TN;
+    const float* src = tail.partial + (size_t)blockIdx.y * tail.nsl * tile + e;
+    float s0 = 0.f, s1 = 0.f;
+    int sl = 0;
+    for (; sl + 1 < tail.nsl; sl += 2) {
+        s0 += src[(size_t)sl * tile];
+        s1 += src[(size_t)(sl + 1) * tile];
+    }
+    if (sl < tail.nsl) s0 += src[(size_t)sl * tile];
+    sink_store(sink, (size_t)m * Nn + n, s0 + s1);
+}
+
 struct GemmPlan {
     int tm, tn, ks, nsplit, k_per_split;
+    int tail_tiles, tail_nsl, tail_k;     // tail slicing (tail_nsl >= 2) of the last tail_tiles tiles
     size_t ws_bytes;
 };
 
@@ -384,14 +467,15 @@ GemmPlan plan_gemm(int M, int Nn, int Kd) {
     // splitting the contraction, which needs the partial products written, read back and added
     if (p.tm == 128 && (long)((M + 127) / 128) * ((Nn + 127) / 128) < 256 && Kd <= 4096) p.tm = 64;
     // a few rounds of 128-row tiles whose last round is mostly empty: the busiest compute unit works through
-    // ceil(tiles / 256) tiles, and 64-row tiles cut that in finer steps (584 tiles: 3 x 128 rows against 5 x 64)
+    // ceil(tiles / 256) tiles, and 64-row tiles cut that in finer steps (where the tail of the 128-row tiles is
+    // not sliced, below)
     if (p.tm == 128) {
         const long t128 = (long)((M + 127) / 128) * ((Nn + 127) / 128), t64 = (long)((M + 63) / 64) * ((Nn + 127) / 128);
-        if (t128 > 256 && t128 <= 4 * 256 && ((t64 + 255) / 256) * 64 * 10 < ((t128 + 255) / 256) * 128 * 9) p.tm = 64;
+        if (t128 > 256 && t128 < 2 * 256 && ((t64 + 255) / 256) * 64 * 10 < ((t128 + 255) / 256) * 128 * 9) p.tm = 64;
     }
     p.tn = 128;
     const long tiles = (long)((M + p.tm - 1) / p.tm) * ((Nn + p.tn - 1) / p.tn);
-    const int chunks = (Kd + KC - 1) / KC;
+    const int chunks = (Kd + KCP - 1) / KCP;
     int max_split = chunks / 8;            // at least 8 chunks (256 contraction elements) per split
     if (max_split < 1) max_split = 1;
     if (max_split > 32) max_split = 32;
@@ -401,7 +485,10 @@ GemmPlan plan_gemm(int M, int Nn, int Kd) {
     // the second launch).
     // 288 tiles are two rounds unsplit and nine eighths of one in eight splits.
     int want = 1;
-    {
+    const long tail_slots = p.tm == 128 ? 512 : 768;      // resident workgroups of the one-wave-group kernels (below)
+    const bool sliceable = p.tm >= 64 && tiles > tail_slots && tiles % tail_slots > 0 && tiles % tail_slots <= tail_slots / 2 &&
+                           tail_slots / (tiles % tail_slots) >= 2 && chunks >= 16;
+    if (!sliceable) {
         const double unit_us = 2.0 * p.tm * p.tn * (double)Kd / 0.55e6;
         double best_t = 0.0;
         for (int ns = 1; ns <= max_split; ++ns) {
@@ -414,11 +501,32 @@ GemmPlan plan_gemm(int M, int Nn, int Kd) {
         }
     }
     const int cps = (chunks + want - 1) / want;
-    p.k_per_split = cps * KC;
+    p.k_per_split = cps * KCP;
     p.nsplit = (Kd + p.k_per_split - 1) / p.k_per_split;
     p.ws_bytes = p.nsplit > 1 ? (size_t)p.nsplit * M * Nn * sizeof(float) : 0;
     // a grid of at most one workgroup per compute unit: two wave groups per tile
     p.ks = tiles * p.nsplit <= 256 && p.tm != 32 ? 2 : 1;      // (the 32-row tile has too few staging slots for 512 threads)
+    // Tail slicing.  Two workgroups of 128 x 128 are resident per compute unit (registers and LDS), three of
+    // 64 x 128 (LDS): 512 or 768 slots.  Tiles beyond the last full round of slots would run one or two to a
+    // compute unit on a mostly idle chip; cut along the contraction (at least 8 chunks per slice) they fill one
+    // more, shorter, round.
+    p.tail_tiles = p.tail_nsl = p.tail_k = 0;
+    if (p.nsplit == 1 && p.ks == 1 && p.tm >= 64) {
+        const long slots = tail_slots, tail = tiles % slots;
+        if (tiles > slots && tail > 0 && tail <= slots / 2) {
+            long nsl = slots / tail;
+            if (nsl > chunks / 8) nsl = chunks / 8;
+            if (nsl > 16) nsl = 16;
+            if (nsl >= 2) {
+                const int cps2 = (int)((chunks + nsl - 1) / nsl);
+                p.tail_k = cps2 * KCP;
+                p.tail_nsl = (Kd + p.tail_k - 1) / p.tail_k;
+                p.tail_tiles = (int)tail;
+                if (p.tail_nsl < 2) p.tail_tiles = p.tail_nsl = p.tail_k = 0;
+                else p.ws_bytes = (size_t)p.tail_tiles * p.tail_nsl * p.tm * p.tn * sizeof(float);
+            }
+        }
+    }
     return p;
 }
 
@@ -433,18 +541,31 @@ int launch(cnn_ctx* ctx, const GemmPlan& p, int M, int Nn, int Kd, const float* 
         if (e != hipSuccess) return cnn::hip_check(ctx, e, "hipFuncSetAttribute(gemm)");
         attr_done = true;
     }
-    dim3 grid((unsigned)((Nn + G::TN - 1) / G::TN), (unsigned)((M + G::TM - 1) / G::TM), (unsigned)p.nsplit);
+    const int tiles_n = (Nn + G::TN - 1) / G::TN, tiles_m = (M + G::TM - 1) / G::TM;
+    dim3 grid((unsigned)tiles_n, (unsigned)tiles_m, (unsigned)p.nsplit);
+    GemmTail tail{0, tiles_n, tiles_n * tiles_m, 1, 0, nullptr};
+    if (p.tail_nsl >= 2) {
+        tail = GemmTail{1, tiles_n, tiles_n * tiles_m - p.tail_tiles, p.tail_nsl, p.tail_k, reinterpret_cast<float*>(ctx->ws)};
+        grid = dim3((unsigned)(tail.whole_tiles + p.tail_tiles * p.tail_nsl));
+    }
     static const std::string name_s = strf("k_gemm<%dx%d %s%s%s>", G::TM, G::TN, G::AKM ? "At" : "A", G::BKM ? "B" : "Bt",
-                                           G::KS == 2 ? " x2" : "");
+                                           G::KS == 2 ? " x2" : "");   // (the chunk size is not part of the name)
     static const std::string name_sgd_s = name_s + "+sgd";
     const char* const name = name_s.c_str();
     const char* const name_sgd = name_sgd_s.c_str();
     {
         cnn::ProfScope ps(ctx, first.w ? name_sgd : name, 2.0 * M * Nn * Kd);
-        hipLaunchKernelGGL(k_gemm<G>, grid, dim3(G::T), lds_bytes, ctx->stream, M, Nn, Kd, p.k_per_split, A, B, first);
+        hipLaunchKernelGGL(k_gemm<G>, grid, dim3(G::T), lds_bytes, ctx->stream, M, Nn, Kd, p.k_per_split, A, B, first, tail);
     }
     int st = cnn::launch_check(ctx, "gemm");
-    if (st != CNN_OK || p.nsplit == 1) return st;
+    if (st != CNN_OK) return st;
+    if (p.tail_nsl >= 2) {
+        cnn::ProfScope ps(ctx, sink.w ? "k_gemm_tail_reduce<sgd>" : "k_gemm_tail_reduce", 0.0);
+        hipLaunchKernelGGL(k_gemm_tail_reduce, dim3((unsigned)(G::TM * G::TN / 256), (unsigned)p.tail_tiles), dim3(256), 0,
+                           ctx->stream, M, Nn, G::TM, G::TN, tail, sink);
+        return cnn::launch_check(ctx, "gemm_tail_reduce");
+    }
+    if (p.nsplit == 1) return st;
     const size_t MN = (size_t)M * Nn;
     size_t g = (MN + 255) / 256;
     if (g > 4096) g = 4096;
@@ -477,18 +598,24 @@ int mfma_gemm(cnn_ctx* ctx, int M, int Nn, int Kd, const float* A, int akm, cons
     const GradSink C = sink ? *sink : sink_dw(Cp);
     const GemmPlan p = plan_gemm(M, Nn, Kd);
     if (p.ws_bytes && (!ctx->ws || ctx->ws_bytes < p.ws_bytes)) return CNN_EWORKSPACE;
-#define GO(MT, NT, WGM, WGN, KS)                                                                               \
-    do {                                                                                                       \
-        if (!akm && !bkm) return launch<GemmCfg<MT, NT, WGM, WGN, false, false, KS>>(ctx, p, M, Nn, Kd, A, B, C); \
-        if (!akm && bkm) return launch<GemmCfg<MT, NT, WGM, WGN, false, true, KS>>(ctx, p, M, Nn, Kd, A, B, C);   \
-        if (akm && bkm) return launch<GemmCfg<MT, NT, WGM, WGN, true, true, KS>>(ctx, p, M, Nn, Kd, A, B, C);     \
-        return launch<GemmCfg<MT, NT, WGM, WGN, true, false, KS>>(ctx, p, M, Nn, Kd, A, B, C);                    \
+#define GO(MT, NT, WGM, WGN, KS, KCH)                                                                               \
+    do {                                                                                                            \
+        if (!akm && !bkm) return launch<GemmCfg<MT, NT, WGM, WGN, false, false, KS, KCH>>(ctx, p, M, Nn, Kd, A, B, C); \
+        if (!akm && bkm) return launch<GemmCfg<MT, NT, WGM, WGN, false, true, KS, KCH>>(ctx, p, M, Nn, Kd, A, B, C);   \
+        if (akm && bkm) return launch<GemmCfg<MT, NT, WGM, WGN, true, true, KS, KCH>>(ctx, p, M, Nn, Kd, A, B, C);     \
+        return launch<GemmCfg<MT, NT, WGM, WGN, true, false, KS, KCH>>(ctx, p, M, Nn, Kd, A, B, C);                    \
     } while (0)
-    if (p.tm == 32) GO(1, 1, 1, 4, 1);
-    if (p.tm == 64 && p.ks == 2) GO(2, 1, 1, 4, 2);
-    if (p.tm == 64) GO(2, 1, 1, 4, 1);
-    if (p.ks == 2) GO(2, 2, 2, 2, 2);
-    GO(2, 2, 2, 2, 1);
+#ifndef GEMM_KC_A
+#define GEMM_KC_A 32
+#endif
+#ifndef GEMM_KC_B
+#define GEMM_KC_B 32
+#endif
+    if (p.tm == 32) GO(1, 1, 1, 4, 1, 32);
+    if (p.tm == 64 && p.ks == 2) GO(2, 1, 1, 4, 2, GEMM_KC_A);
+    if (p.tm == 64) GO(2, 1, 1, 4, 1, 32);
+    if (p.ks == 2) GO(2, 2, 2, 2, 2, GEMM_KC_B);
+    GO(2, 2, 2, 2, 1, 32);
 #undef GO
 }
 

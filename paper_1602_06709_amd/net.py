@@ -68,6 +68,7 @@ class Net:
         self.labels = torch.zeros(n, dtype=torch.int32, device=dev)
         self.loss_per_sample = torch.empty(n, dtype=torch.float32, device=dev)
         self.trace = []
+        self._fc_fused = set()
         self._pooled_ok, self._pooled_first = None, False
         self.marks = None   # a list while a caller wants (op, layer, profile-entry count after the call) per call
         self._reserve()
@@ -99,7 +100,7 @@ class Net:
                 if isinstance(t, torch.Tensor) and t.data_ptr() not in seen:
                     seen.add(t.data_ptr())
                     nbytes += t.numel() * t.element_size()
-            if item[0].endswith("_sgd"):
+            if "_sgd" in item[0]:
                 wi = item[2]
                 nbytes += sum(t.numel() * 4 for t in (self.w[wi], self.v[wi]) if t is not None)
             self.marks.append((item[0], item[1], self.ctx.profile_count(), nbytes))
@@ -117,6 +118,7 @@ class Net:
     def forward(self):
         ctx, wi = self.ctx, 0
         skip = set()
+        self._fc_fused = set()      # fully-connected layers whose activation was folded into their store
         for i, L in enumerate(self.layers):
             xin, kind = self._input_of(i), L[0]
             if i in skip:
@@ -139,8 +141,19 @@ class Net:
                     self._rec("conv_fwd", i, wi, xin, self.w[wi], self.act[i])
                 wi += 1
             elif kind == "fc":
-                B.cnn_fc_fwd(ctx, xin, self.w[wi], out=self.act[i])
-                self._rec("fc_fwd", i, wi, xin, self.w[wi], self.act[i]); wi += 1
+                nxt = self.layers[i + 1][0] if i + 1 < len(self.layers) else None
+                done = None
+                if self.fuse and nxt in ("relu", "sigmoid"):
+                    # the activation behind the layer goes into the GEMM's store; its input is never written
+                    done = B.cnn_fc_fwd_act(ctx, xin, self.w[wi], nxt, out=self.act[i + 1])
+                if done is not None:
+                    self._rec("fc_fwd_act", i, wi, xin, self.w[wi], self.act[i + 1], nxt)
+                    self._fc_fused.add(i)
+                    skip.add(i + 1)
+                else:
+                    B.cnn_fc_fwd(ctx, xin, self.w[wi], out=self.act[i])
+                    self._rec("fc_fwd", i, wi, xin, self.w[wi], self.act[i])
+                wi += 1
             elif kind == "relu":
                 B.cnn_relu_fwd(ctx, xin, out=self.act[i]); self._rec("relu_fwd", i, xin, self.act[i])
             elif kind == "sigmoid":
@@ -248,6 +261,26 @@ class Net:
             elif kind == "fc":
                 dx_out = None if first else dxb.view(xin.shape)
                 done = None
+                # is the input of layer i the output of an activation that was folded into the fully-connected layer
+                # before it?  Then its derivative goes into this layer's backpropagation store, and the gradient lands
+                # in front of the activation
+                act_in = self.layers[i - 1][0] if (i >= 2 and (i - 2) in self._fc_fused) else None
+                if act_in is not None:
+                    dz_out = self.gact[i - 2].view(xin.shape)
+                    if update:
+                        done = B.cnn_fc_bwd_sgd_act(ctx, xin, self.w[wi], dy, act_in, self.v[wi], dz_out=dz_out,
+                                                    lr=self.wl.lr, momentum=self.wl.momentum)
+                        if done is not None:
+                            self._rec("fc_bwd_sgd_act", i, wi, xin, self.w[wi], dy, dz_out, self.v[wi], act_in)
+                    if done is None:
+                        done = B.cnn_fc_bwd_act(ctx, xin, self.w[wi], dy, act_in, dz_out=dz_out, dw_out=self.dw[wi])
+                        if done is not None:
+                            self._rec("fc_bwd_act", i, wi, xin, self.w[wi], dy, dz_out, self.dw[wi], act_in)
+                            if update:
+                                self._sgd_layer(wi)
+                    if done is not None:
+                        skip.add(i - 1)
+                        continue
                 if update:
                     done = B.cnn_fc_bwd_sgd(ctx, xin, self.w[wi], dy, self.v[wi], need_dx=not first, dx_out=dx_out,
                                             lr=self.wl.lr, momentum=self.wl.momentum)
@@ -260,7 +293,7 @@ class Net:
                         self._sgd_layer(wi)
             elif kind == "relu":
                 # with the forward ReLU folded into the convolution only its output exists; a > 0 <=> z > 0
-                mask = self.act[i] if (i >= 1 and self._fused_relu_after(i - 1)) else xin
+                mask = self.act[i] if (i >= 1 and (self._fused_relu_after(i - 1) or (i - 1) in self._fc_fused)) else xin
                 B.cnn_relu_bwd(ctx, mask, dy, out=dxb); self._rec("relu_bwd", i, mask, dy, dxb)
             elif kind == "sigmoid":
                 B.cnn_sigmoid_bwd(ctx, self.act[i], dy, out=dxb); self._rec("sigmoid_bwd", i, self.act[i], dy, dxb)

@@ -122,6 +122,48 @@ def check_trace_item(item, cfg, layers, full, n_samples=20000, n_samples_wgrad=1
         _check_folded(name, cfg, i, wi, lambda: oracle.fc_bwd_weight(x, dy, with_abs=True),
                       lambda idx: oracle.fc_bwd_weight_at(x, dy, idx), w.numel(), w, v, pre, lr, momentum, full, n_samples)
         return r
+    if op == "fc_fwd_act":
+        # act(x W^T): ReLU is exact on the oracle's sum; sigmoid has slope <= 1/4, so the contraction bound shrinks
+        # by that factor, plus a few ulp of the result for the fp32 exponential and division
+        _, _, wi, x, w, a, act = item
+        x, w, a = np_(x), np_(w), np_(a)
+        idx = np.arange(a.size) if full else sample(cfg, 4000 + i, a.size, n_samples)
+        ref, s = oracle.fc_fwd(x, w, with_abs=True) if full else oracle.fc_fwd_at(x, w, idx)
+        ref, s = ref.ravel(), s.ravel()
+        if act == "relu":
+            return check_contraction(name, a.ravel()[idx], np.maximum(ref, 0.0), s)
+        return check_contraction(name, a.ravel()[idx], 1.0 / (1.0 + np.exp(-ref)),
+                                 0.25 * s + 16 * 2.0 ** -23 / PER_ELEM)
+    if op in ("fc_bwd_act", "fc_bwd_sgd_act"):
+        # backpropagation with the derivative of the activation that produced x folded in: the oracle's dy W times
+        # act'(x) taken from the same fp32 x; the weight gradient (or the folded update) as in the plain forms
+        if op == "fc_bwd_act":
+            _, _, wi, x, w, dy, dz, dw, act_in = item
+            w_used = np_(w)
+        else:
+            _, _, wi, x, w, dy, dz, v, act_in = item
+            w_used = pre[0][wi]
+        x, dy, dzn = np_(x), np_(dy), np_(dz)
+        idx = np.arange(dzn.size) if full else sample(cfg, 6000 + i, dzn.size, n_samples)
+        ref, s = oracle.fc_bwd_data(dy, w_used, with_abs=True) if full else oracle.fc_bwd_data_at(dy, w_used, idx)
+        xs = x.ravel()[idx].astype(np.float64)
+        f = (xs > 0).astype(np.float64) if act_in == "relu" else xs * (1.0 - xs)
+        if act_in == "relu":
+            assert np.all(dzn.ravel()[idx][xs <= 0] == 0), name + ": gradient leaked through a closed ReLU"
+        r = check_contraction(name + ":dz", dzn.ravel()[idx], ref.ravel() * f, s.ravel() * f)
+        if op == "fc_bwd_act":
+            dw = np_(dw)
+            if full:
+                rw, sw = oracle.fc_bwd_weight(x, dy, with_abs=True)
+                r = max(r, check_contraction(name + ":dw", dw, rw, sw))
+            else:
+                idw = sample(cfg, 5000 + i, dw.size, n_samples)
+                rw, sw = oracle.fc_bwd_weight_at(x, dy, idw)
+                r = max(r, check_contraction(name + ":dw", dw.ravel()[idw], rw, sw))
+        else:
+            _check_folded(name, cfg, i, wi, lambda: oracle.fc_bwd_weight(x, dy, with_abs=True),
+                          lambda ii: oracle.fc_bwd_weight_at(x, dy, ii), w.numel(), w, v, pre, lr, momentum, full, n_samples)
+        return r
     if op == "conv_fwd":
         _, _, wi, x, w, y = item
         x, w, y = np_(x), np_(w), np_(y)

@@ -377,7 +377,10 @@ def test_bwd_weight_is_bitwise_repeatable(cnn, ctx):
 
 # ------------------------------------------------------------------ fully connected
 FC_CASES = [(64, 1024, 1000), (64, 440, 2048), (5, 36, 20), (130, 256, 136), (256, 2048, 520), (64, 25088, 256),
-            (1, 4096, 1024), (7, 100, 52), (33, 260, 1000), (1024, 64, 64), (300, 1028, 260), (4, 8, 4)]
+            (1, 4096, 1024), (7, 100, 52), (33, 260, 1000), (1024, 64, 64), (300, 1028, 260), (4, 8, 4),
+            # more tiles than resident workgroups with a short last round: the tail tiles are sliced along the
+            # contraction (forward of the first, weight gradient of the second)
+            (1024, 512, 9304), (512, 2304, 4104)]
 
 
 @pytest.mark.parametrize("case", FC_CASES)
@@ -393,6 +396,43 @@ def test_fc_three_passes(cnn, ctx, case):
     P.check_contraction("y", P.np_(y), *oracle.fc_fwd(x, w, with_abs=True))
     P.check_contraction("dx", P.np_(dx), *oracle.fc_bwd_data(dy, w, with_abs=True))
     P.check_contraction("dw", P.np_(dw), *oracle.fc_bwd_weight(x, dy, with_abs=True))
+
+
+@pytest.mark.parametrize("case", [(64, 1024, 1000), (130, 256, 136), (256, 2048, 520), (64, 25088, 256), (1024, 64, 64),
+                                  (300, 1028, 260), (1024, 512, 9304), (1024, 2048, 2048), (4, 8, 4)])
+def test_fc_with_the_activation_folded_into_the_store(cnn, ctx, case):
+    # forward: act(x W^T); backward: the derivative of the activation that produced x folded into dx, with and without
+    # the SGD step -- each bit for bit equal to the unfused sequence (one tile, split contraction, sliced tail tiles)
+    N, I, O = case
+    say("fc+act case", case)
+    w0 = synth.randn(93, 2, (O, I), 0.05); dy = synth.randn(93, 3, (N, O)); v0 = synth.randn(93, 4, (O, I), 0.5)
+    z_in = synth.randn(93, 1, (N, I))
+    for act in ("relu", "sigmoid"):
+        x = P.np_(cnn.cnn_relu_fwd(ctx, dev(z_in)) if act == "relu" else cnn.cnn_sigmoid_fwd(ctx, dev(z_in)))   # an activation's output
+        a = cnn.cnn_fc_fwd_act(ctx, dev(x), dev(w0), act)
+        assert a is not None
+        z = cnn.cnn_fc_fwd(ctx, dev(x), dev(w0))
+        ref_a = cnn.cnn_relu_fwd(ctx, z) if act == "relu" else cnn.cnn_sigmoid_fwd(ctx, z)
+        assert torch.equal(a, ref_a), f"{act}: folded forward differs from fc_fwd + activation"
+        dz, dw = cnn.cnn_fc_bwd_act(ctx, dev(x), dev(w0), dev(dy), act)
+        dx_u, dw_u = cnn.cnn_fc_bwd(ctx, dev(x), dev(w0), dev(dy))
+        ref_dz = cnn.cnn_relu_bwd(ctx, dev(x), dx_u) if act == "relu" else cnn.cnn_sigmoid_bwd(ctx, dev(x), dx_u)
+        assert torch.equal(dz, ref_dz) and torch.equal(dw, dw_u), f"{act}: folded backward differs from the unfused sequence"
+        w, v = dev(w0), dev(v0)
+        r = cnn.cnn_fc_bwd_sgd_act(ctx, dev(x), w, dev(dy), act, v, None, 0.01, 0.9)
+        w2, v2 = dev(w0), dev(v0)
+        r2 = cnn.cnn_fc_bwd_sgd(ctx, dev(x), w2, dev(dy), v2, True, None, 0.01, 0.9)
+        torch.cuda.synchronize()
+        assert r is not None and torch.equal(r[0], ref_dz) and torch.equal(w, w2) and torch.equal(v, v2)
+        # against the oracle
+        lay = [("fc", I, O)]
+        P.check_trace_item(("fc_fwd_act", 0, 0, dev(x), dev(w0), a, act), 93, lay, True)
+        P.check_trace_item(("fc_bwd_act", 0, 0, dev(x), dev(w0), dev(dy), dz, dw, act), 93, lay, True)
+    # shapes only the plain kernels serve are refused, nothing written
+    xo = dev(synth.randn(93, 5, (5, 6))); wo = dev(synth.randn(93, 6, (10, 6))); out = torch.full((5, 10), 7.0, device="cuda")
+    assert cnn.cnn_fc_fwd_act(ctx, xo, wo, "relu", out=out) is None
+    torch.cuda.synchronize()
+    assert bool((out == 7.0).all())
 
 
 # ------------------------------------------------------------------ SGD, layouts, glue
@@ -527,11 +567,18 @@ def test_glue_ops(cnn, ctx):
     P.check_elementwise("sigmoid", P.np_(a), oracle.sigmoid_fwd(z), ulps=8)
     P.check_elementwise("sigmoid_bwd", P.np_(cnn.cnn_sigmoid_bwd(ctx, a, dev(da))), oracle.sigmoid_bwd(P.np_(a), da),
                         atol_scale=np.abs(da) * 0.25)
-    lg = synth.randn(96, 4, (7, 1000), 3.0); lab = synth.rng(96, 5).integers(0, 1000, 7).astype(np.int32)
-    loss, dz = cnn.cnn_softmax_xent(ctx, dev(lg), torch.from_numpy(lab).cuda())
-    lo, dzo = oracle.softmax_xent(lg, lab)
-    assert abs(float(P.np_(loss).astype(np.float64).mean()) - lo) < 1e-5 * abs(lo)
-    assert np.linalg.norm(P.np_(dz) - dzo) / np.linalg.norm(dzo) < 1e-5
+    # 1000 and 9304 classes: the row stays in LDS; 12007: three passes over memory; 3: fewer classes than threads
+    for O in (1000, 9304, 12007, 3):
+        lg = synth.randn(96, 4, (7, O), 3.0); lab = synth.rng(96, 5).integers(0, O, 7).astype(np.int32)
+        loss, dz = cnn.cnn_softmax_xent(ctx, dev(lg), torch.from_numpy(lab).cuda())
+        lo, dzo = oracle.softmax_xent(lg, lab)
+        assert abs(float(P.np_(loss).astype(np.float64).mean()) - lo) < 1e-5 * abs(lo)
+        assert np.linalg.norm(P.np_(dz) - dzo) / np.linalg.norm(dzo) < 1e-5
+    # a label outside [0, O): NaN loss for that sample only, nothing read out of bounds, no -1 term in its row
+    bad = lab.copy(); bad[2] = O + 5
+    loss, dz = cnn.cnn_softmax_xent(ctx, dev(lg), torch.from_numpy(bad).cuda())
+    ln = P.np_(loss)
+    assert np.isnan(ln[2]) and np.all(np.isfinite(np.delete(ln, 2))) and np.all(P.np_(dz)[2] >= 0)
 
 
 def test_argument_validation_launches_nothing(cnn, ctx):
@@ -776,10 +823,10 @@ def _run_folded_step_and_check(cnn, ctx, cfg, full, **kw):
     torch.cuda.synchronize()
     ops = [item[0] for item in net.trace]
     n_weighted = sum(1 for L in wl.layers if L[0] in ("conv", "fc"))
-    assert sum(op.endswith("_sgd") for op in ops) == n_weighted, ops      # every update went through a folded call
-    assert not any(op in ("conv_bwd_weight", "fc_bwd", "conv_bwd_weight_unpool") for op in ops), ops
+    assert sum("_sgd" in op for op in ops) == n_weighted, ops      # every update went through a folded call
+    assert not any(op in ("conv_bwd_weight", "fc_bwd", "fc_bwd_act", "conv_bwd_weight_unpool") for op in ops), ops
     for item in net.trace:
-        if not item[0].endswith("_sgd"):
+        if "_sgd" not in item[0]:
             # the call read this step's weights, which the folded update has since overwritten in place
             wi = item[2] if item[0].startswith(("conv_", "fc_")) else None
             item = tuple(w0[wi] if (wi is not None and isinstance(t, torch.Tensor) and t.data_ptr() == net.w[wi].data_ptr())
