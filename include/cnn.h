@@ -217,6 +217,24 @@ int cnn_conv_bwd_weight_sgd(cnn_ctx* ctx, int N, int C, int H, int W, int K, int
 int cnn_fc_bwd_sgd(cnn_ctx* ctx, int N, int I, int O, const float* x, float* w, const float* dy, float* dx, float* v,
                    float lr, float momentum);
 
+/* ---- Section 2.3's "transpose-weights", kept resident.  Backpropagation runs as a forward convolution of dy with
+ *     wT[c][k][r][s] = w[k][c][R-1-r][S-1-s]        (feature maps swapped, kernel taps mirrored; K*C*R*S floats)
+ *   cnn_conv_bwd_data and its fused forms make that copy in the workspace on every call.  A caller that keeps wT
+ *   beside w saves the copy: cnn_conv_transpose_weights makes it once (and again whenever w is changed by anything
+ *   else), cnn_conv_bwd_data_wt takes it instead of w, and cnn_conv_bwd_weight_sgd_wt -- cnn_conv_bwd_weight_sgd that
+ *   also stores every updated weight at its place in wT -- keeps it current across training steps.
+ *   cnn_conv_bwd_data_wt covers the three backpropagation forms: x_act == NULL: cnn_conv_bwd_data; x_act != NULL,
+ *   arg == NULL: cnn_conv_bwd_data_relu; both given: cnn_conv_bwd_data_unpool_relu (x_act = the pooled activation).
+ *   Same bits as those calls.  Workspace: as CNN_OP_CONV_BWD_DATA / CNN_OP_CONV_BWD_WEIGHT.  CNN_EUNSUPPORTED
+ *   (nothing launched) where the tiled matrix-core kernel does not serve the layer (strided layers, kernels other
+ *   than 3x3 / 5x5 / 7x7): use the plain calls there.  cnn_conv_bwd_weight_sgd_wt returns what
+ *   cnn_conv_bwd_weight_sgd returns. */
+int cnn_conv_transpose_weights(cnn_ctx* ctx, int K, int C, int R, int S, const float* w, float* wT);
+int cnn_conv_bwd_data_wt(cnn_ctx* ctx, int N, int C, int H, int W, int K, int R, int S, int stride, int pad,
+                         const float* dy, const float* wT, const float* x_act, const uint8_t* arg, float* dz);
+int cnn_conv_bwd_weight_sgd_wt(cnn_ctx* ctx, int N, int C, int H, int W, int K, int R, int S, int stride, int pad,
+                               const float* x, const float* dy, float* w, float* v, float* wT, float lr, float momentum);
+
 /* ---- Weight gradient of a first layer whose output went through ReLU and a 2x2 max-pool (Section 3.1: the first
  *   layer has no backpropagation, so the full-size gradient in front of the pool is needed by nobody else):
  *     dw = cnn_conv_bwd_weight(x, cnn_maxpool2_bwd(dpool, arg))

@@ -48,6 +48,9 @@ SIGNATURES = {
     "cnn_fc_bwd": (_i, [_vp, _i, _i, _i, _vp, _vp, _vp, _vp, _vp]),
     "cnn_sgd_update": (_i, [_vp, _sz, _vp, _vp, _vp, _f, _f]),
     "cnn_conv_bwd_weight_sgd": (_i, [_vp] + [_i] * 9 + [_vp] * 4 + [_f, _f]),
+    "cnn_conv_transpose_weights": (_i, [_vp] + [_i] * 4 + [_vp] * 2),
+    "cnn_conv_bwd_data_wt": (_i, [_vp] + [_i] * 9 + [_vp] * 5),
+    "cnn_conv_bwd_weight_sgd_wt": (_i, [_vp] + [_i] * 9 + [_vp] * 5 + [_f, _f]),
     "cnn_fc_bwd_sgd": (_i, [_vp, _i, _i, _i, _vp, _vp, _vp, _vp, _vp, _f, _f]),
     "cnn_fc_fwd_act": (_i, [_vp, _i, _i, _i, _vp, _vp, _vp, _i]),
     "cnn_fc_bwd_act": (_i, [_vp, _i, _i, _i, _vp, _vp, _vp, _vp, _vp, _i]),
@@ -391,6 +394,52 @@ def cnn_conv_bwd_weight_sgd(ctx, x, dy, w, v=None, stride=1, pad=0, lr=0.01, mom
     ctx.reserve_for(OP_CONV_BWD_WEIGHT, N, Cc, H, W, K, R, S, stride, pad)
     st = lib().cnn_conv_bwd_weight_sgd(ctx.handle, N, Cc, H, W, K, R, S, stride, pad, _t(x), _t(dy), _t(w),
                                        _t(v) if v is not None else None, lr, momentum)
+    if st == EUNSUPPORTED:
+        return None
+    _check(st, ctx.handle)
+    return w
+
+
+def cnn_conv_transpose_weights(ctx, w, out=None):
+    """wT[c][k][r][s] = w[k][c][R-1-r][S-1-s] (Section 2.3's transpose-weights with mirrored taps); None where the
+    library does not serve the kernel size."""
+    K, Cc, R, S = w.shape
+    wT = out if out is not None else torch.empty((Cc, K, R, S), dtype=torch.float32, device=w.device)
+    st = lib().cnn_conv_transpose_weights(ctx.handle, K, Cc, R, S, _t(w), _t(wT))
+    if st == EUNSUPPORTED:
+        return None
+    _check(st, ctx.handle)
+    return wT
+
+
+def cnn_conv_bwd_data_wt(ctx, dy, wT, H, W, stride=1, pad=0, x_act=None, arg=None, out=None):
+    """Backpropagation from the resident transpose-weights; x_act / arg select the ReLU and un-pool + ReLU forms (then
+    out is [N][C][2H][2W]).  None (nothing launched) where the tiled kernel does not serve the layer."""
+    Cc, K, R, S = wT.shape
+    N = dy.shape[0]
+    assert tuple(dy.shape) == (N, K, out_dim(H, R, stride, pad), out_dim(W, S, stride, pad))
+    ctx.reserve_for(OP_CONV_BWD_DATA, N, Cc, H, W, K, R, S, stride, pad)
+    shape = (N, Cc, 2 * H, 2 * W) if arg is not None else (N, Cc, H, W)
+    dz = out if out is not None else torch.empty(shape, dtype=torch.float32, device=dy.device)
+    assert tuple(dz.shape) == shape
+    st = lib().cnn_conv_bwd_data_wt(ctx.handle, N, Cc, H, W, K, R, S, stride, pad, _t(dy), _t(wT),
+                                    _t(x_act) if x_act is not None else None,
+                                    _t(arg, torch.uint8) if arg is not None else None, _t(dz))
+    if st == EUNSUPPORTED:
+        return None
+    _check(st, ctx.handle)
+    return dz
+
+
+def cnn_conv_bwd_weight_sgd_wt(ctx, x, dy, w, wT, v=None, stride=1, pad=0, lr=0.01, momentum=0.0):
+    """cnn_conv_bwd_weight_sgd that also keeps the resident transpose-weights wT current; None where unsupported."""
+    N, Cc, H, W = x.shape
+    K, C2, R, S = w.shape
+    assert Cc == C2 and tuple(wT.shape) == (Cc, K, R, S) and (v is None or tuple(v.shape) == tuple(w.shape))
+    assert tuple(dy.shape) == (N, K, out_dim(H, R, stride, pad), out_dim(W, S, stride, pad))
+    ctx.reserve_for(OP_CONV_BWD_WEIGHT, N, Cc, H, W, K, R, S, stride, pad)
+    st = lib().cnn_conv_bwd_weight_sgd_wt(ctx.handle, N, Cc, H, W, K, R, S, stride, pad, _t(x), _t(dy), _t(w),
+                                          _t(v) if v is not None else None, _t(wT), lr, momentum)
     if st == EUNSUPPORTED:
         return None
     _check(st, ctx.handle)

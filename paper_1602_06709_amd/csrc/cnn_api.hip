@@ -322,6 +322,41 @@ int cnn_conv_bwd_weight_sgd(cnn_ctx* ctx, int N, int C, int H, int W, int K, int
     return cnn::igemm_conv_bwd_weight(ctx, s, x, dy, sink);
 }
 
+// ---- Section 2.3's transpose-weights kept resident: made once, handed to backpropagation, refreshed by the update
+int cnn_conv_transpose_weights(cnn_ctx* ctx, int K, int C, int R, int S, const float* w, float* wT) {
+    if (!ctx || !w || !wT || K <= 0 || C <= 0 || R <= 0 || S <= 0 || !aligned16(w) || !aligned16(wT)) return CNN_EINVAL;
+    if ((double)K * C * R * S > 2147483647.0) return CNN_EUNSUPPORTED;
+    return cnn::mfma_conv_transpose_weights(ctx, K, C, R * S, w, wT);
+}
+
+int cnn_conv_bwd_data_wt(cnn_ctx* ctx, int N, int C, int H, int W, int K, int R, int S, int stride, int pad,
+                         const float* dy, const float* wT, const float* x_act, const uint8_t* arg, float* dz) {
+    if (!ctx || !dy || !wT || !dz || !aligned16(dy) || !aligned16(wT) || !aligned16(dz) || (x_act && !aligned16(x_act)) ||
+        (arg && !x_act))
+        return CNN_EINVAL;
+    ConvShape s;
+    int st = make_shape(N, C, H, W, K, R, S, stride, pad, &s);
+    if (st != CNN_OK) return st;
+    if (ctx->force_direct) return CNN_EUNSUPPORTED;
+    return cnn::mfma_conv_bwd_data_wt(ctx, s, dy, wT, dz, x_act, arg);
+}
+
+int cnn_conv_bwd_weight_sgd_wt(cnn_ctx* ctx, int N, int C, int H, int W, int K, int R, int S, int stride, int pad,
+                               const float* x, const float* dy, float* w, float* v, float* wT, float lr, float momentum) {
+    if (!ctx || !x || !dy || !w || !wT || !aligned16(x) || !aligned16(dy) || !aligned16(w) || !aligned16(wT) ||
+        (v && !aligned16(v)))
+        return CNN_EINVAL;
+    ConvShape s;
+    int st = make_shape(N, C, H, W, K, R, S, stride, pad, &s);
+    if (st != CNN_OK) return st;
+    if (ctx->force_direct) return CNN_EUNSUPPORTED;
+    if (cnn::mfma_conv_bwd_weight_keeps_wt(s))      // the reduction writes every updated weight to both copies
+        return cnn::mfma_conv_bwd_weight(ctx, s, x, dy, sink_sgd(w, v, lr, momentum, wT, s.K, s.C));
+    st = cnn_conv_bwd_weight_sgd(ctx, N, C, H, W, K, R, S, stride, pad, x, dy, w, v, lr, momentum);
+    if (st != CNN_OK) return st;
+    return cnn::mfma_conv_transpose_weights(ctx, s.K, s.C, s.R * s.S, w, wT);
+}
+
 int cnn_conv_tile_info(int op, int N, int C, int H, int W, int K, int R, int S, int stride, int pad, int32_t* tile,
                        double* bf) {
     if (!tile || !bf) return CNN_EINVAL;

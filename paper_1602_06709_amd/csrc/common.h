@@ -77,9 +77,16 @@ struct GradSink {
     float lr, mu;
     int act;             // only with w == nullptr
     const float* aux;
+    // only with w != nullptr, convolution weights [K][C][RS]: the mirrored transpose-weights kept beside them
+    // (wT[c][k][RS-1-t] = w[k][c][t], what backpropagation reads) receive every updated weight as well
+    float* wT;
+    int wt_K, wt_C;
 };
-inline GradSink sink_dw(float* dw) { return GradSink{dw, nullptr, nullptr, 0.f, 0.f, ACT_NONE, nullptr}; }
-inline GradSink sink_act(float* out, int act, const float* aux) { return GradSink{out, nullptr, nullptr, 0.f, 0.f, act, aux}; }
+inline GradSink sink_dw(float* dw) { return GradSink{dw, nullptr, nullptr, 0.f, 0.f, ACT_NONE, nullptr, nullptr, 0, 0}; }
+inline GradSink sink_act(float* out, int act, const float* aux) { return GradSink{out, nullptr, nullptr, 0.f, 0.f, act, aux, nullptr, 0, 0}; }
+inline GradSink sink_sgd(float* w, float* v, float lr, float mu, float* wT = nullptr, int K = 0, int C = 0) {
+    return GradSink{nullptr, w, v, lr, mu, ACT_NONE, nullptr, wT, K, C};
+}
 
 __device__ __forceinline__ void sink_store(const GradSink& k, size_t i, float g) {
     if (k.w) {
@@ -127,6 +134,12 @@ int direct_conv_bwd_weight(cnn_ctx*, const ConvShape&, const float* x, const flo
 int mfma_conv_fwd(cnn_ctx*, const ConvShape&, const float* x, const float* w, float* y, int relu);
 int mfma_conv_bwd_data(cnn_ctx*, const ConvShape&, const float* dy, const float* w, float* dx, const float* act,
                        const unsigned char* arg = nullptr);
+// the same with the mirrored transpose-weights handed in (wT[c][k][R-1-r][S-1-s] = w[k][c][r][s]) instead of made per call
+int mfma_conv_bwd_data_wt(cnn_ctx*, const ConvShape&, const float* dy, const float* wT, float* dx, const float* act,
+                          const unsigned char* arg);
+int mfma_conv_transpose_weights(cnn_ctx*, int K, int C, int RS, const float* w, float* wT);
+// does the weight-gradient kernel that serves the shape refresh sink.wT itself?
+bool mfma_conv_bwd_weight_keeps_wt(const ConvShape&);
 int mfma_conv_bwd_weight(cnn_ctx*, const ConvShape&, const float* x, const float* dy, const GradSink& sink);
 size_t mfma_conv_bwd_weight_ws(const ConvShape&);
 size_t mfma_conv_bwd_data_ws(const ConvShape&);

@@ -1040,6 +1040,18 @@ size_t mfma_conv_bwd_data_ws(const ConvShape& s) {
 // act != NULL: dx is zeroed where act <= 0 (act = the ReLU output that was this layer's forward input).
 // arg != NULL as well: act is a pooled ReLU output with window positions arg, and dx is the full-size (2H x 2W)
 // gradient in front of that ReLU + pool.
+int mfma_conv_transpose_weights(cnn_ctx* ctx, int K, int C, int RS, const float* w, float* wT) {
+    const int tk = transpose_tk(RS);
+    dim3 grid((unsigned)((K + tk - 1) / tk), (unsigned)((C + 31) / 32));
+    const size_t tl_bytes = ((size_t)tk * (32 * RS + 1)) * sizeof(float);
+    if (tl_bytes > 48 * 1024) return CNN_EUNSUPPORTED;
+    {
+        ProfScope ps(ctx, "k_transpose_flip", 0.0);
+        hipLaunchKernelGGL(k_transpose_flip, grid, dim3(256), tl_bytes, ctx->stream, K, C, RS, tk, w, wT);
+    }
+    return launch_check(ctx, "transpose_flip");
+}
+
 int mfma_conv_bwd_data(cnn_ctx* ctx, const ConvShape& s, const float* dy, const float* w, float* dx, const float* act,
                        const unsigned char* arg) {
     ConvPlan p;
@@ -1047,16 +1059,19 @@ int mfma_conv_bwd_data(cnn_ctx* ctx, const ConvShape& s, const float* dy, const 
     if (!ctx->ws || ctx->ws_bytes < wt_bytes(s) + p.partial_bytes) return CNN_EWORKSPACE;
     float* wT = reinterpret_cast<float*>(ctx->ws);
     float* partial = reinterpret_cast<float*>(reinterpret_cast<char*>(ctx->ws) + wt_bytes(s));
-    const int RS = s.R * s.S;
-    const int tk = transpose_tk(RS);
-    dim3 grid((unsigned)((s.K + tk - 1) / tk), (unsigned)((s.C + 31) / 32));
-    const size_t tl_bytes = ((size_t)tk * (32 * RS + 1)) * sizeof(float);
-    {
-        ProfScope ps(ctx, "k_transpose_flip", 0.0);
-        hipLaunchKernelGGL(k_transpose_flip, grid, dim3(256), tl_bytes, ctx->stream, s.K, s.C, RS, tk, w, wT);
-    }
-    int st = launch_check(ctx, "transpose_flip");
+    const int st = mfma_conv_transpose_weights(ctx, s.K, s.C, s.R * s.S, w, wT);
     if (st != CNN_OK) return st;
+    return run_plan(ctx, p, dy, wT, dx, partial, arg ? EPI_UNPOOL : (act ? EPI_MASK : EPI_NONE), act,
+                    const_cast<unsigned char*>(arg));
+}
+
+int mfma_conv_bwd_data_wt(cnn_ctx* ctx, const ConvShape& s, const float* dy, const float* wT, float* dx, const float* act,
+                          const unsigned char* arg) {
+    ConvPlan p;
+    if (!bwd_plan(s, &p)) return CNN_EUNSUPPORTED;
+    // the partial tiles sit where the plain call puts them (behind the room of its own transposed copy)
+    if (p.partial_bytes && (!ctx->ws || ctx->ws_bytes < wt_bytes(s) + p.partial_bytes)) return CNN_EWORKSPACE;
+    float* partial = p.partial_bytes ? reinterpret_cast<float*>(reinterpret_cast<char*>(ctx->ws) + wt_bytes(s)) : nullptr;
     return run_plan(ctx, p, dy, wT, dx, partial, arg ? EPI_UNPOOL : (act ? EPI_MASK : EPI_NONE), act,
                     const_cast<unsigned char*>(arg));
 }

@@ -131,7 +131,7 @@ k_gemm(int M, int Nn, int Kd, int k_per_split, const float* __restrict__ A, cons
             t = tail.whole_tiles + r / tail.nsl;
             k_begin = sl * tail.k_per_slice;
             k_end = min(k_begin + tail.k_per_slice, Kd);
-            sink = GradSink{tail.partial + (size_t)r * G::TM * G::TN, nullptr, nullptr, 0.f, 0.f, ACT_NONE, nullptr};     // a partial tile, stored [TM][TN]
+            sink = GradSink{tail.partial + (size_t)r * G::TM * G::TN, nullptr, nullptr, 0.f, 0.f, ACT_NONE, nullptr, nullptr, 0, 0};     // a partial tile, stored [TM][TN]
             ldc = G::TN;
         }
         n0 = (t % tail.tiles_n) * G::TN;

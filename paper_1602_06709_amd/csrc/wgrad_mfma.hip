@@ -382,7 +382,13 @@ __global__ void __launch_bounds__(256) k_wgrad_reduce(int nsplit, int KC, const 
                 vel = fmaf(sink.mu, vv[t], vel);
                 sink.v[e] = vel;
             }
-            sink.w[e] = fmaf(-sink.lr, vel, wv[t]);
+            const float nw = fmaf(-sink.lr, vel, wv[t]);
+            sink.w[e] = nw;
+            if (sink.wT) {      // the mirrored transpose-weights follow the update: wT[c][k][RS-1-t] = w[k][c][t]
+                const int pair = kc0 + j / RS, tap = j % RS;
+                const int k = pair / sink.wt_C, c = pair - k * sink.wt_C;
+                sink.wT[((size_t)c * sink.wt_K + k) * RS + (RS - 1 - tap)] = nw;
+            }
         }
         return;
     }
@@ -505,6 +511,11 @@ using Wg5F24 = WgCfg<5, 5, 2, 1, 5, 8, 24, 2>;
 }  // namespace
 
 namespace cnn {
+
+bool mfma_conv_bwd_weight_keeps_wt(const ConvShape& s) {
+    Plan p;
+    return make_plan<Wg3>(s, &p) || make_plan<Wg5>(s, &p) || make_plan<Wg7>(s, &p);    // all end in k_wgrad_reduce
+}
 
 size_t mfma_conv_bwd_weight_ws(const ConvShape& s) {
     Plan p;

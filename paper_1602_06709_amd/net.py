@@ -16,15 +16,20 @@ from . import synth
 
 
 class Net:
-    def __init__(self, ctx, wl: synth.Workload, weights=None, record=False, fuse=True, fuse_pool=True, fuse_sgd=True):
+    def __init__(self, ctx, wl: synth.Workload, weights=None, record=False, fuse=True, fuse_pool=True, fuse_sgd=True,
+                 resident_wt=True):
         """fuse=True folds every ReLU that follows a convolution into the convolution's store, and its derivative
         into the store of whatever produces the gradient in front of it (the next convolution's backpropagation or
         the max-pool backward); fuse=False calls one entry point per layer.
         fuse_pool (with fuse): a conv -> ReLU -> 2x2 max-pool chain becomes one call that stores only the pooled
         activation and the window positions, where the library serves the shape that way.
         fuse_sgd: step() lets each layer's weight-gradient reduction apply the SGD update (no stored gradient, no
-        separate update pass), where the library serves the shape that way."""
+        separate update pass), where the library serves the shape that way.
+        resident_wt: every convolution that backpropagates keeps the mirrored transpose-weights (Section 2.3) beside its
+        weights; backpropagation reads them, the folded update refreshes them, and they are re-made only after the
+        weights were changed some other way."""
         self.ctx, self.wl, self.record, self.fuse = ctx, wl, record, fuse
+        self.resident_wt = bool(resident_wt)
         self.fuse_sgd = bool(fuse_sgd)
         self.fuse_pool = bool(fuse and fuse_pool)
         self.layers = list(wl.layers)
@@ -68,6 +73,8 @@ class Net:
         self.labels = torch.zeros(n, dtype=torch.int32, device=dev)
         self.loss_per_sample = torch.empty(n, dtype=torch.float32, device=dev)
         self.trace = []
+        self.wT = [None] * len(self.w)          # resident transpose-weights per convolution, made on first use
+        self._wt_state = {}                     # weight index -> "fresh" | "stale" | "off" (not served)
         self._fc_fused = set()
         self._pooled_ok, self._pooled_first = None, False
         self.marks = None   # a list while a caller wants (op, layer, profile-entry count after the call) per call
@@ -180,6 +187,43 @@ class Net:
                                B.conv_bwd_weight_unpool_serves(n[0], L[1], n[2], n[3], L[2], L[3], L[4], L[5], L[6]))
         return self._pooled_ok
 
+    def _wt_for(self, wi):
+        """The resident transpose-weights of convolution wi, current with its weights; None where not kept."""
+        if not self.resident_wt or self._wt_state.get(wi) == "off":
+            return None
+        if self.wT[wi] is None:
+            K, C, R, S = self.w[wi].shape
+            self.wT[wi] = torch.empty((C, K, R, S), dtype=torch.float32, device=self.w[wi].device)
+            self._wt_state[wi] = "stale"
+        if self._wt_state[wi] == "stale":
+            if B.cnn_conv_transpose_weights(self.ctx, self.w[wi], out=self.wT[wi]) is None:
+                self._wt_state[wi], self.wT[wi] = "off", None
+                return None
+            self._wt_state[wi] = "fresh"
+            if self.marks is not None:
+                self.marks.append(("transpose_weights", -1, self.ctx.profile_count(), 0))
+        return self.wT[wi]
+
+    def _weights_changed(self, wi=None):
+        for k in (range(len(self.w)) if wi is None else (wi,)):
+            if self._wt_state.get(k) == "fresh":
+                self._wt_state[k] = "stale"
+
+    def _bwd_data(self, i, wi, dy, H, W, x_act=None, arg=None, out=None):
+        """One of the three backpropagation forms of convolution i, from the resident transpose-weights where kept."""
+        ctx, L = self.ctx, self.layers[i]
+        wT = self._wt_for(wi)
+        if wT is not None:
+            r = B.cnn_conv_bwd_data_wt(ctx, dy, wT, H, W, L[5], L[6], x_act=x_act, arg=arg, out=out)
+            if r is not None:
+                return r
+            self._wt_state[wi], self.wT[wi] = "off", None
+        if arg is not None:
+            return B.cnn_conv_bwd_data_unpool_relu(ctx, dy, self.w[wi], arg, x_act, L[5], L[6], out=out)
+        if x_act is not None:
+            return B.cnn_conv_bwd_data_relu(ctx, dy, self.w[wi], x_act, L[5], L[6], out=out)
+        return B.cnn_conv_bwd_data(ctx, dy, self.w[wi], H, W, L[5], L[6], out=out)
+
     def _wgrad(self, i, wi, update):
         """Weight gradient of conv layer i; with update, applied to the weights on the spot."""
         ctx, L, xin, dy = self.ctx, self.layers[i], self._input_of(i), self.gact[i]
@@ -195,7 +239,14 @@ class Net:
                 self._rec("conv_bwd_weight_unpool", i, wi, xin, dpool, arg, self.dw[wi])
             return
         if update:
-            done = B.cnn_conv_bwd_weight_sgd(ctx, xin, dy, self.w[wi], self.v[wi], L[5], L[6], self.wl.lr, self.wl.momentum)
+            done = None
+            if self._wt_state.get(wi) == "fresh":       # the update keeps the resident transpose-weights current
+                done = B.cnn_conv_bwd_weight_sgd_wt(ctx, xin, dy, self.w[wi], self.wT[wi], self.v[wi], L[5], L[6],
+                                                    self.wl.lr, self.wl.momentum)
+            if done is None:
+                done = B.cnn_conv_bwd_weight_sgd(ctx, xin, dy, self.w[wi], self.v[wi], L[5], L[6], self.wl.lr, self.wl.momentum)
+                if done is not None:
+                    self._weights_changed(wi)
             if done is not None:
                 self._rec("conv_bwd_weight_sgd", i, wi, xin, dy, self.w[wi], self.v[wi])
                 return
@@ -205,6 +256,7 @@ class Net:
             self._sgd_layer(wi)
 
     def _sgd_layer(self, wi):
+        self._weights_changed(wi)
         v = self.v[wi].view(-1) if self.v[wi] is not None else None
         B.cnn_sgd_update(self.ctx, self.w[wi].view(-1), self.dw[wi].view(-1), v, self.wl.lr, self.wl.momentum)
         if self.marks is not None:
@@ -237,24 +289,24 @@ class Net:
                 if pool_in and i == 3 and self._pooled_wgrad_serves():
                     # the convolution in front of that ReLU + pool is the first layer: only its weight gradient wants
                     # the gradient, and it takes it at pooled size (Section 3.1: no backpropagation there)
-                    B.cnn_conv_bwd_data_relu(ctx, dy, self.w[wi], xin, L[5], L[6], out=self.gact[i - 1])
+                    self._bwd_data(i, wi, dy, xin.shape[2], xin.shape[3], x_act=xin, out=self.gact[i - 1])
                     self._rec("conv_bwd_data_relu", i, wi, dy, self.w[wi], xin, self.gact[i - 1])
                     skip.update((i - 1, i - 2))
                     self._pooled_first = True
                 elif not first and pool_in:
                     # gradient in front of that ReLU + pool, straight into the earlier convolution's slot
-                    unpooled = B.cnn_conv_bwd_data_unpool_relu(ctx, dy, self.w[wi], self.arg[i - 1], xin, L[5], L[6],
-                                                               out=self.gact[i - 3])
+                    unpooled = self._bwd_data(i, wi, dy, xin.shape[2], xin.shape[3], x_act=xin, arg=self.arg[i - 1],
+                                              out=self.gact[i - 3])
                 if unpooled is not None:
                     self._rec("conv_bwd_data_unpool_relu", i, wi, dy, self.w[wi], self.arg[i - 1], xin, self.gact[i - 3])
                     skip.update((i - 1, i - 2))
                 elif not first and not (pool_in and i == 3 and self._pooled_first):
                     if relu_in:      # gradient in front of that ReLU, straight into the earlier convolution's slot
-                        B.cnn_conv_bwd_data_relu(ctx, dy, self.w[wi], xin, L[5], L[6], out=self.gact[i - 2])
+                        self._bwd_data(i, wi, dy, xin.shape[2], xin.shape[3], x_act=xin, out=self.gact[i - 2])
                         self._rec("conv_bwd_data_relu", i, wi, dy, self.w[wi], xin, self.gact[i - 2])
                         skip.add(i - 1)
                     else:
-                        B.cnn_conv_bwd_data(ctx, dy, self.w[wi], xin.shape[2], xin.shape[3], L[5], L[6], out=dxb)
+                        self._bwd_data(i, wi, dy, xin.shape[2], xin.shape[3], out=dxb)
                         self._rec("conv_bwd_data", i, wi, dy, self.w[wi], dxb)
                 if update:           # backpropagation has read this iteration's weights: they may change now
                     self._wgrad(i, wi, True)
@@ -310,6 +362,7 @@ class Net:
         return None
 
     def sgd(self):
+        self._weights_changed()
         B.cnn_sgd_update(self.ctx, self.w_arena, self.dw_arena, self.v_arena, self.wl.lr, self.wl.momentum)
         if self.marks is not None:
             self.marks.append(("sgd_update", -1, self.ctx.profile_count(), 0))

@@ -497,6 +497,66 @@ def test_conv_weight_gradient_with_the_sgd_step_folded_in(cnn, ctx, case):
         P.check_fused_update(f"wsgd{case}", w0, v0 if use_v else None, g_ref, sabs, w, v, lr, mu)
 
 
+def _mirrored_transpose(w):
+    """wT[c][k][r][s] = w[k][c][R-1-r][S-1-s], by torch indexing (a permutation: exact)."""
+    return w.flip(2, 3).transpose(0, 1).contiguous()
+
+
+@pytest.mark.parametrize("case", [(4, 64, 28, 128, 3, 1, 1), (3, 16, 28, 72, 3, 1, 1), (2, 32, 12, 64, 5, 1, 2), (2, 24, 14, 40, 7, 1, 3),
+                                  (8, 128, 14, 256, 3, 1, 1), (2, 32, 20, 48, 1, 1, 0), (2, 16, 15, 24, 3, 2, 1)])
+def test_resident_transpose_weights(cnn, ctx, case):
+    # Section 2.3's transpose-weights kept beside the weights: made once, read by the three backpropagation forms
+    # (same bits as the calls that transpose per call), refreshed by the folded update (ring-buffer kernel: inside the
+    # reduction; other kernels: by a transpose behind the update)
+    N, C, H, K, R, stride, pad = case
+    say("resident wT case", case)
+    P_ = (H + 2 * pad - R) // stride + 1
+    w0 = synth.randn(92, 1, (K, C, R, R), 0.05); v0 = synth.randn(92, 2, (K, C, R, R), 0.5)
+    x = np.maximum(synth.randn(92, 3, (N, C, H, H)), 0).astype(np.float32); dy = synth.randn(92, 4, (N, K, P_, P_))
+    w = dev(w0)
+    wT = cnn.cnn_conv_transpose_weights(ctx, w)
+    assert wT is not None and torch.equal(wT, _mirrored_transpose(w))
+    served = cnn.cnn_conv_bwd_data_wt(ctx, dev(dy), wT, H, H, stride, pad)
+    if stride != 1 or R == 1:
+        assert served is None                       # only the implicit GEMM serves these: the plain calls remain
+    else:
+        assert torch.equal(served, cnn.cnn_conv_bwd_data(ctx, dev(dy), w, H, H, stride, pad))
+        assert torch.equal(cnn.cnn_conv_bwd_data_wt(ctx, dev(dy), wT, H, H, stride, pad, x_act=dev(x)),
+                           cnn.cnn_conv_bwd_data_relu(ctx, dev(dy), w, dev(x), stride, pad))
+        arg = torch.from_numpy(synth.rng(92, 5).integers(0, 4, (N, C, H, H)).astype(np.uint8)).cuda()
+        ref = cnn.cnn_conv_bwd_data_unpool_relu(ctx, dev(dy), w, arg, dev(x), stride, pad)
+        got = cnn.cnn_conv_bwd_data_wt(ctx, dev(dy), wT, H, H, stride, pad, x_act=dev(x), arg=arg)
+        assert (ref is None and got is None) or torch.equal(got, ref)
+    # two folded updates in a row: the second one starts from the first one's weights and velocity
+    w1, v1, w2, v2 = dev(w0), dev(v0), dev(w0), dev(v0)
+    for it in range(2):
+        assert cnn.cnn_conv_bwd_weight_sgd_wt(ctx, dev(x), dev(dy), w1, wT, v1, stride, pad, 0.01, 0.9) is not None
+        assert cnn.cnn_conv_bwd_weight_sgd(ctx, dev(x), dev(dy), w2, v2, stride, pad, 0.01, 0.9) is not None
+        torch.cuda.synchronize()
+        assert torch.equal(w1, w2) and torch.equal(v1, v2), f"update {it}: weights differ from cnn_conv_bwd_weight_sgd"
+        assert torch.equal(wT, _mirrored_transpose(w1)), f"update {it}: transpose-weights not current"
+
+
+def test_training_steps_keep_the_resident_transpose_weights_current(cnn, ctx):
+    # VGG-A's convolution stack at minibatch 4 with an update: after every step each convolution's transpose-weights
+    # equal the mirrored transpose of its weights; same weights as a net that transposes per call
+    from paper_1602_06709_amd.net import Net
+    wl = dataclasses.replace(synth.workload(2), sgd=True, lr=1e-5, momentum=0.9)    # small steps: everything stays finite
+    nets = [Net(ctx, wl, synth.make_weights(wl), resident_wt=r) for r in (True, False)]
+    for it in range(3):
+        for net in nets:
+            net.set_input(synth.make_input(wl)); net.set_upstream(synth.make_upstream(wl))
+            net.step()
+        torch.cuda.synchronize()
+        assert bool(torch.isfinite(nets[0].w_arena).all())
+        assert torch.equal(nets[0].w_arena, nets[1].w_arena) and torch.equal(nets[0].v_arena, nets[1].v_arena)
+        kept = [wi for wi, t in enumerate(nets[0].wT) if t is not None]
+        assert len(kept) == 7 and all(nets[0]._wt_state[wi] == "fresh" for wi in kept)
+        for wi in kept:
+            assert torch.equal(nets[0].wT[wi], _mirrored_transpose(nets[0].w[wi])), f"step {it} layer {wi}"
+    assert all(t is None for t in nets[1].wT)
+
+
 def test_folded_sgd_refuses_what_only_the_plain_kernels_serve(cnn, ctx):
     x = dev(synth.randn(95, 5, (2, 5, 9, 9))); dy = dev(synth.randn(95, 6, (2, 7, 9, 9)))
     w0 = synth.randn(95, 7, (7, 5, 3, 3)); w = dev(w0)
