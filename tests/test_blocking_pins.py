@@ -182,3 +182,28 @@ def test_traversal_search_equals_plain_enumeration(layer, acc, stage, simd, chun
     n, c, k, p, q, r, s, st = layer
     assert B.trav_stage_bytes(got, r, s, st) <= stage and 4 * got[0] * got[1] * got[3] * got[4] <= acc
     assert got_bf == B.trav_bytes(got, c, r, s, st) / B.trav_flops(got, c, r, s)
+
+
+def test_traversal_model_hand_worked_example():
+    # tests/golden/hand_blocking.txt: the traversal form's bytes, FLOPs and staging need of one block, by hand
+    g = {}
+    for line in open(os.path.join(os.path.dirname(GOLD), "hand_blocking.txt")):
+        line = line.split("#")[0].strip()
+        if "=" in line:
+            k, v = line.split("=", 1)
+            g[k.strip()] = v.strip()
+    block = tuple(int(t) for t in g["block"].split())
+    ifm, k_h, k_w, st = int(g["ifm"]), int(g["k_h"]), int(g["k_w"]), int(g["stride"])
+    assert B.trav_bytes(block, ifm, k_h, k_w, st) == int(g["trav_bytes"])
+    assert B.trav_flops(block, ifm, k_h, k_w) == int(g["trav_flops"])
+    assert B.trav_stage_bytes(block, k_h, k_w, st) == int(g["stage_bytes"])
+    assert 4 * block[0] * block[1] * block[3] * block[4] == int(g["acc_bytes"])
+    assert round(B.trav_bytes(block, ifm, k_h, k_w, st) / B.trav_flops(block, ifm, k_h, k_w), 6) == float(g["bf_rounded_6"])
+    # a slip each moves a number: the halo forgotten, one staging buffer instead of two, the kernel taps dropped from
+    # the weight share
+    assert B.trav_bytes(block, ifm, 1, 1, st) != int(g["trav_bytes"])
+    assert B.trav_stage_bytes(block, k_h, k_w, st) != int(g["stage_bytes"]) // 2
+    # the search never returns a block that breaks either limit, and finds this block feasible under its own needs
+    got, bf, cnt = B.trav_search((2, ifm, 64, 4, 56, k_h, k_w, st), int(g["acc_bytes"]), int(g["stage_bytes"]), 32, 4)
+    assert cnt > 0 and bf <= float(g["bf_rounded_6"]) + 1e-6
+    assert B.trav_stage_bytes(got, k_h, k_w, st) <= int(g["stage_bytes"])
