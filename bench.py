@@ -89,10 +89,10 @@ class Clocks:
 def calibrate(cnn, ctx, torch, n_floats, reps=5):
     """The box's own ceilings, each the best of `reps` launches timed by the library's HIP events: a register-only
     fp32 MFMA loop, and read / write / copy streams plus both SGD updates over arrays of n_floats floats."""
+    from paper_1602_06709_amd.net import carve_arrays
     n = n_floats // 4 * 4
-    a = torch.ones(n, dtype=torch.float32, device="cuda")
-    b = torch.zeros(n, dtype=torch.float32, device="cuda")
-    c = torch.zeros(n, dtype=torch.float32, device="cuda")
+    a, b, c = carve_arrays(n, 3, "cuda")          # laid out as the network lays out weights / gradients / momentum
+    a.fill_(1.0)
     sink = torch.empty(cnn.PROBE_SINK_FLOATS, dtype=torch.float32, device="cuda")
     was = ctx.profile_count()
     ctx.profile(True)

@@ -299,7 +299,7 @@ int cnn_sgd_update(cnn_ctx* ctx, size_t n, float* w, const float* dw, float* v, 
     static std::atomic<bool> attr_done{false};
     if (!attr_done) {
         hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(&k_sgd<true>),
-                                           hipFuncAttributeMaxDynamicSharedMemorySize, kSgdLdsPlain);
+                                           hipFuncAttributeMaxDynamicSharedMemorySize, kSgdLds);
         if (e == hipSuccess)
             e = hipFuncSetAttribute(reinterpret_cast<const void*>(&k_sgd<false>),
                                     hipFuncAttributeMaxDynamicSharedMemorySize, kSgdLdsPlain);

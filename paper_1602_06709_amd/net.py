@@ -15,6 +15,18 @@ from . import binding as B
 from . import synth
 
 
+def carve_arrays(n_floats, count, dev):
+    """`count` zeroed float arrays of n_floats each, cut from ONE device allocation, each start 16-byte aligned and
+    shifted by a few KB against its neighbours.  The update that streams weights, gradients and momentum side by
+    side ran at 6.8-6.9 TB/s on arrays laid out this way and at 6.3-6.4 TB/s on three separate allocations of the
+    same sizes (same kernel, same launches), so every set of arrays that is walked in lock step is made here."""
+    slot = (n_floats + 1023) // 1024 * 1024
+    shift = [0, 5 * 1024, 11 * 1024, 19 * 1024]
+    assert count <= len(shift)
+    block = torch.zeros(slot * count + shift[count - 1], dtype=torch.float32, device=dev)
+    return [block[i * slot + shift[i]: i * slot + shift[i] + n_floats] for i in range(count)]
+
+
 class Net:
     def __init__(self, ctx, wl: synth.Workload, weights=None, record=False, fuse=True, fuse_pool=True, fuse_sgd=True,
                  resident_wt=True):
@@ -43,9 +55,9 @@ class Net:
             total += (n + 3) // 4 * 4
         self.n_params = sum(sizes)
         self.arena_elems = total
-        self.w_arena = torch.zeros(total, dtype=torch.float32, device=dev)
-        self.dw_arena = torch.zeros(total, dtype=torch.float32, device=dev)
-        self.v_arena = torch.zeros(total, dtype=torch.float32, device=dev) if wl.momentum != 0.0 else None
+        arenas = carve_arrays(total, 3 if wl.momentum != 0.0 else 2, dev)
+        self.w_arena, self.dw_arena = arenas[0], arenas[1]
+        self.v_arena = arenas[2] if wl.momentum != 0.0 else None
         self.w = [self.w_arena[o:o + n].view(s) for o, n, s in zip(offs, sizes, wshapes)]
         self.dw = [self.dw_arena[o:o + n].view(s) for o, n, s in zip(offs, sizes, wshapes)]
         self.v = ([self.v_arena[o:o + n].view(s) for o, n, s in zip(offs, sizes, wshapes)] if self.v_arena is not None
