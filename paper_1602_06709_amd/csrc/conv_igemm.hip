@@ -10,12 +10,17 @@
 // Nothing is copied or unfolded in memory: the second operand is gathered element by element on its way into LDS.
 // An element's address is the sum of a part that depends on its position along the contraction and a part that
 // depends on its output column; the part that is fixed for a thread sits in registers, the part that varies comes
-// from a small table in LDS (per chunk of the contraction: rebuilt two chunks ahead; per output column: built once).
+// from a small table in LDS (per chunk of the contraction: built three chunks ahead by one thread in eight; per
+// output column: built once).
 //
 // Workgroup: 2 x 2 waves, each WMT x WNT blocks of 32 x 32 (v_mfma_f32_32x32x2_f32); chunks of 32 contraction
-// elements, two LDS buffers, one barrier per chunk; the next chunk's elements are fetched into registers before the
-// chunk's MFMAs and stored to LDS after them.  The weight gradient splits the contraction over workgroups and adds
-// the partial products in a fixed order (Section 3.1: the sum over the minibatch).
+// elements in two LDS buffers, one barrier per chunk.  The chunk loop is one straight-line block of eight MFMA groups:
+// between the groups, the registers holding chunk c + 1 go to the other LDS buffer one element at a time and each is
+// refilled at once with its element of chunk c + 2, so every load has a whole chunk to arrive; operands are read one
+// group ahead.  Tensors below 2 GiB are fetched by raw buffer loads (32-bit byte offsets, the hardware returns 0 for
+// an element marked as outside), larger ones through 64-bit addresses.  The weight gradient splits the contraction
+// over one resident round of workgroups and adds the partial products in a fixed order (Section 3.1: the sum over
+// the minibatch).
 #include <stdio.h>
 
 #include "common.h"
@@ -32,6 +37,7 @@ struct IgArgs {
     int M, Nn, Kd;             // the GEMM's sizes: rows, columns, contraction
     int k_per_split;
     int relu;
+    unsigned a_bytes, b_bytes, o_bytes;   // sizes of the operand and output tensors, for their buffer descriptors (below 2 GiB)
 };
 
 // Backpropagation, one phase (a, b) of the stride: input rows h0 + st i (i < Hn) see kernel rows a + st r' (r' < Rn)
@@ -131,7 +137,19 @@ __device__ __forceinline__ int a_k_part(const IgArgs& g, const Phase& ph, int kk
     return n * g.K * PQ + (kk - n * PQ);
 }
 
-template <int MODE, int WMT, int WNT>
+// One table entry per contraction index of a chunk: the gathered operand's part that depends on that index (kernel
+// tap for forward / backpropagation, pixel for the weight gradient) and the first operand's offset along the
+// contraction (-1 past the end of the contraction: such an element is fetched as 0 on both sides).
+template <int MODE>
+__device__ __forceinline__ int4 chunk_entry(const IgArgs& g, const Phase& ph, int kk, int k_end) {
+    const Part t = MODE == WGR ? pix_part<MODE>(g, ph, kk, k_end) : tap_part<MODE>(g, ph, kk, k_end);
+    return make_int4(t.off, t.a, t.b, kk < k_end ? a_k_part<MODE>(g, ph, kk) : -1);
+}
+
+// WIDE = false: both operands are below 2 GiB and are fetched by raw buffer loads with 32-bit byte offsets (an
+// element that contributes 0 gets an offset beyond the descriptor and the hardware returns 0); WIDE = true: 64-bit
+// addresses, a clamped offset and a bit per element that decides at the LDS store whether it counts.
+template <int MODE, int WMT, int WNT, bool WIDE>
 __global__ void __launch_bounds__(256, 2)
 k_conv_igemm(IgArgs g, const float* __restrict__ Asrc, const float* __restrict__ Bsrc, const float* __restrict__ act,
              GradSink sink) {
@@ -141,9 +159,13 @@ k_conv_igemm(IgArgs g, const float* __restrict__ Asrc, const float* __restrict__
     constexpr int B_LDS = BKM ? KC * TN : TN * (KC + 1);
     constexpr int BUF = A_LDS + B_LDS;
     constexpr int NA = TM * KC / 256, NB = TN * KC / 256;   // elements per thread and chunk
-    constexpr int NTAB = BKM ? 2 * KC : TN;                 // table entries (two chunk tables, or one per column)
-    extern __shared__ __attribute__((aligned(16))) float lds[];     // two operand buffers, then the table
-    int4* const tab = reinterpret_cast<int4*>(lds + 2 * BUF);       // (off, a, b, -) per entry: one 16-byte read
+    constexpr int NITEMS = NA + NB;
+    constexpr int NG = KC / 4;                              // MFMA groups per chunk: two contraction steps each
+    constexpr int IPG = (NITEMS + NG - 1) / NG;             // staging items per group
+    constexpr int SC = WIDE ? 1 : 4;                        // offsets in elements (64-bit addressing) or bytes
+    extern __shared__ __attribute__((aligned(16))) float lds[];     // two operand buffers, then the tables
+    int4* const ktab = reinterpret_cast<int4*>(lds + 2 * BUF);      // [2][KC]: chunk tables, built three chunks ahead
+    int4* const ctab = ktab + 2 * KC;                               // [TN]: per output column (weight gradient only)
 
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
     const int half = lane >> 5, l32 = lane & 31;
@@ -171,107 +193,187 @@ k_conv_igemm(IgArgs g, const float* __restrict__ Asrc, const float* __restrict__
 #pragma unroll
             for (int v = 0; v < 16; ++v) acc[i][j][v] = 0.f;
 
-    // ---- staging: who fetches what
-    constexpr int RSTEP = 256 / KC;
-    const int kq = tid % KC, rbase = tid / KC;              // operands stored [row][KC+1]: fixed k, rows rbase + RSTEP i
-    const int a_rs = a_row_stride<MODE>(g);
-    const int bn = tid % TN, bk = tid / TN;                 // BKM: fixed column, k = bk + (256 / TN) i
-    Part fix;                                               // the thread's fixed part of the second operand
-    if (BKM) fix = pix_part<MODE>(g, ph, n0 + bn, Nn);
-
-    auto build_ktab = [&](int c) {                          // chunk c's table of contraction positions (BKM only)
-        if (BKM && tid < KC) {
-            const Part t = tap_part<MODE>(g, ph, k_begin + c * KC + tid, k_end);
-            tab[(c & 1) * KC + tid] = make_int4(t.off, t.a, t.b, 0);
-        }
-    };
-    // fetched elements and, one bit each, whether they count: the selection happens when they go to LDS, so that no
-    // load has a consumer before the chunk's MFMAs (a select right behind each load makes the compiler wait for it)
-    float ra[NA], rb[NB];
-    unsigned oka = 0, okb = 0;
-    auto fetch = [&](int c) {
-        oka = 0; okb = 0;
-        const int k0 = k_begin + c * KC;
-        {
-            const int kk = k0 + kq;
-            const bool kok = kk < k_end;
-            const int kp = a_k_part<MODE>(g, ph, kok ? kk : k_begin);
-#pragma unroll
-            for (int i = 0; i < NA; ++i) {
-                const int m = m0 + rbase + RSTEP * i;
-                const bool ok = kok & (m < g.M);
-                ra[i] = Asrc[ok ? (size_t)(m * a_rs + kp) : 0];
-                oka |= (unsigned)ok << i;
-            }
-        }
-        // table entries four at a time, every read issued before its first use (a read behind a comparison would
-        // expose the LDS latency once per element)
-        Part px = fix;
-        if (!BKM) px = pix_part<MODE>(g, ph, k0 + kq, k_end);
-#pragma unroll
-        for (int i0 = 0; i0 < NB; i0 += 4) {
-            int4 t4[4];
-#pragma unroll
-            for (int u = 0; u < 4; ++u)
-                t4[u] = tab[BKM ? (c & 1) * KC + bk + (256 / TN) * (i0 + u) : rbase + RSTEP * (i0 + u)];
-#pragma unroll
-            for (int u = 0; u < 4; ++u) {
-                Part t;
-                t.off = t4[u].x; t.a = t4[u].y; t.b = t4[u].z;
-                const int o = gather_offset<MODE>(g, px, t);
-                rb[i0 + u] = Bsrc[o >= 0 ? (size_t)o : 0];
-                okb |= (unsigned)(o >= 0) << (i0 + u);
-            }
-        }
-    };
-    auto stage = [&](int buf) {
-        float* la = lds + buf * BUF;
-        float* lb = la + A_LDS;
-#pragma unroll
-        for (int i = 0; i < NA; ++i) la[(rbase + RSTEP * i) * (KC + 1) + kq] = (oka >> i) & 1 ? ra[i] : 0.f;
-        if (BKM) {
-#pragma unroll
-            for (int i = 0; i < NB; ++i) lb[(bk + (256 / TN) * i) * TN + bn] = (okb >> i) & 1 ? rb[i] : 0.f;
-        } else {
-#pragma unroll
-            for (int i = 0; i < NB; ++i) lb[(rbase + RSTEP * i) * (KC + 1) + kq] = (okb >> i) & 1 ? rb[i] : 0.f;
-        }
-    };
-
     if (nchunks > 0) {
-        if (BKM) {
-            build_ktab(0);
-            if (nchunks > 1) build_ktab(1);
-        } else if (tid < TN) {
+        // ---- staging: who fetches what.  Operands stored [row][KC+1]: a thread has a fixed contraction index kq
+        // and rows rbase + RSTEP i; the [k][TN] operand: a fixed column bn and contraction indices bk + BSTEP i.
+        constexpr int RSTEP = 256 / KC, BSTEP = 256 / TN;
+        const int kq = tid % KC, rbase = tid / KC;
+        const int bn = tid % TN, bk = tid / TN;
+        const int a_rs = a_row_stride<MODE>(g);
+        const __amdgpu_buffer_rsrc_t rs_a = __builtin_amdgcn_make_buffer_rsrc(
+            const_cast<float*>(Asrc), 0, (int)g.a_bytes, kRsrcWord3);
+        const __amdgpu_buffer_rsrc_t rs_b = __builtin_amdgcn_make_buffer_rsrc(
+            const_cast<float*>(Bsrc), 0, (int)g.b_bytes, kRsrcWord3);
+        // rows past the last one repeat it: their products land in output rows that are never stored
+        int a_ro[NA];
+#pragma unroll
+        for (int i = 0; i < NA; ++i) a_ro[i] = min(m0 + rbase + RSTEP * i, g.M - 1) * a_rs * SC;
+        Part fix = {};                                      // the thread's fixed part of the second operand
+        if (BKM) fix = pix_part<MODE>(g, ph, n0 + bn, Nn);
+
+        auto build_ktab = [&](int c) {
+            if (tid < KC) ktab[(c & 1) * KC + tid] = chunk_entry<MODE>(g, ph, k_begin + c * KC + tid, k_end);
+        };
+        build_ktab(0);
+        build_ktab(1);
+        if (!BKM && tid < TN) {
             const Part t = tap_part<MODE>(g, ph, n0 + tid, Nn);
-            tab[tid] = make_int4(t.off, t.a, t.b, 0);
+            ctab[tid] = make_int4(t.off, t.a, t.b, 0);
         }
         __syncthreads();
-        fetch(0);
-        stage(0);
-        __syncthreads();
-        constexpr int b_sr = BKM ? 1 : KC + 1, b_sk = BKM ? TN : 1;
-        for (int c = 0; c < nchunks; ++c) {
-            const bool more = c + 1 < nchunks;
-            if (more) fetch(c + 1);
-            const float* ap = lds + (c & 1) * BUF + (wm * WMT * 32 + l32) * (KC + 1) + half * (KC / 2);
-            const float* bp = lds + (c & 1) * BUF + A_LDS + (wn * WNT * 32 + l32) * b_sr + half * (KC / 2) * b_sk;
-#pragma unroll
-            for (int kk = 0; kk < KC / 2; ++kk) {
-                float a[WMT], b[WNT];
-#pragma unroll
-                for (int i = 0; i < WMT; ++i) a[i] = ap[i * 32 * (KC + 1) + kk];
-#pragma unroll
-                for (int j = 0; j < WNT; ++j) b[j] = bp[j * 32 * b_sr + kk * b_sk];
-#pragma unroll
-                for (int i = 0; i < WMT; ++i)
-#pragma unroll
-                    for (int j = 0; j < WNT; ++j)
-                        acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x2f32(a[i], b[j], acc[i][j], 0, 0, 0);
+
+        float ra[NA], rb[NB];
+        unsigned oka = 0, okb = 0;                          // WIDE: one bit per fetched element, set if it counts
+        int a_kv = 0;                                       // the chunk's first-operand offset along the contraction
+        Part px = {};                                       // weight gradient: the chunk's pixel for this thread
+        lds_float* a_dst = (lds_float*)(lds + rbase * (KC + 1) + kq);
+        lds_float* b_dst = (lds_float*)(lds + A_LDS + (BKM ? bk * TN + bn : rbase * (KC + 1) + kq));
+        auto begin_chunk = [&](int c) {                     // this thread's entry of chunk c's table
+            const int4 e = ktab[(c & 1) * KC + kq];
+            a_kv = WIDE ? e.w : (e.w >= 0 ? e.w * 4 : kOutOfRange);
+            px.off = e.x; px.a = e.y; px.b = e.z;
+        };
+        auto table_entry = [&](int c, int j) {              // what B element j of chunk c combines with the thread's part
+            return BKM ? ktab[(c & 1) * KC + bk + BSTEP * j] : ctab[rbase + RSTEP * j];
+        };
+        auto fetch_a = [&](int i) {
+            if (WIDE) {
+                const bool ok = a_kv >= 0;
+                ra[i] = Asrc[ok ? (size_t)(a_ro[i] + a_kv) : 0];
+                oka = (oka & ~(1u << i)) | ((unsigned)ok << i);
+            } else {
+                ra[i] = __builtin_bit_cast(float, __builtin_amdgcn_raw_buffer_load_b32(rs_a, a_ro[i] + a_kv, 0, 0));
             }
-            if (more) stage((c + 1) & 1);
-            if (c + 2 < nchunks) build_ktab(c + 2);
-            __syncthreads();
+        };
+        auto fetch_b = [&](int j, const int4& e) {
+            Part t;
+            t.off = e.x; t.a = e.y; t.b = e.z;
+            const int o = gather_offset<MODE>(g, BKM ? fix : px, t);
+            if (WIDE) {
+                rb[j] = Bsrc[o >= 0 ? (size_t)o : 0];
+                okb = (okb & ~(1u << j)) | ((unsigned)(o >= 0) << j);
+            } else {
+                rb[j] = __builtin_bit_cast(float, __builtin_amdgcn_raw_buffer_load_b32(rs_b, o >= 0 ? o * 4 : kOutOfRange, 0, 0));
+            }
+        };
+        auto stage_a = [&](int i) { a_dst[i * RSTEP * (KC + 1)] = (!WIDE || ((oka >> i) & 1)) ? ra[i] : 0.f; };
+        auto stage_b = [&](int j) {
+            b_dst[BKM ? j * BSTEP * TN : j * RSTEP * (KC + 1)] = (!WIDE || ((okb >> j) & 1)) ? rb[j] : 0.f;
+        };
+        auto fetch_all = [&](int c) {
+            begin_chunk(c);
+#pragma unroll
+            for (int i = 0; i < NA; ++i) fetch_a(i);
+#pragma unroll
+            for (int j0 = 0; j0 < NB; j0 += 4) {
+                int4 e[4];
+#pragma unroll
+                for (int u = 0; u < 4; ++u) e[u] = table_entry(c, j0 + u);
+#pragma unroll
+                for (int u = 0; u < 4; ++u) fetch_b(j0 + u, e[u]);
+            }
+        };
+
+        // chunk 0 to LDS buffer 0, chunk 1 to the registers, then the table of chunk 2 over that of chunk 0
+        fetch_all(0);
+#pragma unroll
+        for (int i = 0; i < NA; ++i) stage_a(i);
+#pragma unroll
+        for (int j = 0; j < NB; ++j) stage_b(j);
+        fetch_all(1);
+        __syncthreads();
+        build_ktab(2);
+        __syncthreads();
+
+        // LDS read pointers of the wave's blocks; the high wave half starts KC/2 further along the contraction
+        constexpr int b_sr = BKM ? 1 : KC + 1, b_sk = BKM ? TN : 1;
+        const lds_float* ap = (const lds_float*)(lds + (wm * WMT * 32 + l32) * (KC + 1) + half * (KC / 2));
+        const lds_float* bp = (const lds_float*)(lds + A_LDS + (wn * WNT * 32 + l32) * b_sr + half * (KC / 2) * b_sk);
+        auto read_group = [&](int gq, float (&a)[WMT][2], float (&b)[WNT][2]) {
+#pragma unroll
+            for (int i = 0; i < WMT; ++i)
+#pragma unroll
+                for (int t = 0; t < 2; ++t) a[i][t] = ap[i * 32 * (KC + 1) + 2 * gq + t];
+#pragma unroll
+            for (int j = 0; j < WNT; ++j)
+#pragma unroll
+                for (int t = 0; t < 2; ++t) b[j][t] = bp[j * 32 * b_sr + (2 * gq + t) * b_sk];
+        };
+        // the table entries of a group's B items are read one group ahead
+        auto read_entries = [&](int c, int gq, int4 (&e)[IPG]) {
+#pragma unroll
+            for (int u = 0; u < IPG; ++u) {
+                const int it = gq * IPG + u;
+                if (it >= NA && it < NITEMS) e[u] = table_entry(c, it - NA);
+            }
+        };
+
+        float a_cur[WMT][2], b_cur[WNT][2];
+        read_group(0, a_cur, b_cur);
+        int wr_off = BUF;                         // staging writes go to the buffer that is not being read
+        a_dst += wr_off;
+        b_dst += wr_off;
+        int4 e_cur[IPG] = {};
+        begin_chunk(2);
+        read_entries(2, 0, e_cur);
+        // Chunk c: its MFMAs, group by group; between them the registers' elements (chunk c + 1) go to the other LDS
+        // buffer one by one, each register being refilled at once with its element of chunk c + 2; one thread in
+        // eight also builds the table of chunk c + 3.  Everything past the end of the contraction is fetched as 0.
+        for (int c = 0; c < nchunks; ++c) {
+            build_ktab(c + 3);
+#pragma unroll
+            for (int gq = 0; gq < NG; ++gq) {
+                int4 e_nxt[IPG] = {};
+                float a_nxt[WMT][2], b_nxt[WNT][2];
+                if (gq + 1 < NG) read_entries(c + 2, gq + 1, e_nxt);
+#pragma unroll
+                for (int u = 0; u < IPG; ++u) {
+                    const int it = gq * IPG + u;
+                    if (it < NA) {
+                        stage_a(it);
+                        fetch_a(it);
+                    } else if (it < NITEMS) {
+                        stage_b(it - NA);
+                        fetch_b(it - NA, e_cur[u]);
+                    }
+                }
+                if (gq + 1 < NG) {
+                    read_group(gq + 1, a_nxt, b_nxt);
+                } else {
+                    __syncthreads();
+                    // swap the roles of the two buffers; the next chunk's table has just become visible
+                    ap += wr_off; bp += wr_off;
+                    a_dst -= wr_off; b_dst -= wr_off;
+                    asm volatile("" : "+v"(ap)); asm volatile("" : "+v"(bp));
+                    asm volatile("" : "+v"(a_dst)); asm volatile("" : "+v"(b_dst));
+                    wr_off = -wr_off;
+                    read_group(0, a_nxt, b_nxt);
+                    begin_chunk(c + 3);
+                    read_entries(c + 3, 0, e_nxt);
+                }
+#pragma unroll
+                for (int t = 0; t < 2; ++t)
+#pragma unroll
+                    for (int i = 0; i < WMT; ++i)
+#pragma unroll
+                        for (int j = 0; j < WNT; ++j)
+                            acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x2f32(a_cur[i][t], b_cur[j][t], acc[i][j], 0, 0, 0);
+#pragma unroll
+                for (int k = 0; k < 2 * WMT * WNT; ++k) {
+                    __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);   // 1 MFMA
+                    __builtin_amdgcn_sched_group_barrier(0x100, 1, 0);   // 1 DS read
+                }
+                __builtin_amdgcn_sched_barrier(0);
+#pragma unroll
+                for (int t = 0; t < 2; ++t) {
+#pragma unroll
+                    for (int i = 0; i < WMT; ++i) a_cur[i][t] = a_nxt[i][t];
+#pragma unroll
+                    for (int j = 0; j < WNT; ++j) b_cur[j][t] = b_nxt[j][t];
+                }
+#pragma unroll
+                for (int u = 0; u < IPG; ++u) e_cur[u] = e_nxt[u];
+            }
         }
     }
 
@@ -294,6 +396,39 @@ k_conv_igemm(IgArgs g, const float* __restrict__ Asrc, const float* __restrict__
             const int i = hw / ph.Wn;
             rs_out = g.H * g.W;
             col = img * g.M * rs_out + (ph.h0 + g.st * i) * g.W + ph.w0 + g.st * (hw - i * ph.Wn);
+        }
+        if (MODE != WGR && !WIDE) {
+            // Forward and backpropagation below 2 GiB: buffer stores (and mask loads) whose per-lane offset is fixed for
+            // the column and whose row goes into the scalar offset; a column or row outside the tensor gets an offset
+            // beyond the descriptor, which the hardware drops.
+            const __amdgpu_buffer_rsrc_t rs_o = __builtin_amdgcn_make_buffer_rsrc(sink.dw, 0, (int)g.o_bytes, kRsrcWord3);
+            const __amdgpu_buffer_rsrc_t rs_m = __builtin_amdgcn_make_buffer_rsrc(const_cast<float*>(act ? act : sink.dw), 0,
+                                                                                 (int)g.o_bytes, kRsrcWord3);
+            const int mlane = m0 + wm * WMT * 32 + 4 * half;
+            const int vo = nok ? (col + mlane * rs_out) * 4 : kOutOfRange;
+            const bool full = m0 + TM <= g.M;                // every row of the tile exists (uniform)
+#pragma unroll
+            for (int i = 0; i < WMT; ++i) {
+                float mask[16];
+                if (MODE == BWD && act) {
+#pragma unroll
+                    for (int v = 0; v < 16; ++v) {
+                        const int mr = i * 32 + 8 * (v / 4) + (v % 4);
+                        const int vv = full || mlane + mr < g.M ? vo : kOutOfRange;
+                        mask[v] = __builtin_bit_cast(float, __builtin_amdgcn_raw_buffer_load_b32(rs_m, vv, mr * rs_out * 4, 0));
+                    }
+                }
+#pragma unroll
+                for (int v = 0; v < 16; ++v) {
+                    const int mr = i * 32 + 8 * (v / 4) + (v % 4);
+                    const int vv = full || mlane + mr < g.M ? vo : kOutOfRange;
+                    float r = acc[i][j][v];
+                    if (MODE == FWD && g.relu) r = fmaxf(r, 0.f);
+                    if (MODE == BWD && act) r = mask[v] > 0.f ? r : 0.f;
+                    __builtin_amdgcn_raw_buffer_store_b32(__builtin_bit_cast(unsigned, r), rs_o, vv, mr * rs_out * 4, 0);
+                }
+            }
+            continue;
         }
 #pragma unroll
         for (int i = 0; i < WMT; ++i) {
@@ -363,7 +498,7 @@ IgPlan plan(int mode, const ConvShape& s) {
     const size_t tiles = ((M + p.tm - 1) / p.tm) * ((Nn + 127) / 128);
     if ((Nn + 127) / 128 > 0x7fffffffu / 2) return p;
     int want = 1;
-    if (mode == WGR && tiles < 256) want = (int)((512 + tiles - 1) / tiles);
+    if (mode == WGR && tiles < 256) want = (int)(512 / tiles);    // one resident round of workgroups (two per compute unit)
     const int chunks = (int)((Kd + KC - 1) / KC);
     int max_split = chunks / 4;
     if (max_split < 1) max_split = 1;
@@ -376,9 +511,9 @@ IgPlan plan(int mode, const ConvShape& s) {
     return p;
 }
 
-template <int MODE, int WMT>
-int launch(cnn_ctx* ctx, const IgPlan& p, const ConvShape& s, const float* A, const float* B, const float* act,
-           const GradSink& sink) {
+template <int MODE, int WMT, bool WIDE>
+int launch_as(cnn_ctx* ctx, const IgPlan& p, const ConvShape& s, const float* A, const float* B, const float* act,
+              const GradSink& sink) {
     constexpr int TM = 64 * WMT, TN = 128;
     const IgArgs& a = p.a;
     const GradSink first = p.nsplit > 1 ? sink_dw(reinterpret_cast<float*>(ctx->ws)) : sink;
@@ -387,20 +522,21 @@ int launch(cnn_ctx* ctx, const IgPlan& p, const ConvShape& s, const float* A, co
     const size_t cols = MODE == BWD ? (size_t)s.N * hn * wn : (size_t)a.Nn;
     dim3 grid((unsigned)((cols + TN - 1) / TN), (unsigned)((a.M + TM - 1) / TM),
               (unsigned)(MODE == BWD ? s.stride * s.stride : p.nsplit));
-    constexpr int lds_bytes = (2 * (TM * (KC + 1) + (MODE != WGR ? KC * TN : TN * (KC + 1))) + 4 * (MODE != WGR ? 2 * KC : TN)) *
+    constexpr int lds_bytes = (2 * (TM * (KC + 1) + (MODE != WGR ? KC * TN : TN * (KC + 1))) + 4 * (2 * KC + (MODE == WGR ? TN : 0))) *
                               (int)sizeof(float);
     static std::atomic<bool> attr_done{false};
     if (!attr_done && lds_bytes > 48 * 1024) {
-        hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(&k_conv_igemm<MODE, WMT, 2>),
+        hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(&k_conv_igemm<MODE, WMT, 2, WIDE>),
                                            hipFuncAttributeMaxDynamicSharedMemorySize, lds_bytes);
         if (e != hipSuccess) return cnn::hip_check(ctx, e, "hipFuncSetAttribute(conv_igemm)");
         attr_done = true;
     }
-    static const std::string name_s = strf("k_conv_igemm<%s %dx%d>", MODE == FWD ? "fwd" : MODE == BWD ? "bwd" : "wgrad", TM, TN);
+    static const std::string name_s = strf("k_conv_igemm<%s %dx%d%s>", MODE == FWD ? "fwd" : MODE == BWD ? "bwd" : "wgrad", TM, TN,
+                                           WIDE ? " wide" : "");
     const char* const name = name_s.c_str();
     {
         cnn::ProfScope ps(ctx, name, cnn::conv_flops(s));
-        hipLaunchKernelGGL((k_conv_igemm<MODE, WMT, 2>), grid, dim3(256), lds_bytes, ctx->stream, a, A, B, act, first);
+        hipLaunchKernelGGL((k_conv_igemm<MODE, WMT, 2, WIDE>), grid, dim3(256), lds_bytes, ctx->stream, a, A, B, act, first);
     }
     int st = cnn::launch_check(ctx, "conv_igemm");
     if (st != CNN_OK || p.nsplit == 1) return st;
@@ -412,6 +548,22 @@ int launch(cnn_ctx* ctx, const IgPlan& p, const ConvShape& s, const float* A, co
         hipLaunchKernelGGL(k_igemm_reduce, dim3((unsigned)gsz), dim3(256), 0, ctx->stream, p.nsplit, MN, first.dw, sink);
     }
     return cnn::launch_check(ctx, "igemm_reduce");
+}
+
+// A = the first operand's tensor (weights, or dy for the weight gradient), B = the gathered one
+template <int MODE, int WMT>
+int launch(cnn_ctx* ctx, IgPlan& p, const ConvShape& s, const float* A, const float* B, const float* act, const GradSink& sink) {
+    const size_t nx = (size_t)s.N * s.C * s.H * s.W, ny = (size_t)s.N * s.K * s.P * s.Q, nw = (size_t)s.K * s.C * s.R * s.S;
+    const size_t na = MODE == WGR ? ny : nw, nb = MODE == BWD ? ny : nx, no = MODE == FWD ? ny : MODE == BWD ? nx : 0;
+    const size_t two_gib = (size_t)1 << 31;
+    if (na * sizeof(float) < two_gib && nb * sizeof(float) < two_gib && no * sizeof(float) < two_gib) {
+        p.a.a_bytes = (unsigned)(na * sizeof(float));
+        p.a.b_bytes = (unsigned)(nb * sizeof(float));
+        p.a.o_bytes = (unsigned)(no * sizeof(float));
+        return launch_as<MODE, WMT, false>(ctx, p, s, A, B, act, sink);
+    }
+    p.a.a_bytes = p.a.b_bytes = p.a.o_bytes = 0;
+    return launch_as<MODE, WMT, true>(ctx, p, s, A, B, act, sink);
 }
 
 }  // namespace
@@ -427,7 +579,7 @@ int igemm_conv_fwd(cnn_ctx* ctx, const ConvShape& s, const float* x, const float
 }
 
 int igemm_conv_bwd_data(cnn_ctx* ctx, const ConvShape& s, const float* dy, const float* w, float* dx, const float* act) {
-    const IgPlan p = plan(BWD, s);
+    IgPlan p = plan(BWD, s);
     if (!p.ok) return CNN_EUNSUPPORTED;
     if (p.tm == 64) return launch<BWD, 1>(ctx, p, s, w, dy, act, sink_dw(dx));
     return launch<BWD, 2>(ctx, p, s, w, dy, act, sink_dw(dx));
@@ -439,7 +591,7 @@ size_t igemm_conv_bwd_weight_ws(const ConvShape& s) {
 }
 
 int igemm_conv_bwd_weight(cnn_ctx* ctx, const ConvShape& s, const float* x, const float* dy, const GradSink& sink) {
-    const IgPlan p = plan(WGR, s);
+    IgPlan p = plan(WGR, s);
     if (!p.ok) return CNN_EUNSUPPORTED;
     if (p.ws_bytes && (!ctx->ws || ctx->ws_bytes < p.ws_bytes)) return CNN_EWORKSPACE;
     if (p.tm == 64) return launch<WGR, 1>(ctx, p, s, dy, x, nullptr, sink);
