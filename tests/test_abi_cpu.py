@@ -182,3 +182,20 @@ def test_tile_report_and_block_search_validation(L):
         assert L.cnn_workspace_bytes(6, 0, 0, 0, 0, 0, 0, 0, 0, 0) > 0
     finally:
         assert L.cnn_destroy(h) == 0
+
+
+def test_parameter_arrays_are_cut_from_one_block():
+    # weights, gradients and momentum of a network are ranges of one allocation: disjoint, in order, each start
+    # 16-byte aligned (the update reads them as float4) and shifted against its neighbours
+    import torch
+    from paper_1602_06709_amd.net import carve_arrays
+    for n in (4, 1000, 4096, 132851392 // 64):
+        arrs = carve_arrays(n, 3, "cpu")
+        assert [a.numel() for a in arrs] == [n] * 3 and all(a.dtype == torch.float32 for a in arrs)
+        ptr = [a.data_ptr() for a in arrs]
+        assert all(p % 16 == 0 for p in ptr)
+        assert ptr[0] + 4 * n <= ptr[1] and ptr[1] + 4 * n <= ptr[2]
+        assert (ptr[1] - ptr[0]) != (ptr[2] - ptr[1])
+        base = arrs[0].untyped_storage().data_ptr()
+        assert all(a.untyped_storage().data_ptr() == base for a in arrs)
+        assert all(float(a.abs().sum()) == 0.0 for a in arrs)
