@@ -15,6 +15,18 @@ int hip_check(cnn_ctx* ctx, hipError_t e, const char* what) {
 }
 int launch_check(cnn_ctx* ctx, const char* what) { return hip_check(ctx, hipGetLastError(), what); }
 
+int lds_attr_once(cnn_ctx* ctx, std::atomic<unsigned long long>& done, const void* fn, int bytes, const char* what) {
+    int dev = 0;
+    hipError_t e = hipGetDevice(&dev);
+    if (e != hipSuccess) return hip_check(ctx, e, "hipGetDevice");
+    const unsigned long long bit = 1ull << (dev & 63);
+    if (done.load(std::memory_order_acquire) & bit) return CNN_OK;
+    e = hipFuncSetAttribute(fn, hipFuncAttributeMaxDynamicSharedMemorySize, bytes);
+    if (e != hipSuccess) return hip_check(ctx, e, what);
+    done.fetch_or(bit, std::memory_order_release);
+    return CNN_OK;
+}
+
 ProfScope::ProfScope(cnn_ctx* c, const char* name, double flops) : ctx(c), ent(nullptr) {
     if (!c || !c->profile || c->prof_used >= 16384) return;
     if (c->prof_used == c->prof.size()) {

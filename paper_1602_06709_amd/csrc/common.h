@@ -123,6 +123,10 @@ inline double conv_flops(const ConvShape& s) {   // Section 3.1: 2 * MB * ifm * 
 }
 
 int hip_check(cnn_ctx* ctx, hipError_t e, const char* what);   // records text, returns CNN_OK / CNN_EHIP
+// A kernel's limit on dynamic LDS is an attribute of the (kernel, device) pair: sets it to `bytes` the first time the
+// kernel is launched on the current device (`done`: one bit per device, one object per kernel).
+int lds_attr_once(cnn_ctx* ctx, std::atomic<unsigned long long>& done, const void* fn, int bytes, const char* what);
+constexpr int kMaxLdsBytes = 160 * 1024;      // LDS of a gfx950 compute unit
 int launch_check(cnn_ctx* ctx, const char* what);              // hipGetLastError after a launch
 
 // ---- plain one-thread-per-output kernels: any shape, slow; the fallback of every contraction

@@ -205,12 +205,10 @@ bool c3_pool_serves(const ConvShape& s) {
 
 int c3_pool_conv_fwd(cnn_ctx* ctx, const ConvShape& s, const float* x, const float* w, float* a, unsigned char* arg) {
     if (!c3_pool_serves(s)) return CNN_EUNSUPPORTED;
-    static std::atomic<bool> attr_done{false};
-    if (!attr_done) {
-        hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(&k_conv_c3_pool),
-                                           hipFuncAttributeMaxDynamicSharedMemorySize, kLdsBytes);
-        if (e != hipSuccess) return hip_check(ctx, e, "hipFuncSetAttribute(conv_c3_pool)");
-        attr_done = true;
+    static std::atomic<unsigned long long> attr_done{0};     // one bit per device: the attribute is the device's
+    {
+        const int st_attr = cnn::lds_attr_once(ctx, attr_done, reinterpret_cast<const void*>(&k_conv_c3_pool), kLdsBytes, "hipFuncSetAttribute(conv_c3_pool)");
+        if (st_attr != CNN_OK) return st_attr;
     }
     const int bands = (s.H + kBR - 1) / kBR;
     {

@@ -524,12 +524,10 @@ int launch_as(cnn_ctx* ctx, const IgPlan& p, const ConvShape& s, const float* A,
               (unsigned)(MODE == BWD ? s.stride * s.stride : p.nsplit));
     constexpr int lds_bytes = (2 * (TM * (KC + 1) + (MODE != WGR ? KC * TN : TN * (KC + 1))) + 4 * (2 * KC + (MODE == WGR ? TN : 0))) *
                               (int)sizeof(float);
-    static std::atomic<bool> attr_done{false};
-    if (!attr_done && lds_bytes > 48 * 1024) {
-        hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(&k_conv_igemm<MODE, WMT, 2, WIDE>),
-                                           hipFuncAttributeMaxDynamicSharedMemorySize, lds_bytes);
-        if (e != hipSuccess) return cnn::hip_check(ctx, e, "hipFuncSetAttribute(conv_igemm)");
-        attr_done = true;
+    static std::atomic<unsigned long long> attr_done{0};     // one bit per device: the attribute is the device's
+    if (lds_bytes > 48 * 1024) {
+        const int st_attr = cnn::lds_attr_once(ctx, attr_done, reinterpret_cast<const void*>(&k_conv_igemm<MODE, WMT, 2, WIDE>), lds_bytes, "hipFuncSetAttribute(conv_igemm)");
+        if (st_attr != CNN_OK) return st_attr;
     }
     static const std::string name_s = strf("k_conv_igemm<%s %dx%d%s>", MODE == FWD ? "fwd" : MODE == BWD ? "bwd" : "wgrad", TM, TN,
                                            WIDE ? " wide" : "");

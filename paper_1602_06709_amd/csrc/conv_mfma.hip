@@ -722,15 +722,16 @@ typedef int (*LaunchFn)(cnn_ctx*, const LaunchArgs&);
 template <class G>
 int launch(cnn_ctx* ctx, const LaunchArgs& a) {
     constexpr bool kHasSK = G::R == 3 && G::VEC == 4 && G::WM == 4;      // instantiations the planner may run this way
-    static std::atomic<size_t> attr_bytes{48 * 1024};
-    if (a.lds_bytes > attr_bytes) {
-        hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(&k_conv_tiled<G, false>),
-                                           hipFuncAttributeMaxDynamicSharedMemorySize, (int)a.lds_bytes);
-        if (e == hipSuccess && kHasSK)
-            e = hipFuncSetAttribute(reinterpret_cast<const void*>(&k_conv_tiled<G, kHasSK>),
-                                    hipFuncAttributeMaxDynamicSharedMemorySize, (int)a.lds_bytes);
-        if (e != hipSuccess) return cnn::hip_check(ctx, e, "hipFuncSetAttribute(conv_tiled)");
-        attr_bytes = a.lds_bytes;
+    // the plans differ in their LDS need: the limit is raised to the whole LDS once per device
+    static std::atomic<unsigned long long> attr_done{0}, attr_done_sk{0};
+    if (a.lds_bytes > (size_t)cnn::kMaxLdsBytes) return CNN_EUNSUPPORTED;
+    {
+        int st_attr = cnn::lds_attr_once(ctx, attr_done, reinterpret_cast<const void*>(&k_conv_tiled<G, false>), cnn::kMaxLdsBytes,
+                                         "hipFuncSetAttribute(conv_tiled)");
+        if (st_attr == CNN_OK && kHasSK)
+            st_attr = cnn::lds_attr_once(ctx, attr_done_sk, reinterpret_cast<const void*>(&k_conv_tiled<G, kHasSK>), cnn::kMaxLdsBytes,
+                                         "hipFuncSetAttribute(conv_tiled runs)");
+        if (st_attr != CNN_OK) return st_attr;
     }
     dim3 grid((unsigned)(a.g.flat ? a.g.ptiles * a.g.mtiles * a.g.nsl : 8 * (a.g.full_per_xcd + a.g.tail_per_xcd * a.g.nsl)));
     if (a.g.sk_share) {

@@ -195,12 +195,10 @@ int c3_strided_conv_fwd(cnn_ctx* ctx, const ConvShape& s, const float* x, const 
     if (s.C != 3 || s.R != G::R || s.S != G::S || s.stride != G::ST || s.pad != 0 || s.W != G::WI || s.H != s.W ||
         s.K > G::KROWS)
         return CNN_EUNSUPPORTED;
-    static std::atomic<bool> attr_done{false};
-    if (!attr_done) {
-        hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(&k_conv_c3_strided<G>),
-                                           hipFuncAttributeMaxDynamicSharedMemorySize, G::LDS_BYTES);
-        if (e != hipSuccess) return hip_check(ctx, e, "hipFuncSetAttribute(conv_c3_strided)");
-        attr_done = true;
+    static std::atomic<unsigned long long> attr_done{0};     // one bit per device: the attribute is the device's
+    {
+        const int st_attr = cnn::lds_attr_once(ctx, attr_done, reinterpret_cast<const void*>(&k_conv_c3_strided<G>), G::LDS_BYTES, "hipFuncSetAttribute(conv_c3_strided)");
+        if (st_attr != CNN_OK) return st_attr;
     }
     const int row_tiles = (s.P + G::TH - 1) / G::TH;
     {

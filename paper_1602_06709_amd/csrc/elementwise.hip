@@ -296,15 +296,13 @@ int cnn_sgd_update(cnn_ctx* ctx, size_t n, float* w, const float* dw, float* v, 
     const size_t groups = (n4 + kSgdBlock - 1) / kSgdBlock;
     if (groups > 0x7fffffffu) return CNN_EUNSUPPORTED;
     const unsigned grid = groups ? (unsigned)groups : 1u;     // fewer than four elements: the scalar tail alone
-    static std::atomic<bool> attr_done{false};
-    if (!attr_done) {
-        hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(&k_sgd<true>),
-                                           hipFuncAttributeMaxDynamicSharedMemorySize, kSgdLds);
-        if (e == hipSuccess)
-            e = hipFuncSetAttribute(reinterpret_cast<const void*>(&k_sgd<false>),
-                                    hipFuncAttributeMaxDynamicSharedMemorySize, kSgdLdsPlain);
-        if (e != hipSuccess) return cnn::hip_check(ctx, e, "hipFuncSetAttribute(sgd)");
-        attr_done = true;
+    static std::atomic<unsigned long long> attr_done{0}, attr_done_plain{0};      // one bit per device each
+    {
+        int st_attr = cnn::lds_attr_once(ctx, attr_done, reinterpret_cast<const void*>(&k_sgd<true>), kSgdLds, "hipFuncSetAttribute(sgd)");
+        if (st_attr == CNN_OK)
+            st_attr = cnn::lds_attr_once(ctx, attr_done_plain, reinterpret_cast<const void*>(&k_sgd<false>), kSgdLdsPlain,
+                                         "hipFuncSetAttribute(sgd plain)");
+        if (st_attr != CNN_OK) return st_attr;
     }
     cnn::ProfScope ps(ctx, v ? "k_sgd<momentum>" : "k_sgd<plain>", 0.0);
     if (v)

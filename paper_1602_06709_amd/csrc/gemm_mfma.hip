@@ -535,12 +535,10 @@ template <class G>
 int launch(cnn_ctx* ctx, const GemmPlan& p, int M, int Nn, int Kd, const float* A, const float* B, const GradSink& sink) {
     const GradSink first = p.nsplit > 1 ? sink_dw(reinterpret_cast<float*>(ctx->ws)) : sink;
     constexpr int lds_bytes = 2 * G::BUF * (int)sizeof(float);
-    static std::atomic<bool> attr_done{false};
-    if (!attr_done && lds_bytes > 48 * 1024) {
-        hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(&k_gemm<G>),
-                                           hipFuncAttributeMaxDynamicSharedMemorySize, lds_bytes);
-        if (e != hipSuccess) return cnn::hip_check(ctx, e, "hipFuncSetAttribute(gemm)");
-        attr_done = true;
+    static std::atomic<unsigned long long> attr_done{0};     // one bit per device: the attribute is the device's
+    if (lds_bytes > 48 * 1024) {
+        const int st_attr = cnn::lds_attr_once(ctx, attr_done, reinterpret_cast<const void*>(&k_gemm<G>), lds_bytes, "hipFuncSetAttribute(gemm)");
+        if (st_attr != CNN_OK) return st_attr;
     }
     const int tiles_n = (Nn + G::TN - 1) / G::TN, tiles_m = (M + G::TM - 1) / G::TM;
     dim3 grid((unsigned)tiles_n, (unsigned)tiles_m, (unsigned)p.nsplit);

@@ -77,12 +77,10 @@ template <int MODE>
 int launch_stream(cnn_ctx* ctx, const char* name, size_t n4, const float* src, float* dst) {
     const size_t groups = (n4 + (size_t)kStreamBlock * StreamCfg<MODE>::U - 1) / ((size_t)kStreamBlock * StreamCfg<MODE>::U);
     if (groups > 0x7fffffffu) return CNN_EUNSUPPORTED;
-    static std::atomic<bool> attr_done{false};
-    if (!attr_done) {
-        const hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(&k_probe_stream<MODE>),
-                                                 hipFuncAttributeMaxDynamicSharedMemorySize, StreamCfg<MODE>::LDS);
-        if (e != hipSuccess) return cnn::hip_check(ctx, e, "hipFuncSetAttribute(probe_stream)");
-        attr_done = true;
+    static std::atomic<unsigned long long> attr_done{0};     // one bit per device: the attribute is the device's
+    {
+        const int st_attr = cnn::lds_attr_once(ctx, attr_done, reinterpret_cast<const void*>(&k_probe_stream<MODE>), StreamCfg<MODE>::LDS, "hipFuncSetAttribute(probe_stream)");
+        if (st_attr != CNN_OK) return st_attr;
     }
     {
         cnn::ProfScope ps(ctx, name, 0.0);

@@ -464,12 +464,12 @@ bool make_plan(const ConvShape& s, Plan* p) {
 template <class G>
 int launch(cnn_ctx* ctx, const Plan& p, const ConvShape& s, const float* x, const float* dy, const GradSink& sink) {
     if (ctx->ws_bytes < p.ws_bytes || !ctx->ws) return CNN_EWORKSPACE;
-    static std::atomic<size_t> attr_bytes{48 * 1024};
-    if (p.lds_bytes > attr_bytes) {
-        hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(&k_wgrad<G>),
-                                           hipFuncAttributeMaxDynamicSharedMemorySize, (int)p.lds_bytes);
-        if (e != hipSuccess) return cnn::hip_check(ctx, e, "hipFuncSetAttribute(wgrad)");
-        attr_bytes = p.lds_bytes;
+    static std::atomic<unsigned long long> attr_done{0};      // one bit per device: the attribute is the device's
+    if (p.lds_bytes > (size_t)cnn::kMaxLdsBytes) return CNN_EUNSUPPORTED;
+    {
+        const int st_attr = cnn::lds_attr_once(ctx, attr_done, reinterpret_cast<const void*>(&k_wgrad<G>), cnn::kMaxLdsBytes,
+                                               "hipFuncSetAttribute(wgrad)");
+        if (st_attr != CNN_OK) return st_attr;
     }
     float* partial = reinterpret_cast<float*>(ctx->ws);
     dim3 grid((unsigned)(p.nsplit * p.g.col_tiles), (unsigned)p.ctiles, (unsigned)p.ktiles);

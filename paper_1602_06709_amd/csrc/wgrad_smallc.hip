@@ -354,12 +354,10 @@ template <int KBK, int JB, int JW, int PW, int CC, int ST, int NPASS, bool POOL 
 int launch(cnn_ctx* ctx, const SmallcPlan& p, const ConvShape& s, const float* x, const float* dy, const GradSink& sink,
            const unsigned char* parg = nullptr) {
     auto kern = &k_wgrad_smallc<KBK, JB, JW, PW, CC, ST, NPASS, POOL>;
-    static std::atomic<bool> attr_done{false};
-    if (!attr_done) {
-        hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(kern), hipFuncAttributeMaxDynamicSharedMemorySize,
-                                           150 * 1024);
-        if (e != hipSuccess) return cnn::hip_check(ctx, e, "hipFuncSetAttribute(wgrad_smallc)");
-        attr_done = true;
+    static std::atomic<unsigned long long> attr_done{0};     // one bit per device: the attribute is the device's
+    {
+        const int st_attr = cnn::lds_attr_once(ctx, attr_done, reinterpret_cast<const void*>(kern), 150 * 1024, "hipFuncSetAttribute(wgrad_smallc)");
+        if (st_attr != CNN_OK) return st_attr;
     }
     float* partial = reinterpret_cast<float*>(ctx->ws);
     static const std::string name_s = strf("k_wgrad_smallc<KB%d JB%d JW%d PW%d ST%d%s>", KBK, JB, JW, PW, ST, POOL ? " unpool" : "");
