@@ -140,16 +140,21 @@ __device__ __forceinline__ int a_k_part(const IgArgs& g, const Phase& ph, int kk
 // One table entry per contraction index of a chunk: the gathered operand's part that depends on that index (kernel
 // tap for forward / backpropagation, pixel for the weight gradient) and the first operand's offset along the
 // contraction (-1 past the end of the contraction: such an element is fetched as 0 on both sides).
-template <int MODE>
+// NOCHECK (see the kernel): x is a byte offset, beyond every descriptor past the end of the contraction.
+template <int MODE, bool NOCHECK>
 __device__ __forceinline__ int4 chunk_entry(const IgArgs& g, const Phase& ph, int kk, int k_end) {
     const Part t = MODE == WGR ? pix_part<MODE>(g, ph, kk, k_end) : tap_part<MODE>(g, ph, kk, k_end);
-    return make_int4(t.off, t.a, t.b, kk < k_end ? a_k_part<MODE>(g, ph, kk) : -1);
+    const bool in = kk < k_end;
+    return make_int4(NOCHECK ? (in ? t.off * 4 : kOutOfRange) : t.off, t.a, t.b, in ? a_k_part<MODE>(g, ph, kk) : -1);
 }
 
 // WIDE = false: both operands are below 2 GiB and are fetched by raw buffer loads with 32-bit byte offsets (an
 // element that contributes 0 gets an offset beyond the descriptor and the hardware returns 0); WIDE = true: 64-bit
 // addresses, a clamped offset and a bit per element that decides at the LDS store whether it counts.
-template <int MODE, int WMT, int WNT, bool WIDE>
+// NOCHECK (never with WIDE): every window element of an existing output position exists - forward and weight
+// gradient without padding, backpropagation of 1x1 kernels without padding - so a gathered element's byte offset is
+// one addition of the two parts, with no coordinates to compare (1x1 layers, the commonest shape that comes here).
+template <int MODE, int WMT, int WNT, bool WIDE, bool NOCHECK>
 __global__ void __launch_bounds__(256, 2)
 k_conv_igemm(IgArgs g, const float* __restrict__ Asrc, const float* __restrict__ Bsrc, const float* __restrict__ act,
              GradSink sink) {
@@ -210,15 +215,17 @@ k_conv_igemm(IgArgs g, const float* __restrict__ Asrc, const float* __restrict__
         for (int i = 0; i < NA; ++i) a_ro[i] = min(m0 + rbase + RSTEP * i, g.M - 1) * a_rs * SC;
         Part fix = {};                                      // the thread's fixed part of the second operand
         if (BKM) fix = pix_part<MODE>(g, ph, n0 + bn, Nn);
+        if (BKM && NOCHECK)                                 // as a byte offset; a column past the end reads element 0
+            fix.off = n0 + bn < Nn ? (fix.off + (MODE == BWD ? fix.a * g.Q + fix.b : 0)) * 4 : 0;
 
         auto build_ktab = [&](int c) {
-            if (tid < KC) ktab[(c & 1) * KC + tid] = chunk_entry<MODE>(g, ph, k_begin + c * KC + tid, k_end);
+            if (tid < KC) ktab[(c & 1) * KC + tid] = chunk_entry<MODE, NOCHECK>(g, ph, k_begin + c * KC + tid, k_end);
         };
         build_ktab(0);
         build_ktab(1);
         if (!BKM && tid < TN) {
             const Part t = tap_part<MODE>(g, ph, n0 + tid, Nn);
-            ctab[tid] = make_int4(t.off, t.a, t.b, 0);
+            ctab[tid] = make_int4(NOCHECK ? t.off * 4 : t.off, t.a, t.b, 0);
         }
         __syncthreads();
 
@@ -246,6 +253,10 @@ k_conv_igemm(IgArgs g, const float* __restrict__ Asrc, const float* __restrict__
             }
         };
         auto fetch_b = [&](int j, const int4& e) {
+            if (NOCHECK) {
+                rb[j] = __builtin_bit_cast(float, __builtin_amdgcn_raw_buffer_load_b32(rs_b, (BKM ? fix.off : px.off) + e.x, 0, 0));
+                return;
+            }
             Part t;
             t.off = e.x; t.a = e.y; t.b = e.z;
             const int o = gather_offset<MODE>(g, BKM ? fix : px, t);
@@ -511,7 +522,7 @@ IgPlan plan(int mode, const ConvShape& s) {
     return p;
 }
 
-template <int MODE, int WMT, bool WIDE>
+template <int MODE, int WMT, bool WIDE, bool NOCHECK>
 int launch_as(cnn_ctx* ctx, const IgPlan& p, const ConvShape& s, const float* A, const float* B, const float* act,
               const GradSink& sink) {
     constexpr int TM = 64 * WMT, TN = 128;
@@ -526,15 +537,15 @@ int launch_as(cnn_ctx* ctx, const IgPlan& p, const ConvShape& s, const float* A,
                               (int)sizeof(float);
     static std::atomic<unsigned long long> attr_done{0};     // one bit per device: the attribute is the device's
     if (lds_bytes > 48 * 1024) {
-        const int st_attr = cnn::lds_attr_once(ctx, attr_done, reinterpret_cast<const void*>(&k_conv_igemm<MODE, WMT, 2, WIDE>), lds_bytes, "hipFuncSetAttribute(conv_igemm)");
+        const int st_attr = cnn::lds_attr_once(ctx, attr_done, reinterpret_cast<const void*>(&k_conv_igemm<MODE, WMT, 2, WIDE, NOCHECK>), lds_bytes, "hipFuncSetAttribute(conv_igemm)");
         if (st_attr != CNN_OK) return st_attr;
     }
     static const std::string name_s = strf("k_conv_igemm<%s %dx%d%s>", MODE == FWD ? "fwd" : MODE == BWD ? "bwd" : "wgrad", TM, TN,
-                                           WIDE ? " wide" : "");
+                                           WIDE ? " wide" : NOCHECK ? " unpadded" : "");
     const char* const name = name_s.c_str();
     {
         cnn::ProfScope ps(ctx, name, cnn::conv_flops(s));
-        hipLaunchKernelGGL((k_conv_igemm<MODE, WMT, 2, WIDE>), grid, dim3(256), lds_bytes, ctx->stream, a, A, B, act, first);
+        hipLaunchKernelGGL((k_conv_igemm<MODE, WMT, 2, WIDE, NOCHECK>), grid, dim3(256), lds_bytes, ctx->stream, a, A, B, act, first);
     }
     int st = cnn::launch_check(ctx, "conv_igemm");
     if (st != CNN_OK || p.nsplit == 1) return st;
@@ -558,10 +569,13 @@ int launch(cnn_ctx* ctx, IgPlan& p, const ConvShape& s, const float* A, const fl
         p.a.a_bytes = (unsigned)(na * sizeof(float));
         p.a.b_bytes = (unsigned)(nb * sizeof(float));
         p.a.o_bytes = (unsigned)(no * sizeof(float));
-        return launch_as<MODE, WMT, false>(ctx, p, s, A, B, act, sink);
+        // no coordinate can leave its tensor: see NOCHECK at the kernel
+        if (s.pad == 0 && (MODE != BWD || (s.R == 1 && s.S == 1)))
+            return launch_as<MODE, WMT, false, true>(ctx, p, s, A, B, act, sink);
+        return launch_as<MODE, WMT, false, false>(ctx, p, s, A, B, act, sink);
     }
     p.a.a_bytes = p.a.b_bytes = p.a.o_bytes = 0;
-    return launch_as<MODE, WMT, true>(ctx, p, s, A, B, act, sink);
+    return launch_as<MODE, WMT, true, false>(ctx, p, s, A, B, act, sink);
 }
 
 }  // namespace
