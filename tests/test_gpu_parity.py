@@ -221,7 +221,10 @@ IGEMM_CASES = [(2, 256, 28, 28, 512, 1, 1, 1, 0), (3, 64, 56, 56, 128, 3, 3, 2, 
                (3, 20, 17, 23, 70, 2, 2, 2, 0), (2, 40, 33, 31, 64, 4, 4, 4, 2), (1, 130, 19, 19, 200, 3, 3, 3, 1),
                (2, 128, 28, 28, 256, 5, 5, 2, 2), (1, 5, 6, 6, 3, 2, 3, 1, 1), (65, 8, 9, 9, 16, 3, 2, 2, 1),
                # stride-1 3x3 with a prime width: the ring-buffer weight gradient has no column tile for it
-               (2, 32, 20, 37, 48, 3, 3, 1, 1), (1, 24, 12, 67, 40, 3, 3, 1, 1)]
+               (2, 32, 20, 37, 48, 3, 3, 1, 1), (1, 24, 12, 67, 40, 3, 3, 1, 1),
+               # no padding: gathered without coordinate checks (ragged rows, columns and contraction; strides 1 and 3)
+               (2, 8, 24, 24, 24, 9, 9, 1, 0), (2, 12, 19, 21, 40, 4, 4, 1, 0), (3, 70, 13, 17, 90, 1, 1, 1, 0),
+               (2, 33, 20, 22, 65, 1, 1, 3, 0)]
 
 
 @pytest.mark.parametrize("case", IGEMM_CASES)
