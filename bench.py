@@ -17,7 +17,7 @@ after the timed region (the GPU has just been busy); no read sits between warm-u
 takes milliseconds, during which an idle GPU drops its clocks.
 `roofline` describes the dominant kernel (largest share of the timed region): achieved = algorithmic FLOPs of its
 launches / their summed duration, measured with HIP events that the library records on its own stream around every
-kernel launch, inside the timed region, on every 5th timed step (`--profile-every`, `profiled_steps` in the
+kernel launch, inside the timed region, on every 10th timed step (`--profile-every`, `profiled_steps` in the
 output): the event records cost ~2 % of a step.  `frac` is against the published peak (157.3 TFLOP/s fp32 matrix,
 8 TB/s HBM); `frac_of_sustained` against what this run's own calibration (`calibration`: a register-only MFMA loop
 and plain streams, run after the timed region) reached on this machine.
@@ -140,9 +140,9 @@ def main():
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-profile", action="store_true", help="leave the per-kernel events out of the timed region")
     ap.add_argument("--no-calibration", action="store_true", help="skip the ceilings measured after the timed region")
-    ap.add_argument("--profile-every", type=int, default=5,
+    ap.add_argument("--profile-every", type=int, default=10,
                     help="record the per-kernel HIP events on every P-th step of the timed region (the two event "
-                         "records around each launch cost about 0.5 ms per VGG-A step; default: steps 0, 5, ...)")
+                         "records around each launch cost about 0.5 ms per VGG-A step; default: steps 0, 10, ...)")
     ap.add_argument("--separate-sgd", action="store_true",
                     help="store the weight gradients and update in one pass at the end instead of inside their reductions")
     ap.add_argument("--per-kernel", action="store_true", help="print the per-kernel table to stderr")
