@@ -199,3 +199,13 @@ def test_parameter_arrays_are_cut_from_one_block():
         base = arrs[0].untyped_storage().data_ptr()
         assert all(a.untyped_storage().data_ptr() == base for a in arrs)
         assert all(float(a.abs().sum()) == 0.0 for a in arrs)
+
+
+def test_bench_refuses_more_than_one_gpu():
+    # one GPU per box: the benchmark says so and exits before touching a device
+    import subprocess
+    import sys
+    root = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+    r = subprocess.run([sys.executable, os.path.join(root, "bench.py"), "--gpus", "2"], capture_output=True, text=True, timeout=120)
+    assert r.returncode != 0
+    assert "one GPU" in (r.stderr + r.stdout)
